@@ -1,0 +1,88 @@
+"""Index construction for the oracle side (test infrastructure): k-means codebooks and
+IVF lists.  The paper only says PQ/IVF are trained by k-means with t iterations
+(Section 3.1, cost O(mCn(d/m)t); Section 6.1, C = 256, C' coarse lists); any valid
+codebook is acceptable data for both the oracle scan and the GPU scan, so the numeric
+values produced here are "parity unpinned"; what is pinned is Lloyd's invariant (the
+objective never increases) and determinism.
+
+Random choices (training rows, initial centroids) are inputs, never drawn here.
+Distances inside k-means use a library matmul in float64 (a library primitive as a step).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _assign(x64: np.ndarray, c64: np.ndarray):
+    """Nearest centroid per row (smallest index on ties) and its squared distance."""
+    out_a = np.empty(x64.shape[0], dtype=np.int64)
+    out_d = np.empty(x64.shape[0], dtype=np.float64)
+    cn = (c64 * c64).sum(axis=1)
+    step = max(1, (1 << 24) // max(1, c64.shape[0]))
+    for lo in range(0, x64.shape[0], step):
+        xs = x64[lo:lo + step]
+        dist = (xs * xs).sum(axis=1)[:, None] - 2.0 * (xs @ c64.T) + cn[None, :]
+        a = np.argmin(dist, axis=1)
+        out_a[lo:lo + step] = a
+        out_d[lo:lo + step] = dist[np.arange(xs.shape[0]), a]
+    return out_a, out_d
+
+
+def kmeans(train: np.ndarray, K: int, iters: int, init_rows: np.ndarray):
+    """Lloyd's algorithm.  Returns (centroids float32 [K][dim], objective per iteration).
+
+    Initial centroids are train[init_rows]; an empty cluster keeps its previous
+    centroid; a centroid is the float64 mean of its members rounded to float32.
+    objective[i] is the mean squared distance to the nearest centroid measured at the
+    start of iteration i (before that iteration's update).
+    """
+    assert init_rows.shape[0] == K
+    x64 = train.astype(np.float64)
+    cent = train[init_rows].astype(np.float32)
+    objective = []
+    for _ in range(iters):
+        a, dmin = _assign(x64, cent.astype(np.float64))
+        objective.append(float(dmin.mean()))
+        sums = np.zeros((K, x64.shape[1]), dtype=np.float64)
+        np.add.at(sums, a, x64) if x64.shape[0] < 4096 else _scatter_sum(sums, a, x64)
+        cnt = np.bincount(a, minlength=K)
+        nz = cnt > 0
+        cent[nz] = (sums[nz] / cnt[nz, None]).astype(np.float32)
+    return cent, objective
+
+
+def _scatter_sum(sums, a, x64):
+    order = np.argsort(a, kind="stable")
+    a_s = a[order]
+    starts = np.flatnonzero(np.r_[True, a_s[1:] != a_s[:-1]])
+    sums[a_s[starts]] = np.add.reduceat(x64[order], starts, axis=0)
+
+
+def train_pq(train: np.ndarray, M: int, iters: int, init_rows: np.ndarray) -> np.ndarray:
+    """PQ codebooks [M][256][d/M]: one k-means per subspace (Section 2.2)."""
+    d = train.shape[1]
+    dsub = d // M
+    cb = np.empty((M, 256, dsub), dtype=np.float32)
+    for j in range(M):
+        cb[j], _ = kmeans(np.ascontiguousarray(train[:, j * dsub:(j + 1) * dsub]), 256,
+                          iters, init_rows)
+    return cb
+
+
+def ivf_assign(base: np.ndarray, centroids: np.ndarray):
+    """Coarse assignment of every base vector, then list-contiguous storage order.
+
+    Returns (order, list_offsets): order[p] = original id stored at position p (ascending
+    id inside a list), list_offsets int64 [nlist+1].
+    """
+    nlist = centroids.shape[0]
+    c64 = centroids.astype(np.float64)
+    a = np.empty(base.shape[0], dtype=np.int64)
+    step = 1 << 15
+    for lo in range(0, base.shape[0], step):
+        a[lo:lo + step], _ = _assign(base[lo:lo + step].astype(np.float64), c64)
+    order = np.argsort(a, kind="stable").astype(np.int32)
+    counts = np.bincount(a, minlength=nlist)
+    list_offsets = np.zeros(nlist + 1, dtype=np.int64)
+    np.cumsum(counts, out=list_offsets[1:])
+    return order, list_offsets
