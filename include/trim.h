@@ -1,0 +1,183 @@
+/*
+ * libtrim: the filter-then-refine scan of TRIM (arXiv 2508.17828) for one AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer marked "device" is HIP device memory on the current device, owned
+ * by the caller for the whole call and until the work enqueued on `stream` has finished.
+ * Pointers marked "host" are ordinary host memory read during the call only.  The library
+ * keeps no state between calls, allocates no device memory and never synchronises: all
+ * work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream).
+ *
+ * Every function returns 0 on success or a negative trim_status; nothing is enqueued when
+ * a negative status is returned.  Checks are made on the host from the arguments alone;
+ * device-resident structure (probe ids, list offsets) is clamped inside the kernels so
+ * that no access leaves the arrays described here, whatever those arrays hold.
+ *
+ * Conventions (paper notation in brackets):
+ *   n      base vectors [n], d dimensions [d], M subspaces [m], 256 centroids each [C]
+ *   code   one byte per subspace: the landmark of x is its PQ reconstruction (Section 3.1)
+ *   dlx    Gamma(l,x), the UNSQUARED distance of x to its landmark (Section 3.3 step 1)
+ *   gamma  the relaxation parameter of Equation 3, gamma >= 0; 0 is the strict bound
+ *   all returned distances are SQUARED Euclidean distances (Equation 3 bounds Gamma^2)
+ *   ids    original id of the vector stored at a position; NULL means id = position
+ *   order  results are ordered by (squared distance, id); ties go to the smaller id
+ *
+ * Arithmetic is binary32 with a fixed rounding order, so that survivor sets are
+ * reproducible bit for bit:
+ *   table entry / encode distance : acc = fma(x_t - c_t, x_t - c_t, acc), t ascending
+ *   Gamma(l,q)^2                  : s = T[0][c_0] + T[1][c_1] + ... summed left to right
+ *   bound (Equation 3)            : a = sqrt(s); e = a - b; g = fma((2*gamma)*a, b, e*e)
+ *   exact distance                : 32 partial sums; coordinate group G (4 consecutive
+ *                                   coordinates) is added, in order, to partial G mod 32 by
+ *                                   fma; then p[l] += p[l+h] for h = 16, 8, 4, 2, 1
+ */
+#ifndef TRIM_H
+#define TRIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum trim_status {
+    TRIM_OK = 0,
+    TRIM_INVALID_ARG = -1,       /* null pointer, negative size, gamma < 0 or NaN, ... */
+    TRIM_UNSUPPORTED_SHAPE = -2, /* see trim_shape_supported */
+    TRIM_WORKSPACE = -3,         /* workspace missing or smaller than trim_range_workspace_bytes */
+    TRIM_HIP_ERROR = -4          /* a HIP call failed; see trim_last_hip_error */
+} trim_status;
+
+/* Limits of this build. */
+#define TRIM_MAX_K 1024       /* kNN result size */
+#define TRIM_MAX_BATCH 4096   /* kNN batch size */
+#define TRIM_MAX_NPROBE 4096  /* probed lists per query */
+
+/* The stored index of Section 3.3 (preprocessing): raw vectors, their landmark codes and
+ * landmark distances, and the PQ centroids.  All arrays device, read-only. */
+typedef struct trim_index_view {
+    int64_t n;              /* 0 <= n < 2^31 */
+    int32_t d;              /* d % 4 == 0 */
+    int32_t M;              /* d % M == 0, M % 4 == 0 */
+    const float *base;      /* [n][d] row-major, in scan (storage) order */
+    const uint8_t *codes;   /* [n][M] row-major */
+    const float *dlx;       /* [n] */
+    const int32_t *ids;     /* [n] or NULL */
+    const float *codebooks; /* [M][256][d/M] */
+} trim_index_view;
+
+/* Which stored positions a query scans, and in what order: the lists probes[q][0],
+ * probes[q][1], ... one after the other, positions ascending inside a list
+ * (inverted-file candidates as in the paper's IVFPQ integration, Section 6.1).
+ * A NULL trim_candidates* means every query scans positions 0..n-1. */
+typedef struct trim_candidates {
+    int32_t nlist;
+    int32_t nprobe;              /* 1..TRIM_MAX_NPROBE */
+    const int64_t *list_offsets; /* device [nlist+1], nondecreasing, within [0, n] */
+    const int32_t *probes;       /* device [nq][nprobe]; ids outside [0,nlist) are skipped */
+    int64_t max_candidates;      /* host value: upper bound on one query's candidate count
+                                    (e.g. the sum of the nprobe longest lists); used to size
+                                    masks; a query with more candidates is cut at this bound */
+} trim_candidates;
+
+/* Optional per-query counters (device, each [nq] or NULL): candidates scanned, and
+ * candidates whose exact distance was computed.  Pruning ratio = 1 - n_exact/n_scanned. */
+typedef struct trim_stats {
+    int32_t *n_scanned;
+    int32_t *n_exact;
+} trim_stats;
+
+/* 1 if (d, M) can be searched by this build, else 0.  Needs d % 4 == 0, d % M == 0,
+ * M % 4 == 0, d/M <= 64, and room in the 160 KB of LDS for the kernel's working set. */
+int trim_shape_supported(int32_t d, int32_t M);
+
+/*
+ * Preprocessing step 1 of Section 3.3: codes_out[x][j] = index of the centroid of subspace j
+ * nearest to x's j-th sub-vector (smallest index on ties); dlx_out[x] = Gamma(l,x), the
+ * distance from x to the vector its code represents.
+ * base [n][d] device, codebooks [M][256][d/M] device, codes_out [n][M] device,
+ * dlx_out [n] device.
+ */
+int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
+                uint8_t *codes_out, float *dlx_out, void *stream);
+
+/*
+ * Query processing, operation 1 (Section 3.3; the distance table of Section 2.2):
+ * lut_out[q][j][c] = squared distance from the j-th sub-vector of query q to centroid c of
+ * subspace j.  queries [nq][d] device, lut_out [nq][M][256] device.
+ * mfma = 0: direct differences on the vector ALU in the rounding order above (this is the
+ * table the searches build internally).  mfma = 1: expanded form ||q||^2 - 2 q.c + ||c||^2
+ * with the cross term on the matrix cores (d/M must be 4 or 8); agrees with mfma = 0 only
+ * to rounding, so survivor sets computed from it may differ at exact ties.
+ */
+int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *codebooks,
+                   int32_t M, float *lut_out, int32_t mfma, void *stream);
+
+/*
+ * Approximate kNN by the scan of Section 4.2 (problem statement: Section 2.1).
+ * Per query: the result set R (size k) is first filled with the first k candidates, all with
+ * exact distances; the remaining candidates are taken in batches of `batch`; inside a batch
+ * the threshold tau (k-th squared distance in R; +inf while |R| < k) is frozen; a candidate
+ * survives iff g <= tau (Equation 3); survivors get exact distances and are merged into R.
+ * batch = 1 is the paper's vector-at-a-time rule.
+ *
+ * queries [nq][d] device.  lut: device [nq][M][256] or NULL (tables are then built inside
+ * the kernel from index->codebooks).  cand: host struct or NULL.  1 <= k <= TRIM_MAX_K,
+ * 1 <= batch <= TRIM_MAX_BATCH, gamma >= 0.
+ * out_ids [nq][k], out_d2 [nq][k] device: ascending by (d2, id); rows with fewer than k
+ * candidates are padded with id -1, d2 +inf.
+ * stats: host struct or NULL.  survivor_mask: device or NULL; if given it must hold
+ * nq * mask_words 32-bit words, mask_words >= ceil(max candidates per query / 32); the call
+ * overwrites it: bit (i % 32) of word [q][i / 32] is 1 iff the candidate with scan-order
+ * number i had its exact distance computed.
+ */
+int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
+                    const float *lut, const trim_candidates *cand, int32_t k, float gamma,
+                    int32_t batch, int32_t *out_ids, float *out_d2, const trim_stats *stats,
+                    uint32_t *survivor_mask, int64_t mask_words, void *stream);
+
+/*
+ * Approximate range search by the scan of Section 4.2 (problem statement: Section 2.1):
+ * tau = radius^2 (squared once in binary32) for every candidate; a candidate survives iff
+ * g <= tau; a survivor is a result iff its exact squared distance <= tau.
+ *
+ * Results are written in CSR form in scan order: out_offsets [nq+1] device (always
+ * complete), out_ids / out_d2 [capacity] device.  *required (device int64) receives the
+ * total number of results; if it exceeds `capacity`, only the entries whose global index
+ * is below `capacity` are written (the caller checks *required after synchronising and
+ * calls again with a larger buffer).
+ * workspace: device, at least trim_range_workspace_bytes(...) bytes, 256-byte aligned;
+ * contents on entry are ignored.  survivor_mask as in trim_search_knn.
+ */
+int trim_search_range(const trim_index_view *index, const float *queries, int64_t nq,
+                      const float *lut, const trim_candidates *cand, float radius, float gamma,
+                      int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                      int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
+                      int64_t mask_words, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/* Bytes of workspace trim_search_range needs for nq queries with at most max_candidates
+ * candidates each (index->n when there is no candidate structure). */
+size_t trim_range_workspace_bytes(int64_t nq, int64_t max_candidates);
+
+/*
+ * Candidate generation for inverted-file search (Section 6.1: IVFPQ with C' coarse lists and
+ * nprobe probed lists): probes_out[q][p] = id of the p-th nearest coarse centroid to query q
+ * by exact squared distance (rounding order above), nearest first, ties to the smaller id.
+ * queries [nq][d], centroids [nlist][d], probes_out [nq][nprobe] device; nprobe <= nlist,
+ * nprobe <= TRIM_MAX_NPROBE.
+ */
+int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *centroids,
+                   int32_t nlist, int32_t nprobe, int32_t *probes_out, void *stream);
+
+/* Text for a trim_status. */
+const char *trim_strerror(int status);
+/* The hipError_t (as int) behind the calling thread's most recent TRIM_HIP_ERROR, else 0. */
+int trim_last_hip_error(void);
+/* Library version, "major.minor". */
+const char *trim_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRIM_H */

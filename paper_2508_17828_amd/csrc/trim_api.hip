@@ -1,0 +1,415 @@
+// C ABI of libtrim (see include/trim.h): argument checks, LDS carve-up, launches.
+// No device allocation, no synchronisation, no state between calls.
+#include "../../include/trim.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <mutex>
+
+#include "trim_aux.h"
+#include "trim_search.h"
+
+namespace {
+
+using namespace trim;
+
+thread_local int g_last_hip_error = 0;
+
+constexpr size_t kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return TRIM_HIP_ERROR;
+}
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t _e = (expr);                         \
+        if (_e != hipSuccess) return hip_fail(_e);      \
+    } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t up16(size_t x) { return (x + 15u) & ~size_t(15); }
+
+struct Plan {
+    int threads;
+    int P, Mp, vec;
+    size_t lds;
+    uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+};
+
+// Decide table phases, block size and LDS layout for a search launch.
+// cap = survivor-list capacity (max(batch,k) for kNN, round size for range).
+bool make_plan(int d, int M, int nseg, int cap, int k, bool range, Plan *pl) {
+    if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
+    const int nsegs = nseg > 0 ? nseg : 1;
+    size_t fixed = up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) + up16((size_t)nsegs * 4) +
+                   up16((size_t)cap * 4) * (range ? 3 : 2) + up16((size_t)k * 4) * 2 + up16(sizeof(Ctl));
+    for (int P = 1; P <= M / 4; ++P) {
+        if (M % P) continue;
+        const int Mp = M / P;
+        if (Mp % 4) continue;
+        const size_t tab = (size_t)Mp * kC * 4;
+        if (tab + fixed > kLdsBytes) continue;
+        pl->P = P;
+        pl->Mp = Mp;
+        pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
+        size_t off = tab;
+        pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
+        pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
+        pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
+        pl->off_spos = (uint32_t)off; off += up16((size_t)cap * 4);
+        pl->off_sd2 = (uint32_t)off;  off += up16((size_t)cap * 4);
+        pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
+        pl->off_rd2 = (uint32_t)off;  off += up16((size_t)k * 4);
+        pl->off_rid = (uint32_t)off;  off += up16((size_t)k * 4);
+        pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
+        pl->lds = off;
+        // block size: enough waves per CU whatever the LDS footprint allows
+        const size_t per_cu = kLdsBytes / off;  // workgroups per CU by LDS
+        pl->threads = per_cu >= 4 ? 256 : per_cu >= 2 ? 512 : 1024;
+        return true;
+    }
+    return false;
+}
+
+template <int MODE>
+int launch_search(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
+    void (*fn)(const SearchArgs) = nullptr;
+    switch (pl.vec) {
+        case 4: fn = search_kernel<MODE, 4>; break;
+        case 2: fn = search_kernel<MODE, 2>; break;
+        default: fn = search_kernel<MODE, 1>; break;
+    }
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds));
+    hipLaunchKernelGGL(fn, grid, dim3(pl.threads), pl.lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int check_index(const trim_index_view *ix) {
+    if (!ix) return TRIM_INVALID_ARG;
+    if (ix->n < 0 || ix->n >= (int64_t(1) << 31)) return TRIM_INVALID_ARG;
+    if (ix->d <= 0 || ix->M <= 0) return TRIM_INVALID_ARG;
+    if (!trim_shape_supported(ix->d, ix->M)) return TRIM_UNSUPPORTED_SHAPE;
+    if (ix->n > 0 && (!ix->base || !ix->codes || !ix->dlx)) return TRIM_INVALID_ARG;
+    if (!aligned16(ix->base) || !aligned16(ix->codes) || !aligned16(ix->codebooks))
+        return TRIM_INVALID_ARG;
+    return TRIM_OK;
+}
+
+int check_cand(const trim_candidates *c) {
+    if (!c) return TRIM_OK;
+    if (c->nlist <= 0 || c->nprobe <= 0 || c->nprobe > TRIM_MAX_NPROBE) return TRIM_INVALID_ARG;
+    if (!c->list_offsets || !c->probes) return TRIM_INVALID_ARG;
+    return TRIM_OK;
+}
+
+void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries, const float *lut,
+                 const trim_candidates *cand, float gamma, const trim_stats *stats,
+                 uint32_t *mask, int64_t mask_words, const Plan &pl) {
+    a.base = ix->base; a.codes = ix->codes; a.dlx = ix->dlx; a.ids = ix->ids;
+    a.codebooks = ix->codebooks; a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
+    a.queries = queries; a.lut = lut;
+    a.list_offsets = cand ? cand->list_offsets : nullptr;
+    a.probes = cand ? cand->probes : nullptr;
+    a.nlist = cand ? cand->nlist : 0;
+    a.nseg = cand ? cand->nprobe : 0;
+    const int64_t hard = (int64_t(1) << 31) - 1 - TRIM_MAX_BATCH - 2048;
+    int64_t mc = cand ? cand->max_candidates : ix->n;
+    if (mc <= 0 || mc > hard) mc = hard;
+    a.max_cand = (int32_t)mc;
+    a.P = pl.P; a.Mp = pl.Mp;
+    a.two_gamma = 2.0f * gamma;
+    a.n_scanned = stats ? stats->n_scanned : nullptr;
+    a.n_exact = stats ? stats->n_exact : nullptr;
+    a.mask = mask; a.mask_words = mask_words;
+    a.off_q = pl.off_q; a.off_segp = pl.off_segp; a.off_segd = pl.off_segd;
+    a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
+    a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
+}
+
+int fill_u32(uint32_t *p, size_t count, uint32_t v, hipStream_t st) {
+    if (count == 0) return TRIM_OK;
+    size_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, count, v);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+constexpr int kRangeRound = 2048;   // survivor-list capacity per round in range mode
+constexpr int kRangeSplitTarget = 2048;  // aim for at least this many workgroups
+
+int range_nsplit(int64_t nq, int64_t max_cand) {
+    int64_t want = (kRangeSplitTarget + nq - 1) / (nq > 0 ? nq : 1);
+    if (want < 1) want = 1;
+    // at least 4096 candidates per chunk so that the table fill is amortised
+    int64_t most = (max_cand + 4095) / 4096;
+    if (most < 1) most = 1;
+    if (want > most) want = most;
+    if (want > 65535) want = 65535;
+    return (int)want;
+}
+
+struct RangeLayout {
+    int nsplit;
+    int chunk;
+    int64_t rmask_words;
+    size_t off_counts, off_cbase, total;
+};
+
+RangeLayout range_layout(int64_t nq, int64_t max_cand) {
+    RangeLayout L;
+    L.nsplit = range_nsplit(nq, max_cand);
+    int64_t chunk = (max_cand + L.nsplit - 1) / L.nsplit;
+    chunk = (chunk + 63) / 64 * 64;
+    if (chunk < 64) chunk = 64;
+    L.chunk = (int)chunk;
+    L.rmask_words = (int64_t)L.nsplit * (chunk / 32);
+    size_t off = (size_t)nq * L.rmask_words * 4;
+    off = (off + 255) & ~size_t(255);
+    L.off_counts = off; off += (size_t)nq * L.nsplit * 4;
+    off = (off + 255) & ~size_t(255);
+    L.off_cbase = off; off += (size_t)nq * L.nsplit * 8;
+    L.total = (off + 255) & ~size_t(255);
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+int trim_shape_supported(int32_t d, int32_t M) {
+    Plan pl;
+    return make_plan(d, M, 64, 1024, 10, true, &pl) ? 1 : 0;
+}
+
+int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
+                uint8_t *codes_out, float *dlx_out, void *stream) {
+    if (n < 0 || d <= 0 || M <= 0) return TRIM_INVALID_ARG;
+    if (d % M || M % 4) return TRIM_UNSUPPORTED_SHAPE;
+    const int dsub = d / M;
+    if ((size_t)kC * dsub * 4 > 64 * 1024) return TRIM_UNSUPPORTED_SHAPE;
+    if (n == 0) return TRIM_OK;
+    if (!base || !codebooks || !codes_out || !dlx_out) return TRIM_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(codes_out) & 3u) return TRIM_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    const size_t lds = (size_t)kC * dsub * 4;
+    if (dsub == 4)
+        hipLaunchKernelGGL(encode_kernel<4>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
+    else if (dsub == 8)
+        hipLaunchKernelGGL(encode_kernel<8>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
+    else
+        hipLaunchKernelGGL(encode_kernel<0>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *codebooks, int32_t M,
+                   float *lut_out, int32_t mfma, void *stream) {
+    if (nq < 0 || d <= 0 || M <= 0) return TRIM_INVALID_ARG;
+    if (d % M) return TRIM_UNSUPPORTED_SHAPE;
+    if (mfma) return TRIM_UNSUPPORTED_SHAPE;
+    if (nq == 0) return TRIM_OK;
+    if (!queries || !codebooks || !lut_out) return TRIM_INVALID_ARG;
+    if (!aligned16(codebooks) || nq > 0x7fffffff) return TRIM_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int dsub = d / M;
+    const int jper = 8;
+    // grid.y is limited to 65535: walk the queries in slabs
+    for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
+        const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
+        hipLaunchKernelGGL(lut_kernel, dim3((M + jper - 1) / jper, (unsigned)cnt), dim3(256),
+                           (size_t)d * 4, st, queries + (size_t)q0 * d, d, codebooks, M, dsub, jper,
+                           lut_out + (size_t)q0 * M * kC);
+        HIP_TRY(hipGetLastError());
+    }
+    return TRIM_OK;
+}
+
+int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
+                    const float *lut, const trim_candidates *cand, int32_t k, float gamma,
+                    int32_t batch, int32_t *out_ids, float *out_d2, const trim_stats *stats,
+                    uint32_t *survivor_mask, int64_t mask_words, void *stream) {
+    int rc = check_index(index);
+    if (rc) return rc;
+    if ((rc = check_cand(cand))) return rc;
+    if (nq < 0 || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
+        return TRIM_INVALID_ARG;
+    if (!(gamma >= 0.0f) || std::isinf(gamma)) return TRIM_INVALID_ARG;
+    if (nq == 0) return TRIM_OK;
+    if (!queries || !out_ids || !out_d2) return TRIM_INVALID_ARG;
+    if (!lut && !index->codebooks) return TRIM_INVALID_ARG;
+    if (lut && !aligned16(lut)) return TRIM_INVALID_ARG;
+    if (survivor_mask && mask_words <= 0) return TRIM_INVALID_ARG;
+    Plan pl;
+    const int cap = batch > k ? batch : k;
+    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, cap, k, false, &pl))
+        return TRIM_UNSUPPORTED_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
+    SearchArgs a{};
+    fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
+    a.k = k; a.batch = batch; a.radius2 = 0.0f;
+    a.out_ids = out_ids; a.out_d2 = out_d2;
+    a.chunk = 0; a.nsplit = 1;
+    for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
+        const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
+        SearchArgs b = a;
+        b.queries = queries + (size_t)q0 * index->d;
+        if (lut) b.lut = lut + (size_t)q0 * index->M * kC;
+        if (b.probes) b.probes += (size_t)q0 * b.nseg;
+        b.out_ids += (size_t)q0 * k; b.out_d2 += (size_t)q0 * k;
+        if (b.n_scanned) b.n_scanned += q0;
+        if (b.n_exact) b.n_exact += q0;
+        if (b.mask) b.mask += (size_t)q0 * mask_words;
+        if ((rc = launch_search<kKnn>(b, pl, dim3(1, (unsigned)cnt), st))) return rc;
+    }
+    return TRIM_OK;
+}
+
+size_t trim_range_workspace_bytes(int64_t nq, int64_t max_candidates) {
+    if (nq <= 0 || max_candidates < 0) return 256;
+    return range_layout(nq, max_candidates).total;
+}
+
+int trim_search_range(const trim_index_view *index, const float *queries, int64_t nq,
+                      const float *lut, const trim_candidates *cand, float radius, float gamma,
+                      int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                      int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
+                      int64_t mask_words, void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_index(index);
+    if (rc) return rc;
+    if ((rc = check_cand(cand))) return rc;
+    if (nq < 0 || nq > 65535ll * 65535ll || capacity < 0) return TRIM_INVALID_ARG;
+    if (!(gamma >= 0.0f) || std::isinf(gamma) || !(radius >= 0.0f)) return TRIM_INVALID_ARG;
+    if (!out_offsets) return TRIM_INVALID_ARG;
+    if (capacity > 0 && (!out_ids || !out_d2)) return TRIM_INVALID_ARG;
+    if (lut && !aligned16(lut)) return TRIM_INVALID_ARG;
+    if (!lut && !index->codebooks) return TRIM_INVALID_ARG;
+    if (survivor_mask && mask_words <= 0) return TRIM_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (nq == 0) {
+        if ((rc = fill_u32(reinterpret_cast<uint32_t *>(out_offsets), 2, 0u, st))) return rc;
+        if (required && (rc = fill_u32(reinterpret_cast<uint32_t *>(required), 2, 0u, st))) return rc;
+        return TRIM_OK;
+    }
+    if (!queries) return TRIM_INVALID_ARG;
+    int64_t max_cand = cand ? cand->max_candidates : index->n;
+    if (cand && max_cand <= 0) return TRIM_INVALID_ARG;  // needed to size the masks
+    const RangeLayout L = range_layout(nq, max_cand);
+    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return TRIM_WORKSPACE;
+    Plan pl;
+    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, kRangeRound, 1, true, &pl))
+        return TRIM_UNSUPPORTED_SHAPE;
+
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    uint32_t *rmask = reinterpret_cast<uint32_t *>(ws);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.off_counts);
+    int64_t *cbase = reinterpret_cast<int64_t *>(ws + L.off_cbase);
+
+    if ((rc = fill_u32(rmask, (size_t)nq * L.rmask_words, 0u, st))) return rc;
+    if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
+    if (stats && stats->n_exact && (rc = fill_u32(reinterpret_cast<uint32_t *>(stats->n_exact), (size_t)nq, 0u, st)))
+        return rc;
+
+    SearchArgs a{};
+    fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
+    a.k = 1; a.batch = kRangeRound;
+    a.radius2 = radius * radius;
+    a.chunk = L.chunk; a.nsplit = L.nsplit;
+    a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;
+    if (a.max_cand > max_cand) a.max_cand = (int32_t)max_cand;
+
+    RangeFillArgs f{};
+    f.base = index->base; f.ids = index->ids; f.queries = queries;
+    f.list_offsets = a.list_offsets; f.probes = a.probes; f.n = index->n; f.d = index->d;
+    f.nlist = a.nlist; f.nseg = a.nseg; f.max_cand = a.max_cand; f.chunk = L.chunk;
+    f.nsplit = L.nsplit; f.result_mask = rmask; f.rmask_words = L.rmask_words;
+    f.chunk_base = cbase; f.out_ids = out_ids; f.out_d2 = out_d2; f.capacity = capacity;
+    const int nsegs = a.nseg > 0 ? a.nseg : 1;
+    size_t off = 0;
+    f.off_q = (uint32_t)off;    off += up16((size_t)index->d * 4);
+    f.off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
+    f.off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
+    f.off_list = (uint32_t)off; off += 2048 * 4;
+    const size_t fill_lds = off;
+
+    for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
+        const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
+        SearchArgs b = a;
+        b.queries = queries + (size_t)q0 * index->d;
+        if (lut) b.lut = lut + (size_t)q0 * index->M * kC;
+        if (b.probes) b.probes += (size_t)q0 * b.nseg;
+        if (b.n_scanned) b.n_scanned += q0;
+        if (b.n_exact) b.n_exact += q0;
+        if (b.mask) b.mask += (size_t)q0 * mask_words;
+        b.result_mask += (size_t)q0 * L.rmask_words;
+        b.chunk_counts += (size_t)q0 * L.nsplit;
+        if ((rc = launch_search<kRange>(b, pl, dim3((unsigned)L.nsplit, (unsigned)cnt), st))) return rc;
+    }
+    hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(1024), 0, st, counts, nq, L.nsplit, cbase,
+                       out_offsets, required);
+    HIP_TRY(hipGetLastError());
+    if (capacity > 0) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(range_fill_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)fill_lds));
+        for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
+            const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
+            RangeFillArgs g = f;
+            g.queries = queries + (size_t)q0 * index->d;
+            if (g.probes) g.probes += (size_t)q0 * g.nseg;
+            g.result_mask += (size_t)q0 * L.rmask_words;
+            g.chunk_base += (size_t)q0 * L.nsplit;
+            hipLaunchKernelGGL(range_fill_kernel, dim3((unsigned)L.nsplit, (unsigned)cnt), dim3(256),
+                               fill_lds, st, g);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    return TRIM_OK;
+}
+
+int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *centroids,
+                   int32_t nlist, int32_t nprobe, int32_t *probes_out, void *stream) {
+    if (nq < 0 || d <= 0 || nlist <= 0 || nprobe <= 0) return TRIM_INVALID_ARG;
+    if (nprobe > nlist || nprobe > TRIM_MAX_NPROBE) return TRIM_INVALID_ARG;
+    if (d % 4) return TRIM_UNSUPPORTED_SHAPE;
+    int npow2 = 1;
+    while (npow2 < nlist) npow2 <<= 1;
+    const size_t lds = (size_t)npow2 * 8 + (size_t)d * 4;
+    if (lds > kLdsBytes) return TRIM_UNSUPPORTED_SHAPE;
+    if (nq == 0) return TRIM_OK;
+    if (!queries || !centroids || !probes_out || !aligned16(centroids)) return TRIM_INVALID_ARG;
+    if (nq > 0x7fffffff) return TRIM_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(ivf_probe_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const int threads = npow2 >= 2048 ? 1024 : 256;
+    hipLaunchKernelGGL(ivf_probe_kernel, dim3((unsigned)nq), dim3(threads), lds, st, queries, d,
+                       centroids, nlist, npow2, nprobe, probes_out);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+const char *trim_strerror(int status) {
+    switch (status) {
+        case TRIM_OK: return "ok";
+        case TRIM_INVALID_ARG: return "invalid argument";
+        case TRIM_UNSUPPORTED_SHAPE: return "unsupported shape (d, M) for this build";
+        case TRIM_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TRIM_HIP_ERROR: return "HIP call failed (see trim_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+int trim_last_hip_error(void) { return g_last_hip_error; }
+
+const char *trim_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,271 @@
+// Kernels around the scan: PQ encode, stand-alone distance tables, range-search output
+// assembly, coarse-probe selection, small fills.
+#pragma once
+
+#include "trim_device.h"
+
+namespace trim {
+
+// ---- fills (used instead of memset nodes so that callers may capture the stream) ----
+__global__ void fill_u32_kernel(uint32_t *p, size_t count, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// ---- PQ encode (Section 3.3, preprocessing step 1) ----
+// One thread per vector; the block stages one subspace's 256 centroids in LDS at a time.
+// DSUB > 0: sub-vector length known at compile time (kept in registers); DSUB == 0: generic.
+template <int DSUB>
+__global__ __launch_bounds__(256) void encode_kernel(const float *__restrict__ base, int64_t n,
+                                                     int d, const float *__restrict__ codebooks,
+                                                     int M, int dsub_rt,
+                                                     uint8_t *__restrict__ codes,
+                                                     float *__restrict__ dlx) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *cb = reinterpret_cast<float *>(smem);  // [256][dsub]
+    const int dsub = DSUB > 0 ? DSUB : dsub_rt;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool valid = i < n;
+    const float *x = base + (size_t)(valid ? i : 0) * d;
+    float tot = 0.0f;
+    uint32_t packed = 0;
+    for (int j = 0; j < M; ++j) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < kC * dsub; e += blockDim.x)
+            cb[e] = codebooks[(size_t)j * kC * dsub + e];
+        __syncthreads();
+        float best = __builtin_inff();
+        int arg = 0;
+        if constexpr (DSUB > 0) {
+            float xr[DSUB];
+#pragma unroll
+            for (int t = 0; t < DSUB; ++t) xr[t] = x[j * DSUB + t];
+            for (int c = 0; c < kC; ++c) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int t = 0; t < DSUB; ++t) {
+                    const float e = xr[t] - cb[c * DSUB + t];
+                    acc = __builtin_fmaf(e, e, acc);
+                }
+                if (acc < best) { best = acc; arg = c; }
+            }
+        } else {
+            for (int c = 0; c < kC; ++c) {
+                float acc = 0.0f;
+                for (int t = 0; t < dsub; ++t) {
+                    const float e = x[j * dsub + t] - cb[c * dsub + t];
+                    acc = __builtin_fmaf(e, e, acc);
+                }
+                if (acc < best) { best = acc; arg = c; }
+            }
+        }
+        tot = tot + best;
+        packed |= (uint32_t)arg << (8 * (j & 3));
+        if ((j & 3) == 3) {
+            if (valid) *reinterpret_cast<uint32_t *>(codes + (size_t)i * M + (j - 3)) = packed;
+            packed = 0;
+        }
+    }
+    if (valid) dlx[i] = __fsqrt_rn(tot);
+}
+
+// ---- stand-alone distance table (Section 3.3, query-processing operation 1) ----
+// grid (ceil(M / jper), nq); each block writes jper table rows of one query.
+__global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ queries, int d,
+                                                  const float *__restrict__ codebooks, int M,
+                                                  int dsub, int jper, float *__restrict__ lut) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *q_lds = reinterpret_cast<float *>(smem);
+    const int64_t q = blockIdx.y;
+    const int j0 = blockIdx.x * jper;
+    const int nj = j0 + jper <= M ? jper : M - j0;
+    for (int t = threadIdx.x; t < d; t += blockDim.x) q_lds[t] = queries[(size_t)q * d + t];
+    __syncthreads();
+    build_table_rows(lut + ((size_t)q * M + j0) * kC, q_lds, codebooks, dsub, j0, nj);
+}
+
+// ---- range search: offsets from per-chunk counts (single workgroup) ----
+// counts [nq*nsplit] -> chunk_base [nq*nsplit] (exclusive prefix), out_offsets [nq+1],
+// *required = total.
+__global__ __launch_bounds__(1024) void range_offsets_kernel(const int32_t *__restrict__ counts,
+                                                             int64_t nq, int nsplit,
+                                                             int64_t *__restrict__ chunk_base,
+                                                             int64_t *__restrict__ out_offsets,
+                                                             int64_t *__restrict__ required) {
+    __shared__ int64_t part[1024];
+    const int64_t total_items = nq * nsplit;
+    const int T = blockDim.x;
+    const int64_t per = (total_items + T - 1) / T;
+    const int64_t lo = (int64_t)threadIdx.x * per;
+    const int64_t hi = lo + per < total_items ? lo + per : total_items;
+    int64_t s = 0;
+    for (int64_t i = lo; i < hi; ++i) s += counts[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t run = 0;
+        for (int t = 0; t < T; ++t) { const int64_t v = part[t]; part[t] = run; run += v; }
+        out_offsets[nq] = run;
+        if (required) *required = run;
+    }
+    __syncthreads();
+    int64_t run = part[threadIdx.x];
+    for (int64_t i = lo; i < hi; ++i) {
+        chunk_base[i] = run;
+        if (i % nsplit == 0) out_offsets[i / nsplit] = run;
+        run += counts[i];
+    }
+}
+
+// ---- range search: write the results of one (query, chunk) in scan order ----
+struct RangeFillArgs {
+    const float *base;
+    const int32_t *ids;
+    const float *queries;
+    const int64_t *list_offsets;
+    const int32_t *probes;
+    int64_t n;
+    int32_t d, nlist, nseg, max_cand, chunk, nsplit;
+    const uint32_t *result_mask;
+    int64_t rmask_words;
+    const int64_t *chunk_base;
+    int32_t *out_ids;
+    float *out_d2;
+    int64_t capacity;
+    uint32_t off_q, off_segp, off_segd, off_list;
+};
+
+__global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
+    int *segp = reinterpret_cast<int *>(smem + a.off_segp);
+    int *segd = reinterpret_cast<int *>(smem + a.off_segd);
+    int *list = reinterpret_cast<int *>(smem + a.off_list);  // [2048] scan-order numbers
+    __shared__ int s_total;
+
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int lane = tid & (kWave - 1);
+    const int64_t q = blockIdx.y;
+    const int split = blockIdx.x;
+    const int nseg = a.nseg > 0 ? a.nseg : 1;
+
+    for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
+    for (int p = tid; p < nseg; p += T) {
+        int64_t s = 0, e = a.n;
+        if (a.nseg > 0) {
+            const int32_t l = a.probes[(size_t)q * a.nseg + p];
+            if (l >= 0 && l < a.nlist) {
+                s = a.list_offsets[l];
+                e = a.list_offsets[l + 1];
+                s = s < 0 ? 0 : (s > a.n ? a.n : s);
+                e = e < s ? s : (e > a.n ? a.n : e);
+            } else {
+                s = e = 0;
+            }
+        }
+        segd[p] = (int)s;
+        segp[p + 1] = (int)(e - s);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int64_t run = 0;
+        segp[0] = 0;
+        for (int p = 0; p < nseg; ++p) {
+            int64_t len = segp[p + 1];
+            if (run + len > a.max_cand) len = a.max_cand - run;
+            segd[p] = segd[p] - (int)run;
+            run += len;
+            segp[p + 1] = (int)run;
+        }
+        s_total = (int)run;
+    }
+    __syncthreads();
+    const int total = s_total;
+    const int c_begin = split * a.chunk;
+    if (c_begin >= total) return;
+    const int c_end = c_begin + a.chunk < total ? c_begin + a.chunk : total;
+    int64_t out = a.chunk_base[(size_t)q * a.nsplit + split];
+
+    // rounds of 64 mask words (2048 candidates); wave 0 expands set bits in order
+    for (int r0 = c_begin; r0 < c_end; r0 += 2048) {
+        __shared__ int s_cnt;
+        if (tid < kWave) {
+            const int c_w = r0 + lane * 32;
+            uint32_t w = 0;
+            if (c_w < c_end) w = a.result_mask[(size_t)q * a.rmask_words + (c_w >> 5)];
+            int cnt = __popc(w);
+            int incl = cnt;  // inclusive prefix over the wave
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int v = __shfl_up(incl, o);
+                if (lane >= o) incl += v;
+            }
+            int at = incl - cnt;
+            while (w) {
+                const int b = __ffs((int)w) - 1;
+                w &= w - 1;
+                list[at++] = c_w + b;
+            }
+            if (lane == kWave - 1) s_cnt = incl;
+        }
+        __syncthreads();
+        const int cnt = s_cnt;
+        for (int i = tid >> 5; i < cnt; i += T >> 5) {
+            const int c = list[i];
+            // segment of c by binary search over the prefix table
+            int lo = 0, hi = nseg - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (c >= segp[mid + 1]) lo = mid + 1; else hi = mid;
+            }
+            const int pos = c + segd[lo];
+            const float d2 = exact_d2_half(a.base + (size_t)pos * a.d, q_lds, a.d, tid & 31);
+            if ((tid & 31) == 0 && out + i < a.capacity) {
+                a.out_ids[out + i] = a.ids ? a.ids[pos] : pos;
+                a.out_d2[out + i] = d2;
+            }
+        }
+        out += cnt;
+        __syncthreads();
+    }
+}
+
+// ---- coarse probe selection (Section 6.1: IVFPQ with C' lists, nprobe probed) ----
+// One workgroup per query: exact distances to all centroids (half wave each), then a
+// bitonic sort of (distance bits, list id) keys in LDS; the first nprobe ids are written.
+__global__ __launch_bounds__(1024) void ivf_probe_kernel(const float *__restrict__ queries, int d,
+                                                         const float *__restrict__ centroids,
+                                                         int nlist, int npow2, int nprobe,
+                                                         int32_t *__restrict__ probes) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);  // [npow2]
+    float *q_lds = reinterpret_cast<float *>(smem + (size_t)npow2 * 8);
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int64_t q = blockIdx.x;
+    for (int t = tid; t < d; t += T) q_lds[t] = queries[(size_t)q * d + t];
+    for (int i = nlist + tid; i < npow2; i += T) keys[i] = ~0ull;
+    __syncthreads();
+    for (int l = tid >> 5; l < nlist; l += T >> 5) {
+        const float d2 = exact_d2_half(centroids + (size_t)l * d, q_lds, d, tid & 31);
+        // d2 >= 0 (or NaN): its bit pattern orders like its value
+        if ((tid & 31) == 0)
+            keys[l] = ((unsigned long long)__float_as_uint(d2) << 32) | (uint32_t)l;
+    }
+    __syncthreads();
+    for (int size = 2; size <= npow2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < npow2 >> 1; i += T) {
+                const int lo = ((i / stride) * stride << 1) + (i % stride);
+                const int hi = lo + stride;
+                const bool up = ((lo & size) == 0);
+                const unsigned long long x = keys[lo], y = keys[hi];
+                if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int p = tid; p < nprobe; p += T) probes[(size_t)q * nprobe + p] = (int32_t)(keys[p] & 0xffffffffu);
+}
+
+}  // namespace trim

@@ -1,0 +1,151 @@
+// Device-side building blocks of the TRIM scan for gfx950 (wave64).
+//
+// Rounding order (binary32, no contraction; this file is compiled with -ffp-contract=off
+// and every fused multiply-add is written as __builtin_fmaf):
+//   sub-vector distance : acc = fma(x_t - c_t, x_t - c_t, acc), t ascending
+//   Gamma(l,q)^2        : table entries added left to right over the subspaces
+//   bound (Equation 3)  : a = sqrt(s); e = a - b; g = fma((2*gamma)*a, b, e*e)
+//   exact distance      : lane l of a 32-lane group owns coordinate groups l, l+32, ...
+//                         (4 coordinates each, fma in order); then a 5-step butterfly
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace trim {
+
+constexpr int kC = 256;          // centroids per subspace (the paper's C)
+constexpr int kWave = 64;
+
+struct Hit {
+    float d2;
+    int32_t id;
+};
+
+__device__ __forceinline__ bool hit_less(float d2a, int32_t ida, float d2b, int32_t idb) {
+    return d2a < d2b || (d2a == d2b && ida < idb);
+}
+
+// Squared distance between a query sub-vector held in LDS and a centroid in global memory.
+__device__ __forceinline__ float subvec_sqdist(const float *__restrict__ x,
+                                               const float *__restrict__ c, int dsub) {
+    float acc = 0.0f;
+    if ((dsub & 3) == 0) {
+        for (int t = 0; t < dsub; t += 4) {
+            const float4 cv = *reinterpret_cast<const float4 *>(c + t);
+            const float4 xv = *reinterpret_cast<const float4 *>(x + t);
+            float e;
+            e = xv.x - cv.x; acc = __builtin_fmaf(e, e, acc);
+            e = xv.y - cv.y; acc = __builtin_fmaf(e, e, acc);
+            e = xv.z - cv.z; acc = __builtin_fmaf(e, e, acc);
+            e = xv.w - cv.w; acc = __builtin_fmaf(e, e, acc);
+        }
+    } else {
+        for (int t = 0; t < dsub; ++t) {
+            const float e = x[t] - c[t];
+            acc = __builtin_fmaf(e, e, acc);
+        }
+    }
+    return acc;
+}
+
+// Distance-table rows [j0, j0+nj) of one query (Section 2.2 / Section 3.3 operation 1):
+// out[(j-j0)*256 + c] = || q_j - centroid_{j,c} ||^2.  q points at the whole query (LDS or
+// global), out at LDS or global.  All threads of the block take part.
+__device__ __forceinline__ void build_table_rows(float *__restrict__ out,
+                                                 const float *__restrict__ q,
+                                                 const float *__restrict__ codebooks, int dsub,
+                                                 int j0, int nj) {
+    for (int e = threadIdx.x; e < nj * kC; e += blockDim.x) {
+        const int j = j0 + (e >> 8);
+        const int c = e & (kC - 1);
+        out[e] = subvec_sqdist(q + j * dsub, codebooks + ((size_t)j * kC + c) * dsub, dsub);
+    }
+}
+
+// Equation 3 from s = Gamma(l,q)^2 and b = Gamma(l,x).
+__device__ __forceinline__ float plb_from_s(float s, float b, float two_gamma) {
+    const float a = __fsqrt_rn(s);
+    const float e = a - b;
+    const float t = two_gamma * a;
+    return __builtin_fmaf(t, b, e * e);
+}
+
+// Exact squared distance, computed by the 32 lanes of a half wave (all 32 must call it
+// together).  row: global, 16-byte aligned; q: LDS.  Every lane returns the result.
+__device__ __forceinline__ float exact_d2_half(const float *__restrict__ row,
+                                               const float *__restrict__ q, int d, int lane32) {
+    float acc = 0.0f;
+    const float4 *r4 = reinterpret_cast<const float4 *>(row);
+    const float4 *q4 = reinterpret_cast<const float4 *>(q);
+    const int ng = d >> 2;
+    for (int g = lane32; g < ng; g += 32) {
+        const float4 xv = r4[g];
+        const float4 qv = q4[g];
+        float e;
+        e = qv.x - xv.x; acc = __builtin_fmaf(e, e, acc);
+        e = qv.y - xv.y; acc = __builtin_fmaf(e, e, acc);
+        e = qv.z - xv.z; acc = __builtin_fmaf(e, e, acc);
+        e = qv.w - xv.w; acc = __builtin_fmaf(e, e, acc);
+    }
+#pragma unroll
+    for (int h = 16; h >= 1; h >>= 1) acc = acc + __shfl_xor(acc, h, 32);
+    return acc;
+}
+
+// Sum of table entries selected by 4*VEC consecutive code bytes (VEC dwords), added to s
+// in subspace order.  tab points at the table row of the first of these subspaces.
+template <int VEC>
+__device__ __forceinline__ float gather_add(float s, const float *__restrict__ tab,
+                                            const uint32_t (&w)[VEC]) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t code = (w[v] >> (8 * b)) & 0xffu;
+            s = s + tab[(v * 4 + b) * kC + code];
+        }
+    }
+    return s;
+}
+
+template <int VEC> struct CodeVec;
+template <> struct CodeVec<4> { using type = uint4; };
+template <> struct CodeVec<2> { using type = uint2; };
+template <> struct CodeVec<1> { using type = uint32_t; };
+
+template <int VEC>
+__device__ __forceinline__ void load_codes(uint32_t (&w)[VEC], const uint8_t *__restrict__ p) {
+    if constexpr (VEC == 4) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else if constexpr (VEC == 2) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        w[0] = v.x; w[1] = v.y;
+    } else {
+        w[0] = *reinterpret_cast<const uint32_t *>(p);
+    }
+}
+
+// s += table entries of subspaces [0, Mp) of one candidate (Mp % (4*VEC) == 0).
+template <int VEC>
+__device__ __forceinline__ float table_sum(float s, const float *__restrict__ tab,
+                                           const uint8_t *__restrict__ code, int Mp) {
+    constexpr int STEP = 4 * VEC;
+    int j = 0;
+    for (; j + 2 * STEP <= Mp; j += 2 * STEP) {
+        uint32_t w0[VEC], w1[VEC];
+        load_codes<VEC>(w0, code + j);
+        load_codes<VEC>(w1, code + j + STEP);
+        s = gather_add<VEC>(s, tab + j * kC, w0);
+        s = gather_add<VEC>(s, tab + (j + STEP) * kC, w1);
+    }
+    for (; j < Mp; j += STEP) {
+        uint32_t w0[VEC];
+        load_codes<VEC>(w0, code + j);
+        s = gather_add<VEC>(s, tab + j * kC, w0);
+    }
+    return s;
+}
+
+}  // namespace trim

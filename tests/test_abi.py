@@ -1,0 +1,82 @@
+"""CPU-only checks of the boundary: libtrim.so loads, exports every function that
+include/trim.h declares, and rejects bad arguments on the host before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "trim.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2508_17828_amd import trim
+    if not os.path.exists(trim.LIB_PATH):
+        from paper_2508_17828_amd import build
+        build.build()
+    return trim.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(trim_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_function_is_exported(L):
+    from paper_2508_17828_amd import trim
+    names = declared_functions()
+    assert set(names) == set(trim.EXPORTS), (names, trim.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_header_cites_the_paper_for_each_operation():
+    src = open(HEADER).read()
+    for name, cite in (("trim_encode", "Section 3.3"), ("trim_build_lut", "Section 3.3"),
+                       ("trim_search_knn", "Section 4.2"), ("trim_search_range", "Section 4.2"),
+                       ("trim_ivf_probe", "Section 6.1")):
+        decl = src.index("int " + name)
+        comment = src.rfind("/*", 0, decl)
+        assert cite in src[comment:decl], name
+
+
+def test_host_side_validation(L):
+    from paper_2508_17828_amd import trim
+    assert L.trim_shape_supported(128, 32) == 1
+    assert L.trim_shape_supported(128, 16) == 1
+    assert L.trim_shape_supported(960, 120) == 1
+    assert L.trim_shape_supported(1536, 192) == 1
+    assert L.trim_shape_supported(130, 13) == 0      # d % 4
+    assert L.trim_shape_supported(128, 6) == 0       # d % M
+    assert L.trim_shape_supported(120, 30) == 0      # M % 4
+    assert L.trim_strerror(0) == b"ok"
+    assert b"shape" in L.trim_strerror(-2)
+    assert L.trim_version().decode().count(".") == 1
+    assert L.trim_range_workspace_bytes(100, 10_000) >= 100 * 10_000 // 8
+    # null index / bad sizes are refused before any HIP call
+    assert L.trim_search_knn(None, None, 1, None, None, 10, 0.0, 64, None, None, None, None, 0, None) == -1
+    view = trim._IndexView(10, 128, 32, None, None, None, None, None)
+    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, None, None, None, None, 0, None) == -1
+    view = trim._IndexView(0, 128, 6, None, None, None, None, None)
+    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, None, None, None, None, 0, None) == -2
+    assert L.trim_encode(None, 5, 128, None, 32, None, None, None) == -1
+    assert L.trim_encode(None, 0, 128, None, 32, None, None, None) == 0
+    assert L.trim_encode(None, 5, 128, None, 6, None, None, None) == -2
+    assert L.trim_build_lut(None, 3, 128, None, 32, None, 0, None) == -1
+    assert L.trim_ivf_probe(None, 3, 128, None, 16, 32, None, None) == -1   # nprobe > nlist
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2508_17828_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "synth.py", f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2508_17828_amd" not in text, f

@@ -1,0 +1,247 @@
+"""GPU parity: every entry point of libtrim, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Bars: PQ codes, landmark distances (they feed the
+masks), survivor masks, counters and result ids bit-exact; squared distances within
+1e-4 relative (they are in fact produced in the same rounding order, so equality is
+asserted first and the tolerance only documents the contract)."""
+import numpy as np
+import pytest
+
+from paper_2508_17828_amd import synth
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def T():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2508_17828_amd import trim
+    trim.lib()
+    return trim
+
+
+def to_dev(T, b):
+    import torch
+    ix = b.index
+    dev = "cuda:0"
+    t = lambda a: None if a is None else torch.from_numpy(a).to(dev)
+    gi = T.Index(t(ix.base), t(ix.codes), t(ix.dlx), t(ix.codebooks), ids=t(ix.ids),
+                 list_offsets=t(ix.list_offsets),
+                 max_list_len=int(np.diff(ix.list_offsets).max()) if ix.list_offsets is not None else 0)
+    return gi, t(b.queries), t(b.probes)
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+CASES = {
+    # name: (workload, n, nq, nlist, nprobe)
+    "c1": ("C1", 0, 0, -1, -1),                 # the full tiny config: 10k x 128, M=16
+    "c2s": ("C2", 60_000, 96, 64, 8),            # M=32, dsub=4, IVF; ragged lists
+    "c3s": ("C3", 12_000, 24, -1, -1),           # d=960, M=120 (8-byte code loads), k=100
+    "c4s": ("C4", 16_000, 32, 32, 6),            # d=1536, M=192: table in two LDS phases
+    "c5s": ("C5", 80_000, 64, 128, 16),          # M=32 with many short lists
+}
+
+
+def case(name):
+    wname, n, nq, nlist, nprobe = CASES[name]
+    return helpers.cached(wname, n, nq, nlist, nprobe)
+
+
+# ---- trim_encode ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_encode(T, oracle, name):
+    b = case(name)
+    gi, _, _ = to_dev(T, b)
+    codes, dlx = T.trim_encode(gi.base, gi.codebooks)
+    np.testing.assert_array_equal(codes.cpu().numpy(), b.index.codes)
+    np.testing.assert_array_equal(dlx.cpu().numpy().view(np.uint32), b.index.dlx.view(np.uint32))
+
+
+def test_encode_generic_subvector_length(T, oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    for d, M, n in ((48, 8, 1000), (24, 12, 515), (128, 4, 300)):   # dsub 6, 2, 32
+        base = rng.standard_normal((n, d)).astype(np.float32)
+        cb = rng.standard_normal((M, 256, d // M)).astype(np.float32)
+        rc, rd = oracle.encode(base, cb)
+        codes, dlx = T.trim_encode(torch.from_numpy(base).cuda(), torch.from_numpy(cb).cuda())
+        np.testing.assert_array_equal(codes.cpu().numpy(), rc)
+        np.testing.assert_array_equal(dlx.cpu().numpy().view(np.uint32), rd.view(np.uint32))
+
+
+# ---- trim_build_lut --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_build_lut(T, oracle, name):
+    b = case(name)
+    gi, q, _ = to_dev(T, b)
+    lut = T.trim_build_lut(q, gi.codebooks)
+    ref = oracle.build_lut(b.queries, b.index.codebooks)
+    np.testing.assert_array_equal(lut.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+# ---- trim_ivf_probe ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["c2s", "c4s", "c5s"])
+def test_ivf_probe(T, oracle, name):
+    import torch
+    b = case(name)
+    _, q, _ = to_dev(T, b)
+    cen = torch.from_numpy(b.centroids).cuda()
+    for nprobe in (1, b.w.nprobe, b.w.nlist):
+        got = T.trim_ivf_probe(q, cen, nprobe).cpu().numpy()
+        np.testing.assert_array_equal(got, oracle.ivf_probe(b.queries, b.centroids, nprobe))
+
+
+# ---- trim_search_knn ---------------------------------------------------------------------------
+
+def check_knn(T, oracle, b, k, gamma, batch, prebuilt_lut=False):
+    gi, q, probes = to_dev(T, b)
+    lut = T.trim_build_lut(q, gi.codebooks) if prebuilt_lut else None
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, lut=lut, want_mask=True)
+    ref = oracle.search_knn(b.index, b.queries, k, gamma, batch, b.probes, want_mask=True)
+    np.testing.assert_array_equal(got["n_scanned"].cpu().numpy(), ref["n_scanned"])
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
+    np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"])
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_allclose(got["d2"].cpu().numpy(), ref["d2"], rtol=RTOL)
+    np.testing.assert_array_equal(got["d2"].cpu().numpy(), ref["d2"])
+    return got, ref
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.6])
+@pytest.mark.parametrize("batch", [1, 100, 256, 4096])
+def test_knn_c1(T, oracle, gamma, batch):
+    check_knn(T, oracle, case("c1"), 10, gamma, batch)
+
+
+@pytest.mark.parametrize("name,k,batch", [("c2s", 10, 1024), ("c2s", 1, 64), ("c2s", 70, 333),
+                                          ("c5s", 10, 1024), ("c3s", 100, 4096),
+                                          ("c3s", 100, 512), ("c4s", 10, 2048)])
+@pytest.mark.parametrize("gamma", [0.0, 0.5, 0.8])
+def test_knn_shapes(T, oracle, name, k, batch, gamma):
+    got, ref = check_knn(T, oracle, case(name), k, gamma, batch)
+    if gamma == 0.0:
+        bi, _ = oracle.brute_knn(case(name).index, case(name).queries, k, case(name).probes)
+        np.testing.assert_array_equal(got["ids"].cpu().numpy(), bi)
+
+
+@pytest.mark.parametrize("name", ["c2s", "c4s"])
+def test_knn_with_prebuilt_table(T, oracle, name):
+    check_knn(T, oracle, case(name), 10, 0.5, 512, prebuilt_lut=True)
+
+
+def test_knn_large_k(T, oracle):
+    check_knn(T, oracle, case("c2s"), 1024, 0.3, 4096)
+    check_knn(T, oracle, case("c1"), 200, 0.0, 128)
+
+
+def test_knn_few_candidates_and_padding(T, oracle):
+    import torch
+    b = case("c1")
+    ix = b.index
+    small = type(ix)(ix.base[:7].copy(), ix.codes[:7].copy(), ix.dlx[:7].copy(), ix.codebooks)
+    sb = helpers.Built(b.w, small, b.queries[:5].copy(), None, None)
+    got, ref = check_knn(T, oracle, sb, 10, 0.0, 16)
+    assert np.all(got["ids"].cpu().numpy()[:, 7:] == -1)
+    assert np.all(np.isinf(got["d2"].cpu().numpy()[:, 7:]))
+    # no queries at all
+    gi, q, _ = to_dev(T, sb)
+    out = T.trim_search_knn(gi, q[:0], 10, 0.0, 16)
+    assert out["ids"].shape == (0, 10)
+
+
+def test_knn_empty_and_repeated_lists(T, oracle):
+    # probes that name empty lists, and the same list twice (scanned twice, as the oracle does)
+    b = case("c2s")
+    ix = b.index
+    lo = ix.list_offsets.copy()
+    # empty out list 3 by moving its boundary: lists 3 and 4 become [empty], [3+4]
+    lo[4] = lo[3]
+    ix2 = type(ix)(ix.base, ix.codes, ix.dlx, ix.codebooks, ids=ix.ids, list_offsets=lo)
+    probes = b.probes.copy()
+    probes[:, 0] = 3
+    probes[:, 2] = probes[:, 1]
+    b2 = helpers.Built(b.w, ix2, b.queries, probes, b.centroids)
+    check_knn(T, oracle, b2, 10, 0.4, 256)
+    probes[:] = 3                                   # nothing to scan at all
+    b3 = helpers.Built(b.w, ix2, b.queries, probes, b.centroids)
+    got, _ = check_knn(T, oracle, b3, 10, 0.4, 256)
+    assert np.all(got["ids"].cpu().numpy() == -1)
+
+
+def test_knn_is_deterministic(T, oracle):
+    b = case("c5s")
+    gi, q, probes = to_dev(T, b)
+    a = T.trim_search_knn(gi, q, 10, 0.7, 1024, probes=probes, want_mask=True)
+    c = T.trim_search_knn(gi, q, 10, 0.7, 1024, probes=probes, want_mask=True)
+    for key in ("ids", "d2", "n_exact", "mask"):
+        assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy())
+
+
+def test_argument_errors(T):
+    import torch
+    b = case("c1")
+    gi, q, _ = to_dev(T, b)
+    for kw in (dict(k=0), dict(k=T.TRIM_MAX_K + 1), dict(batch=0), dict(batch=T.TRIM_MAX_BATCH + 1),
+               dict(gamma=-0.1), dict(gamma=float("nan"))):
+        args = dict(k=10, gamma=0.0, batch=64); args.update(kw)
+        with pytest.raises(T.TrimError):
+            T.trim_search_knn(gi, q, args["k"], args["gamma"], args["batch"])
+    assert not T.trim_shape_supported(130, 16) and not T.trim_shape_supported(128, 6)
+    assert T.trim_shape_supported(128, 32) and T.trim_shape_supported(1536, 192)
+    with pytest.raises(TypeError):
+        T.trim_encode(gi.base, gi.codebooks[:, :, :7].contiguous())
+    with pytest.raises(TypeError):
+        T.trim_encode(gi.base.cpu(), gi.codebooks)
+
+
+# ---- trim_search_range ---------------------------------------------------------------------------
+
+def check_range(T, oracle, b, radius, gamma):
+    gi, q, probes = to_dev(T, b)
+    got = T.trim_search_range(gi, q, radius, gamma, probes=probes, want_mask=True)
+    ref = oracle.search_range(b.index, b.queries, radius, gamma, b.probes, want_mask=True)
+    np.testing.assert_array_equal(got["n_scanned"].cpu().numpy(), ref["n_scanned"])
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
+    np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"])
+    np.testing.assert_array_equal(got["offsets"].cpu().numpy(), ref["offsets"])
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_allclose(got["d2"].cpu().numpy(), ref["d2"], rtol=RTOL)
+    np.testing.assert_array_equal(got["d2"].cpu().numpy(), ref["d2"])
+    return got, ref
+
+
+@pytest.mark.parametrize("name,percent", [("c1", 1.0), ("c2s", 0.5), ("c4s", 0.5), ("c5s", 0.2),
+                                          ("c3s", 1.0)])
+@pytest.mark.parametrize("gamma", [0.0, 0.7])
+def test_range(T, oracle, name, percent, gamma):
+    b = case(name)
+    radius = helpers.radius_at_percentile(b, percent, 24, 2000)
+    got, ref = check_range(T, oracle, b, radius, gamma)
+    if gamma == 0.0:
+        assert ref["offsets"][-1] > 0
+
+
+def test_range_degenerate_radii_and_capacity(T, oracle):
+    b = case("c2s")
+    check_range(T, oracle, b, 0.0, 0.0)                      # nothing within radius 0
+    got, ref = check_range(T, oracle, b, 1e6, 0.0)            # everything is a result
+    assert ref["offsets"][-1] == ref["n_scanned"].sum()
+    gi, q, probes = to_dev(T, b)
+    with pytest.raises(T.TrimCapacityError) as e:
+        T.trim_search_range(gi, q, 1e6, 0.0, probes=probes, capacity=1000)
+    assert e.value.required == ref["offsets"][-1]
+    import torch
+    with pytest.raises(T.TrimError):
+        T.trim_search_range(gi, q, 1.0, 0.0, probes=probes,
+                            workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
