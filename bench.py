@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the TRIM filter-then-refine scan on one MI355X.
+
+A step = one pass of the whole hot path over the full query batch of the workload:
+coarse-probe selection, distance tables (built inside the scan kernel), lower-bound scan
+with pruning, exact refinement of survivors and top-k selection.  Inputs (index, queries)
+are resident in HBM before the timed region; results stay on the device.
+
+Prints ONE JSON line (see the design doc for the definition of every field).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", help="C1..C5 (default C2, the headline config)")
+    ap.add_argument("--gamma", type=float, default=None,
+                    help="relaxation to time (default: largest swept gamma with recall@k >= 0.95)")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--truth-queries", type=int, default=1000,
+                    help="queries used for the exact ground truth behind recall@k")
+    ap.add_argument("--cpu-queries", type=int, default=2000,
+                    help="queries the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-sweep", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(the path has no collective; see DESIGN.md, 'How it would shard')", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2508_17828_amd import index_setup, synth, trim
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    trim.lib()
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    batch = args.batch or w.batch
+    t0 = time.time()
+    bw = index_setup.build_workload(w)
+    ix, queries = bw.index, bw.queries
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+    nq, k = w.nq, w.k
+
+    def probes_for(q):
+        return trim.trim_ivf_probe(q, bw.centroids, w.nprobe) if w.nlist else None
+
+    # ---- ground truth on a query subset: exact kNN over ALL n by the strict scan (gamma = 0
+    # never prunes a true neighbour), no candidate structure ----
+    nt = min(args.truth_queries, nq)
+    truth = None
+    if nt > 0:
+        truth = trim.trim_search_knn(ix, queries[:nt].contiguous(), k, 0.0, 4096,
+                                     want_stats=False)["ids"]
+
+    def run_once(gamma, want_stats=True):
+        pr = probes_for(queries)
+        return trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, want_stats=want_stats)
+
+    # ---- sweep of the relaxation parameter (untimed quality numbers, short timing) ----
+    sweep = []
+    gammas = sorted(set(list(w.gammas) + ([] if args.no_sweep else [0.2, 0.4, 0.6, 0.7, 0.9])))
+    if args.gamma is not None:
+        gammas = [args.gamma]
+    for g in gammas:
+        r = run_once(g)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        reps = 0 if args.gamma is not None else 3
+        for _ in range(reps):
+            run_once(g, want_stats=False)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / max(1, reps)
+        scanned = int(r["n_scanned"].sum().item())
+        exact = int(r["n_exact"].sum().item())
+        rec = round(index_setup.recall_at_k(r["ids"][:nt], truth), 4) if nt > 0 else None
+        sweep.append(dict(gamma=g, recall=rec,
+                          pruning_ratio=round(1.0 - exact / max(1, scanned), 5),
+                          qps=round(nq / (ms * 1e-3), 1) if reps else None, n_scanned=scanned,
+                          n_exact=exact))
+    ok = [s for s in sweep if s["recall"] is not None and s["recall"] >= 0.95]
+    chosen = max(ok, key=lambda s: s["gamma"]) if ok else min(sweep, key=lambda s: s["gamma"])
+    gamma = chosen["gamma"]
+
+    # ---- timed region: K steps, events around each step and around the scan kernel ----
+    out = (torch.empty((nq, k), dtype=torch.int32, device="cuda"),
+           torch.empty((nq, k), dtype=torch.float32, device="cuda"))
+    for _ in range(args.warmup):
+        pr = probes_for(queries)
+        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, want_stats=False, out=out)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t_start = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        pr = probes_for(queries)
+        ev[s][1].record()
+        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, want_stats=False, out=out)
+        ev[s][2].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3 / args.steps
+    step_ms = sum(e[0].elapsed_time(e[2]) for e in ev) / args.steps
+    scan_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ms_per_step = max(wall_ms, step_ms)
+    qps = nq / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (the fused scan): algorithmic bytes per launch ----
+    # codes + landmark distance per scanned candidate, raw row + id per exact distance,
+    # the query itself and the k results; the table never leaves LDS.
+    alg_bytes = (chosen["n_scanned"] * (w.M + 4) + chosen["n_exact"] * (4 * w.d + 4) +
+                 nq * (4 * w.d + 8 * k))
+    scan_bytes = chosen["n_scanned"] * (w.M + 4)
+    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+    roofline = dict(bound="hbm", kernel="search_kernel<knn>", achieved=round(achieved, 1),
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
+                    traffic=None, kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
+                    scan_stream_gbs=round(scan_bytes / (scan_ms * 1e-3) / 1e9, 1),
+                    candidates_per_s=round(chosen["n_scanned"] / (scan_ms * 1e-3), 1))
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded query sample ----
+    cpu = None
+    if args.cpu_queries > 0:
+        from oracle import trim_oracle
+        nc = min(args.cpu_queries, nq)
+        h = lambda t: None if t is None else t.cpu().numpy()
+        oix = trim_oracle.Index(h(ix.base), h(ix.codes), h(ix.dlx), h(ix.codebooks), ids=h(ix.ids),
+                                list_offsets=h(ix.list_offsets))
+        qh = h(queries[:nc].contiguous())
+        t1 = time.perf_counter()
+        ph = trim_oracle.ivf_probe(qh, h(bw.centroids), w.nprobe) if w.nlist else None
+        ro = trim_oracle.search_knn(oix, qh, k, gamma, batch, ph)
+        cpu_s = time.perf_counter() - t1
+        same = bool(np.array_equal(ro["ids"], out[0][:nc].cpu().numpy()))
+        cpu = dict(value=round(nc / cpu_s, 1), unit="queries/s", cores=trim_oracle.num_threads(),
+                   kind="oracle", sample=f"first {nc} of {nq} queries, same index, gamma and batch; "
+                   f"{cpu_s:.1f} s; ids equal to the GPU's: {same}")
+
+    line = {
+        "metric": "queries/sec at recall@10>=0.95 (1 MI355X); pruning ratio; scan HBM GB/s",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n} base x {nq} queries, d={w.d}, PQ M={w.M}x256, "
+                               f"IVF nlist={w.nlist} nprobe={w.nprobe}, kNN k={k}",
+                   "gamma": gamma, "batch": batch, "recall_at_k": chosen["recall"],
+                   "recall_truth": f"exact kNN over all n for the first {nt} queries",
+                   "pruning_ratio": chosen["pruning_ratio"],
+                   "timed": "probe selection + fused table/scan/refine/select, inputs in HBM",
+                   "setup_s": round(setup_s, 1)},
+        "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -31,6 +31,7 @@
  * gamma > 0 on the paper's datasets cannot be pinned here: the datasets are absent.)
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -412,3 +413,6 @@ void trim_oracle_ivf_probe(const float *queries, int64_t nq, int d, const float 
         free(R);
     }
 }
+
+/* Threads the parallel loops above use (reported next to the CPU-baseline timing). */
+int trim_oracle_num_threads(void) { return omp_get_max_threads(); }

@@ -212,3 +212,7 @@ def ivf_probe(queries, centroids, nprobe):
                                 _p(centroids, f32), C.c_int(nlist), C.c_int(nprobe),
                                 _p(probes, i32))
     return probes
+
+
+def num_threads() -> int:
+    return int(lib().trim_oracle_num_threads())

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const float *__restrict__ b
             packed = 0;
         }
     }
-    if (valid) dlx[i] = __fsqrt_rn(tot);
+    if (valid) dlx[i] = trim::sqrt_rn(tot);
 }
 
 // ---- stand-alone distance table (Section 3.3, query-processing operation 1) ----

@@ -22,6 +22,11 @@ struct Hit {
     int32_t id;
 };
 
+// Correctly rounded binary32 square root.  (The __fsqrt_rn intrinsic maps to the bare
+// hardware approximation, which is within 1 ulp but not always the nearest value; sqrtf
+// is expanded by the compiler into the approximation plus a correction step.)
+__device__ __forceinline__ float sqrt_rn(float x) { return __builtin_sqrtf(x); }
+
 __device__ __forceinline__ bool hit_less(float d2a, int32_t ida, float d2b, int32_t idb) {
     return d2a < d2b || (d2a == d2b && ida < idb);
 }
@@ -65,7 +70,7 @@ __device__ __forceinline__ void build_table_rows(float *__restrict__ out,
 
 // Equation 3 from s = Gamma(l,q)^2 and b = Gamma(l,x).
 __device__ __forceinline__ float plb_from_s(float s, float b, float two_gamma) {
-    const float a = __fsqrt_rn(s);
+    const float a = sqrt_rn(s);
     const float e = a - b;
     const float t = two_gamma * a;
     return __builtin_fmaf(t, b, e * e);
@@ -127,23 +132,45 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[VEC], const uint8_t *__
     }
 }
 
-// s += table entries of subspaces [0, Mp) of one candidate (Mp % (4*VEC) == 0).
+// Early-abandon threshold on the running table sum (an exact shortcut, not part of the
+// paper's method).  Table entries are >= 0, so the binary32 running sum never decreases, and
+// for a = sqrt(s) >= b the computed bound of Equation 3 is >= (a - b)^2.  Hence, once
+// s > (b + sqrt(tau))^2 by a margin that covers all rounding, the finished bound is
+// certain to exceed tau and the remaining subspaces need not be read: the candidate is
+// pruned exactly as the full evaluation would prune it.  Margin: the computed chain
+// sqrt -> subtract -> square loses < 4 ulp (2.4e-7 relative); 1e-5 is used.  The floor keeps
+// the argument inside the normal range.  tau = +inf gives +inf (never abandons).
+__device__ __forceinline__ float abandon_threshold(float b, float sqrt_tau) {
+    const float r = b + sqrt_tau;
+    return fmaxf(r * r * 1.00001f, 1e-30f);
+}
+
+// s += table entries of subspaces [0, Mp) of one candidate (Mp % (4*VEC) == 0), stopping
+// early once s > thr (see abandon_threshold).  A stopped sum is still a valid lower
+// estimate of the full sum and still > thr.
 template <int VEC>
 __device__ __forceinline__ float table_sum(float s, const float *__restrict__ tab,
-                                           const uint8_t *__restrict__ code, int Mp) {
+                                           const uint8_t *__restrict__ code, int Mp, float thr) {
     constexpr int STEP = 4 * VEC;
-    int j = 0;
-    for (; j + 2 * STEP <= Mp; j += 2 * STEP) {
+    if (Mp == 2 * STEP) {
+        // whole row in two loads (e.g. 32 subspaces): fetch both, test in between
         uint32_t w0[VEC], w1[VEC];
-        load_codes<VEC>(w0, code + j);
-        load_codes<VEC>(w1, code + j + STEP);
-        s = gather_add<VEC>(s, tab + j * kC, w0);
-        s = gather_add<VEC>(s, tab + (j + STEP) * kC, w1);
+        load_codes<VEC>(w0, code);
+        load_codes<VEC>(w1, code + STEP);
+        s = gather_add<VEC>(s, tab, w0);
+        if (!(s > thr)) s = gather_add<VEC>(s, tab + STEP * kC, w1);
+        return s;
     }
-    for (; j < Mp; j += STEP) {
-        uint32_t w0[VEC];
-        load_codes<VEC>(w0, code + j);
-        s = gather_add<VEC>(s, tab + j * kC, w0);
+    uint32_t w[VEC];
+    load_codes<VEC>(w, code);
+    for (int j = 0; j < Mp; j += STEP) {
+        uint32_t nxt[VEC];
+        const bool more = j + STEP < Mp;
+        if (more) load_codes<VEC>(nxt, code + j + STEP);   // one chunk of lookahead
+        s = gather_add<VEC>(s, tab + j * kC, w);
+        if (!more || s > thr) break;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) w[v] = nxt[v];
     }
     return s;
 }

@@ -231,6 +231,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     while (c0 < c_end) {
         const int c1 = seed ? kseed : (c0 + a.batch < c_end ? c0 + a.batch : c_end);
         const float tau = ctl->tau;
+        const float sqrt_tau = trim::sqrt_rn(tau);
         const int iters = (c1 - c0 + T - 1) / T;
         // ---- filter: bound every candidate of the batch, compact the survivors ----
         const SegCursor cur0 = cur;
@@ -253,10 +254,15 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     if (seed) {
                         live = true;
                     } else {
+                        const float b = a.dlx[pos];
+                        const float thr = abandon_threshold(b, sqrt_tau);
                         float s = ph == 0 ? 0.0f : sd2[cl];
-                        s = table_sum<VEC>(s, tab, a.codes + (size_t)pos * a.M + ph * a.Mp, a.Mp);
+                        if (!(s > thr))
+                            s = table_sum<VEC>(s, tab, a.codes + (size_t)pos * a.M + ph * a.Mp,
+                                               a.Mp, thr);
                         if (last) {
-                            live = plb_from_s(s, a.dlx[pos], a.two_gamma) <= tau;
+                            // an abandoned sum is certainly pruned; otherwise s is complete
+                            live = !(s > thr) && plb_from_s(s, b, a.two_gamma) <= tau;
                         } else {
                             sd2[cl] = s;
                         }
