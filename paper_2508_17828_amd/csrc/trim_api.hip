@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <mutex>
 
 #include "trim_aux.h"
@@ -38,15 +39,32 @@ struct Plan {
     int P, Mp, vec;
     size_t lds;
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_plb, off_cnt, off_wq;
+    int span, wqcap;
 };
 
 // Decide table phases, block size and LDS layout for a search launch.
 // cap = survivor-list capacity (max(batch,k) for kNN, round size for range).
-bool make_plan(int d, int M, int nseg, int cap, int k, bool range, Plan *pl) {
+// batch = candidates per threshold update (range: = cap).  The span of candidates bounded
+// between two barriers is the largest multiple of batch up to kSpanTarget that fits
+// (at least one batch, at most kMaxBatchesPerSpan batches).
+constexpr int kSpanTarget = 4096;
+constexpr int kMaxBatchesPerSpan = 1024;
+
+bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
+    static const int span_target = getenv("TRIM_SPAN") ? atoi(getenv("TRIM_SPAN")) : kSpanTarget;
     if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
     const int nsegs = nseg > 0 ? nseg : 1;
+    int nbatch = span_target / batch;
+    if (nbatch < 1) nbatch = 1;
+    if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
+    const int span = nbatch * batch;
+    // two work-queue arrays of 16-bit entries; a wave's share of a span is rounded up to 64
+    const size_t wq_bytes = up16((size_t)(span + 64 * 16) * 2 * 2);
+    if (span > 65535) return false;
     size_t fixed = up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) + up16((size_t)nsegs * 4) +
-                   up16((size_t)cap * 4) * (range ? 3 : 2) + up16((size_t)k * 4) * 2 + up16(sizeof(Ctl));
+                   up16((size_t)cap * 4) * (range ? 3 : 2) + up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
+                   up16((size_t)span * 4) + up16((size_t)nbatch * 4) + wq_bytes;
     for (int P = 1; P <= M / 4; ++P) {
         if (M % P) continue;
         const int Mp = M / P;
@@ -63,13 +81,19 @@ bool make_plan(int d, int M, int nseg, int cap, int k, bool range, Plan *pl) {
         pl->off_spos = (uint32_t)off; off += up16((size_t)cap * 4);
         pl->off_sd2 = (uint32_t)off;  off += up16((size_t)cap * 4);
         pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
-        pl->off_rd2 = (uint32_t)off;  off += up16((size_t)k * 4);
-        pl->off_rid = (uint32_t)off;  off += up16((size_t)k * 4);
+        pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+        pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
         pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
+        pl->off_plb = (uint32_t)off;  off += up16((size_t)span * 4);
+        pl->off_cnt = (uint32_t)off;  off += up16((size_t)nbatch * 4);
+        pl->off_wq = (uint32_t)off;   off += wq_bytes;
+        pl->span = span;
         pl->lds = off;
         // block size: enough waves per CU whatever the LDS footprint allows
         const size_t per_cu = kLdsBytes / off;  // workgroups per CU by LDS
         pl->threads = per_cu >= 4 ? 256 : per_cu >= 2 ? 512 : 1024;
+        const int nwaves = pl->threads / 64;
+        pl->wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
         return true;
     }
     return false;
@@ -130,6 +154,8 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_q = pl.off_q; a.off_segp = pl.off_segp; a.off_segd = pl.off_segd;
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
+    a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
+    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap;
 }
 
 int fill_u32(uint32_t *p, size_t count, uint32_t v, hipStream_t st) {
@@ -185,7 +211,7 @@ extern "C" {
 
 int trim_shape_supported(int32_t d, int32_t M) {
     Plan pl;
-    return make_plan(d, M, 64, 1024, 10, true, &pl) ? 1 : 0;
+    return make_plan(d, M, 64, 2048, 2048, 10, true, &pl) ? 1 : 0;
 }
 
 int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
@@ -249,7 +275,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     if (survivor_mask && mask_words <= 0) return TRIM_INVALID_ARG;
     Plan pl;
     const int cap = batch > k ? batch : k;
-    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, cap, k, false, &pl))
+    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, cap, batch, k, false, &pl))
         return TRIM_UNSUPPORTED_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
@@ -306,7 +332,7 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
     if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return TRIM_WORKSPACE;
     Plan pl;
-    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, kRangeRound, 1, true, &pl))
+    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, kRangeRound, kRangeRound, 1, true, &pl))
         return TRIM_UNSUPPORTED_SHAPE;
 
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -411,5 +437,18 @@ const char *trim_strerror(int status) {
 int trim_last_hip_error(void) { return g_last_hip_error; }
 
 const char *trim_version(void) { return "0.1"; }
+
+#ifdef TRIM_PHASE_TIMING
+// Profiling builds only: read (and optionally clear) the per-phase cycle totals.
+int trim_debug_phase_ticks(unsigned long long *out8, int reset) {
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_phase_ticks), 8 * sizeof(unsigned long long)));
+    if (reset) {
+        unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_phase_ticks), z, sizeof(z)));
+    }
+    return TRIM_OK;
+}
+#endif
 
 }  // extern "C"

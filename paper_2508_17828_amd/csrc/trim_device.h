@@ -98,11 +98,47 @@ __device__ __forceinline__ float exact_d2_half(const float *__restrict__ row,
     return acc;
 }
 
+// Four rows at once (same arithmetic per row as exact_d2_half; the four loads of each step
+// are in flight together).
+__device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
+                                                 const float *__restrict__ r1,
+                                                 const float *__restrict__ r2,
+                                                 const float *__restrict__ r3,
+                                                 const float *__restrict__ q, int d, int lane32,
+                                                 float (&out)[4]) {
+    const float4 *rows[4] = {reinterpret_cast<const float4 *>(r0), reinterpret_cast<const float4 *>(r1),
+                             reinterpret_cast<const float4 *>(r2), reinterpret_cast<const float4 *>(r3)};
+    const float4 *q4 = reinterpret_cast<const float4 *>(q);
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const int ng = d >> 2;
+    for (int g = lane32; g < ng; g += 32) {
+        float4 xv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xv[u] = rows[u][g];
+        const float4 qv = q4[g];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float e;
+            e = qv.x - xv[u].x; acc[u] = __builtin_fmaf(e, e, acc[u]);
+            e = qv.y - xv[u].y; acc[u] = __builtin_fmaf(e, e, acc[u]);
+            e = qv.z - xv[u].z; acc[u] = __builtin_fmaf(e, e, acc[u]);
+            e = qv.w - xv[u].w; acc[u] = __builtin_fmaf(e, e, acc[u]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int h = 16; h >= 1; h >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], h, 32);
+        out[u] = acc[u];
+    }
+}
+
 // Sum of table entries selected by 4*VEC consecutive code bytes (VEC dwords), added to s
-// in subspace order.  tab points at the table row of the first of these subspaces.
+// in subspace order.  tab points at the table row of the first of these subspaces.  Stops
+// early once s > thr; a stopped sum is a lower estimate of the full sum that is still > thr.
 template <int VEC>
 __device__ __forceinline__ float gather_add(float s, const float *__restrict__ tab,
-                                            const uint32_t (&w)[VEC]) {
+                                            const uint32_t (&w)[VEC], float thr) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
 #pragma unroll
@@ -110,6 +146,8 @@ __device__ __forceinline__ float gather_add(float s, const float *__restrict__ t
             const uint32_t code = (w[v] >> (8 * b)) & 0xffu;
             s = s + tab[(v * 4 + b) * kC + code];
         }
+        // early abandon every 8 subspaces (see abandon_threshold)
+        if ((v & 1) == 1 && v + 1 < VEC && s > thr) return s;
     }
     return s;
 }
@@ -143,36 +181,6 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[VEC], const uint8_t *__
 __device__ __forceinline__ float abandon_threshold(float b, float sqrt_tau) {
     const float r = b + sqrt_tau;
     return fmaxf(r * r * 1.00001f, 1e-30f);
-}
-
-// s += table entries of subspaces [0, Mp) of one candidate (Mp % (4*VEC) == 0), stopping
-// early once s > thr (see abandon_threshold).  A stopped sum is still a valid lower
-// estimate of the full sum and still > thr.
-template <int VEC>
-__device__ __forceinline__ float table_sum(float s, const float *__restrict__ tab,
-                                           const uint8_t *__restrict__ code, int Mp, float thr) {
-    constexpr int STEP = 4 * VEC;
-    if (Mp == 2 * STEP) {
-        // whole row in two loads (e.g. 32 subspaces): fetch both, test in between
-        uint32_t w0[VEC], w1[VEC];
-        load_codes<VEC>(w0, code);
-        load_codes<VEC>(w1, code + STEP);
-        s = gather_add<VEC>(s, tab, w0);
-        if (!(s > thr)) s = gather_add<VEC>(s, tab + STEP * kC, w1);
-        return s;
-    }
-    uint32_t w[VEC];
-    load_codes<VEC>(w, code);
-    for (int j = 0; j < Mp; j += STEP) {
-        uint32_t nxt[VEC];
-        const bool more = j + STEP < Mp;
-        if (more) load_codes<VEC>(nxt, code + j + STEP);   // one chunk of lookahead
-        s = gather_add<VEC>(s, tab + j * kC, w);
-        if (!more || s > thr) break;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) w[v] = nxt[v];
-    }
-    return s;
 }
 
 }  // namespace trim

@@ -7,6 +7,18 @@
 
 #include "trim_device.h"
 
+// Optional per-phase cycle accounting (profiling builds only: -DTRIM_PHASE_TIMING).
+#ifdef TRIM_PHASE_TIMING
+__device__ unsigned long long g_phase_ticks[8];
+#define TRIM_TICK_INIT() unsigned long long _acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long _last = clock64();
+#define TRIM_TICK(i) do { if (threadIdx.x == 0) { unsigned long long _n = clock64(); _acc[i] += _n - _last; _last = _n; } } while (0)
+#define TRIM_TICK_FLUSH() do { if (threadIdx.x == 0) { for (int _i = 0; _i < 8; ++_i) atomicAdd(&g_phase_ticks[_i], _acc[_i]); } } while (0)
+#else
+#define TRIM_TICK_INIT()
+#define TRIM_TICK(i)
+#define TRIM_TICK_FLUSH()
+#endif
+
 namespace trim {
 
 enum Mode { kKnn = 0, kRange = 1 };
@@ -31,7 +43,8 @@ struct SearchArgs {
     // table phases: the M subspaces are handled Mp at a time (P = M / Mp passes per batch)
     int32_t P, Mp;
     // search parameters
-    int32_t k, batch;  // range: batch = survivor-list capacity per round
+    int32_t k, batch;  // range: batch = span = survivor-list capacity per round
+    int32_t span;      // candidates bounded between two barriers (a multiple of batch)
     float two_gamma;
     float radius2;
     // outputs
@@ -48,13 +61,14 @@ struct SearchArgs {
     int32_t *chunk_counts;   // [nq][nsplit]
     // LDS carve-up (byte offsets)
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_plb, off_cnt, off_wq;
+    int32_t wqcap;     // entries per wave in each of the two work-queue arrays
 };
 
 struct Ctl {
     int32_t total;       // candidates of this query (after clamping)
     int32_t nsurv;       // survivors appended in the current batch
     float tau;
-    int32_t rsize;
     int32_t nresult;     // range: results in this chunk
     int32_t nexact;
 };
@@ -91,42 +105,35 @@ struct SegCursor {
     }
 };
 
-// Insert (d2,id) into the sorted result set held in LDS; executed by one whole wave.
-// Returns the new size.
-__device__ __forceinline__ int result_insert(volatile float *rd2, volatile int32_t *rid,
-                                             int rsize, int k, float d2, int32_t id, int lane) {
-    // rank = number of entries e with !(item < R[e])
-    int rank = 0;
-    for (int e0 = 0; e0 < rsize; e0 += kWave) {
-        const int e = e0 + lane;
-        bool keep = false;
-        if (e < rsize) keep = !hit_less(d2, id, rd2[e], rid[e]);
-        rank += __popcll(__ballot(keep));
-    }
-    const int nsize = rsize < k ? rsize + 1 : k;
-    if (rank >= nsize) return rsize;  // not better than the current k-th
-    // shift R[rank .. nsize-2] up by one, highest chunk first
-    for (int e0 = ((nsize - 1) / kWave) * kWave; e0 >= 0 && e0 + kWave > rank; e0 -= kWave) {
-        const int e = e0 + lane;
-        const bool mv = e > rank && e < nsize;
-        float td2 = 0.0f;
-        int32_t tid = 0;
-        if (mv) { td2 = rd2[e - 1]; tid = rid[e - 1]; }
-        __builtin_amdgcn_wave_barrier();
-        if (mv) { rd2[e] = td2; rid[e] = tid; }
-        __builtin_amdgcn_wave_barrier();
-    }
-    if (lane == 0) { rd2[rank] = d2; rid[rank] = id; }
-    __builtin_amdgcn_wave_barrier();
-    return nsize;
-}
+constexpr int32_t kEmptyId = 0x7fffffff;  // id of an unused slot of R (its d2 is +inf)
 
-// Merge the refined survivors of a batch into R (wave 0 only) and publish tau.
-__device__ __forceinline__ void merge_batch(float *sd2, int32_t *sid, int ns, float *rd2_,
-                                            int32_t *rid_, Ctl *ctl, int k, int lane) {
-    volatile float *rd2 = rd2_;
-    volatile int32_t *rid = rid_;
-    int rsize = ctl->rsize;
+// Entries per lane that hold a result set of size k in one wave's registers.
+__host__ __device__ inline int result_slots(int k) { return k <= 64 ? 1 : k <= 128 ? 2 : k <= 256 ? 4 : 16; }
+
+// Merge the refined survivors of a batch into R and publish tau (the "result queue update"
+// of Section 4.2).  Executed by ONE whole wave.  R lives in LDS between calls (64*E
+// entries, ascending by (d2,id), unused slots = (+inf, kEmptyId)); during the call lane l
+// keeps entries l*E .. l*E+E-1 in registers, so an insertion is a ballot (rank), one
+// cross-lane shift and a few selects, with no LDS round trip.
+template <int E>
+__device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid, int ns,
+                                            float *rd2, int32_t *rid, Ctl *ctl, int k, int lane) {
+    float r_d2[E];
+    int32_t r_id[E];
+#pragma unroll
+    for (int s = 0; s < E; ++s) { r_d2[s] = rd2[lane * E + s]; r_id[s] = rid[lane * E + s]; }
+    const int kl = (k - 1) / E, ks = (k - 1) % E;  // lane and slot of the k-th entry
+    float t_d2;
+    int32_t t_id;
+    auto load_kth = [&]() {
+        float vd = r_d2[0];
+        int32_t vi = r_id[0];
+#pragma unroll
+        for (int s = 1; s < E; ++s) if (s == ks) { vd = r_d2[s]; vi = r_id[s]; }
+        t_d2 = __shfl(vd, kl);
+        t_id = __shfl(vi, kl);
+    };
+    load_kth();
     for (int i0 = 0; i0 < ns; i0 += kWave) {
         const int i = i0 + lane;
         bool pending = i < ns;
@@ -134,20 +141,51 @@ __device__ __forceinline__ void merge_batch(float *sd2, int32_t *sid, int ns, fl
         int32_t id = 0;
         if (pending) { d2 = sd2[i]; id = sid[i]; }
         for (;;) {
-            bool cand = pending;
-            if (cand && rsize >= k) cand = hit_less(d2, id, rd2[k - 1], rid[k - 1]);
-            const unsigned long long m = __ballot(cand);
+            const unsigned long long m = __ballot(pending && hit_less(d2, id, t_d2, t_id));
             if (m == 0) break;
             const int src = __ffsll((long long)m) - 1;
             const float xd2 = __shfl(d2, src);
             const int32_t xid = __shfl(id, src);
             if (lane == src) pending = false;
-            rsize = result_insert(rd2, rid, rsize, k, xd2, xid, lane);
+            // rank = number of entries that are not greater than the item (a prefix of R)
+            int rank = 0;
+#pragma unroll
+            for (int s = 0; s < E; ++s)
+                rank += __popcll(__ballot(!hit_less(xd2, xid, r_d2[s], r_id[s])));
+            const float c_d2 = __shfl_up(r_d2[E - 1], 1);
+            const int32_t c_id = __shfl_up(r_id[E - 1], 1);
+#pragma unroll
+            for (int s = E - 1; s >= 0; --s) {
+                const int g = lane * E + s;
+                const float p_d2 = s > 0 ? r_d2[s > 0 ? s - 1 : 0] : c_d2;
+                const int32_t p_id = s > 0 ? r_id[s > 0 ? s - 1 : 0] : c_id;
+                if (g == rank) { r_d2[s] = xd2; r_id[s] = xid; }
+                else if (g > rank) { r_d2[s] = p_d2; r_id[s] = p_id; }
+                if (g >= k) { r_d2[s] = __builtin_inff(); r_id[s] = kEmptyId; }
+            }
+            load_kth();
         }
     }
-    if (lane == 0) {
-        ctl->rsize = rsize;
-        ctl->tau = rsize >= k ? rd2[k - 1] : __builtin_inff();
+#pragma unroll
+    for (int s = 0; s < E; ++s) { rd2[lane * E + s] = r_d2[s]; rid[lane * E + s] = r_id[s]; }
+    if (lane == 0) ctl->tau = t_d2;  // +inf while R holds fewer than k entries
+}
+
+// The wide variants are kept out of line so that their registers do not add to the
+// pressure of the scan loop.
+__device__ __attribute__((noinline)) void merge_batch_wide(const float *sd2, const int32_t *sid, int ns,
+                                                           float *rd2, int32_t *rid, Ctl *ctl, int k,
+                                                           int lane) {
+    if (result_slots(k) == 4) merge_batch<4>(sd2, sid, ns, rd2, rid, ctl, k, lane);
+    else merge_batch<16>(sd2, sid, ns, rd2, rid, ctl, k, lane);
+}
+
+__device__ __forceinline__ void merge_dispatch(const float *sd2, const int32_t *sid, int ns, float *rd2,
+                                               int32_t *rid, Ctl *ctl, int k, int lane) {
+    switch (result_slots(k)) {
+        case 1: merge_batch<1>(sd2, sid, ns, rd2, rid, ctl, k, lane); break;
+        case 2: merge_batch<2>(sd2, sid, ns, rd2, rid, ctl, k, lane); break;
+        default: merge_batch_wide(sd2, sid, ns, rd2, rid, ctl, k, lane); break;
     }
 }
 
@@ -161,9 +199,12 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     int32_t *spos = reinterpret_cast<int32_t *>(smem + a.off_spos);  // survivor position -> id
     float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // partial s, then d2
     int32_t *sidx = reinterpret_cast<int32_t *>(smem + a.off_sidx);  // range: scan-order number
+    float *plbs = reinterpret_cast<float *>(smem + a.off_plb);       // [span] partial s, then bound
+    int *cnt0 = reinterpret_cast<int *>(smem + a.off_cnt);           // [span / batch]
     float *rd2 = reinterpret_cast<float *>(smem + a.off_rd2);
     int32_t *rid = reinterpret_cast<int32_t *>(smem + a.off_rid);
     Ctl *ctl = reinterpret_cast<Ctl *>(smem + a.off_ctl);
+    uint16_t *wq = reinterpret_cast<uint16_t *>(smem + a.off_wq);   // per-wave work queues
 
     const int tid = threadIdx.x;
     const int T = blockDim.x;
@@ -172,8 +213,11 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     const int split = blockIdx.x;
     const int nseg = a.nseg > 0 ? a.nseg : 1;
 
+    TRIM_TICK_INIT();
     // ---- prologue: query, segment table, table ----
     for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
+    if (MODE == kKnn)
+        for (int g = tid; g < kWave * result_slots(a.k); g += T) { rd2[g] = __builtin_inff(); rid[g] = kEmptyId; }
     for (int p = tid; p < nseg; p += T) {
         int64_t s = 0, e = a.n;
         if (a.nseg > 0) {
@@ -203,7 +247,6 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         }
         ctl->total = (int)run;
         ctl->nsurv = 0;
-        ctl->rsize = 0;
         ctl->tau = MODE == kRange ? a.radius2 : __builtin_inff();
         ctl->nresult = 0;
         ctl->nexact = 0;
@@ -220,112 +263,303 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     }
     SegCursor cur;
     cur.init(segp, segd);
+    (void)split;
 
     const int nhalf = T >> 5;
     const int half = tid >> 5;
     const int lane32 = tid & 31;
     const int kseed = MODE == kKnn ? (a.k < total ? a.k : total) : 0;
 
-    int c0 = c_begin;
-    bool seed = MODE == kKnn && kseed > 0;
-    while (c0 < c_end) {
-        const int c1 = seed ? kseed : (c0 + a.batch < c_end ? c0 + a.batch : c_end);
-        const float tau = ctl->tau;
-        const float sqrt_tau = trim::sqrt_rn(tau);
-        const int iters = (c1 - c0 + T - 1) / T;
-        // ---- filter: bound every candidate of the batch, compact the survivors ----
-        const SegCursor cur0 = cur;
-        for (int ph = 0; ph < a.P; ++ph) {
-            if (a.P > 1) {
-                __syncthreads();
-                fill_table(tab, a, q_lds, q, ph * a.Mp, a.Mp);
-                __syncthreads();
-                cur = cur0;
-            }
-            const bool last = ph == a.P - 1;
-            for (int it = 0; it < iters; ++it) {
-                const int cl = it * T + tid;  // batch-local number
-                const int c = c0 + cl;
-                const bool valid = c < c1;
-                bool live = false;
-                int pos = 0;
-                if (valid) {
-                    pos = cur.pos(c, segp, segd);
-                    if (seed) {
-                        live = true;
-                    } else {
-                        const float b = a.dlx[pos];
-                        const float thr = abandon_threshold(b, sqrt_tau);
-                        float s = ph == 0 ? 0.0f : sd2[cl];
-                        if (!(s > thr))
-                            s = table_sum<VEC>(s, tab, a.codes + (size_t)pos * a.M + ph * a.Mp,
-                                               a.Mp, thr);
-                        if (last) {
-                            // an abandoned sum is certainly pruned; otherwise s is complete
-                            live = !(s > thr) && plb_from_s(s, b, a.two_gamma) <= tau;
-                        } else {
-                            sd2[cl] = s;
-                        }
-                    }
-                }
-                if (last) {
-                    // wave-level compaction: ballot + prefix count, one LDS atomic per wave
-                    const unsigned long long m = __ballot(live);
-                    if (m != 0) {
-                        int basei = 0;
-                        if (lane == 0) basei = atomicAdd(&ctl->nsurv, __popcll(m));
-                        basei = __shfl(basei, 0);
-                        if (live) {
-                            const int slot = basei + __popcll(m & ((1ull << lane) - 1ull));
-                            spos[slot] = pos;
-                            if (MODE == kRange) sidx[slot] = c;
-                            if (a.mask) {
-                                const int64_t wi = c >> 5;
-                                if (wi < a.mask_words)
-                                    atomicOr(&a.mask[(size_t)q * a.mask_words + wi], 1u << (c & 31));
-                            }
-                        }
-                    }
-                }
+    // Storage position of the candidate with scan-order number c (binary search over the
+    // segment prefix; used only for the few candidates that survive).
+    auto locate = [&](int c) {
+        int lo = 0, hi = nseg - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (c >= segp[mid + 1]) lo = mid + 1; else hi = mid;
+        }
+        return c + segd[lo];
+    };
+
+    // Append the calling lane's candidate (if live) to the survivor list: wave ballot,
+    // prefix count, one LDS atomic per wave.  Must be called by whole waves.
+    auto append = [&](bool live, int c) {
+        const unsigned long long m = __ballot(live);
+        if (m == 0) return;
+        int basei = 0;
+        if (lane == 0) basei = atomicAdd(&ctl->nsurv, __popcll(m));
+        basei = __shfl(basei, 0);
+        if (live) {
+            const int slot = basei + __popcll(m & ((1ull << lane) - 1ull));
+            spos[slot] = locate(c);
+            if (MODE == kRange) sidx[slot] = c;
+            if (a.mask) {
+                const int64_t wi = c >> 5;
+                if (wi < a.mask_words)
+                    atomicOr(&a.mask[(size_t)q * a.mask_words + wi], 1u << (c & 31));
             }
         }
-        __syncthreads();
-        const int ns = ctl->nsurv;
-        if (ns > 0) {
-            // ---- refine: exact distances of the survivors, one half wave per row ----
-            for (int i = half; i < ns; i += nhalf) {
-                const int pos = spos[i];
-                const float d2 = exact_d2_half(a.base + (size_t)pos * a.d, q_lds, a.d, lane32);
-                if (lane32 == 0) {
+    };
+
+    // Refine the listed survivors (one half wave per raw row, two rows in flight), then
+    // select: merge into R and publish the new tau.  Called by the whole block after a
+    // barrier that made the survivor list visible; ends with a barrier.
+    auto refine_and_select = [&](int ns) {
+        for (int i = half; i < ns; i += 4 * nhalf) {
+            int idx[4], pos[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                idx[u] = i + u * nhalf;
+                ok[u] = idx[u] < ns;              // uniform within the half wave
+                pos[u] = spos[ok[u] ? idx[u] : i];
+            }
+            float d2[4];
+            exact_d2_half_x4(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
+                             a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d, q_lds,
+                             a.d, lane32, d2);
+            if (lane32 == 0) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (!ok[u]) continue;
                     if (MODE == kKnn) {
-                        sd2[i] = d2;
-                        spos[i] = a.ids ? a.ids[pos] : pos;
-                    } else if (d2 <= a.radius2) {
-                        const int c = sidx[i];
+                        sd2[idx[u]] = d2[u];
+                        spos[idx[u]] = a.ids ? a.ids[pos[u]] : pos[u];
+                    } else if (d2[u] <= a.radius2) {
+                        const int c = sidx[idx[u]];
                         atomicOr(&a.result_mask[(size_t)q * a.rmask_words + (c >> 5)], 1u << (c & 31));
                         atomicAdd(&ctl->nresult, 1);
                     }
                 }
             }
-            __syncthreads();
-            // ---- select: merge into R, publish the new tau ----
-            if (MODE == kKnn && tid < kWave) merge_batch(sd2, spos, ns, rd2, rid, ctl, a.k, lane);
-            if (tid == 0) {
-                ctl->nexact += ns;
-                ctl->nsurv = 0;
-            }
-            __syncthreads();
         }
-        c0 = c1;
-        seed = false;
+        __syncthreads();
+        TRIM_TICK(4);
+        if (MODE == kKnn && tid < kWave) merge_dispatch(sd2, spos, ns, rd2, rid, ctl, a.k, lane);
+        if (tid == 0) {
+            ctl->nexact += ns;
+            ctl->nsurv = 0;
+        }
+        __syncthreads();
+        TRIM_TICK(5);
+    };
+
+    TRIM_TICK(0);
+    // ---- seed: the first k candidates populate R, all with exact distances ----
+    if (kseed > 0) {
+        for (int i0 = 0; i0 < kseed; i0 += T) append(i0 + tid < kseed, i0 + tid);
+        __syncthreads();
+        refine_and_select(kseed);
     }
 
+    TRIM_TICK(1);
+    // ---- main loop over super-chunks of `span` candidates (a whole number of batches) ----
+    // Stage A bounds every candidate of the super-chunk with no barrier in between and
+    // keeps the bounds in LDS; it counts, per batch, the candidates that pass the
+    // threshold in force at the start of the super-chunk.  Thresholds only fall, so that
+    // set contains every later survivor, and batches whose count is zero are skipped
+    // outright.  Stage B walks the remaining batches in order with the up-to-date
+    // threshold, which reproduces the batch-by-batch rule exactly.
+    constexpr int H0 = VEC >= 2 ? 8 : 4;   // subspaces bounded in round 0
+    constexpr int U = 4;                   // candidates per lane in flight in round 0
+    const int wave = tid >> 6, nwaves = T >> 6;
+    // This wave's slice [lo, hi) of a span of the given length.
+    auto wave_slice = [&](int span_len, int &lo, int &hi) {
+        const int wchunk = ((span_len + nwaves - 1) / nwaves + kWave - 1) & ~(kWave - 1);
+        lo = wave * wchunk;
+        hi = lo + wchunk < span_len ? lo + wchunk : span_len;
+    };
+    // Issue the loads (first H0 code bytes, landmark distance) of U x 64 candidates.
+    auto issue_loads = [&](int c0n, int base, int hi, uint32_t (&w)[U][H0 / 4], float (&bq)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int cl = base + u * kWave + lane;
+            bq[u] = 0.0f;
+#pragma unroll
+            for (int v = 0; v < H0 / 4; ++v) w[u][v] = 0;
+            if (cl < hi) {
+                const int pos = cur.pos(c0n + cl, segp, segd);
+                load_codes<H0 / 4>(w[u], a.codes + (size_t)pos * a.M);
+                bq[u] = a.dlx[pos];
+            }
+        }
+    };
+    // The first round-0 step of the NEXT span is loaded into these registers while the
+    // current span is still being finished, so that its memory latency is hidden.
+    uint32_t pw[U][H0 / 4];
+    float pbq[U];
+    if (c_begin + kseed < c_end) {
+        const int c0n = c_begin + kseed;
+        int lo, hi;
+        wave_slice(c0n + a.span < c_end ? a.span : c_end - c0n, lo, hi);
+        issue_loads(c0n, lo, hi, pw, pbq);
+    }
+
+    for (int c0 = c_begin + kseed; c0 < c_end; c0 += a.span) {
+        const int span = c0 + a.span < c_end ? a.span : c_end - c0;
+        const int nb = (span + a.batch - 1) / a.batch;
+        __syncthreads();  // every thread is done reading the previous super-chunk's counts
+        for (int b = tid; b < nb; b += T) cnt0[b] = 0;
+        const float tau0 = ctl->tau;
+        const float sqrt_tau0 = trim::sqrt_rn(tau0);
+        __syncthreads();
+        // Rounds, wave by wave.  Each wave owns a contiguous slice of the span.  Round 0
+        // bounds ALL its candidates over the first H0 subspaces, branch-free, U x 64
+        // candidates in flight.  Whoever is not abandoned yet goes on the wave's own work
+        // queue; each later round takes that queue densely (one candidate per lane),
+        // continues the table sum over the next subspaces and queues what is still alive.
+        // Lanes stay full although most candidates stop after a few subspaces, and since a
+        // queue is private to its wave no block-wide barrier separates the rounds.  The
+        // partial sum of a queued candidate waits in plbs[].
+        int wlo, whi;
+        wave_slice(span, wlo, whi);
+        TRIM_TICK(2);
+        uint16_t *qin = wq + (size_t)wave * a.wqcap;
+        uint16_t *qout = wq + (size_t)(nwaves + wave) * a.wqcap;
+        int qn = 0;  // length of this wave's queue (same in every lane)
+        const unsigned long long lt_mask = (1ull << lane) - 1ull;
+        for (int ph = 0; ph < a.P; ++ph) {
+            if (a.P > 1) {
+                __syncthreads();
+                fill_table(tab, a, q_lds, q, ph * a.Mp, a.Mp);
+                __syncthreads();
+            }
+            const bool last_ph = ph == a.P - 1;
+            for (int h0 = 0; h0 < a.Mp;) {
+                int h1;
+                int qnext = 0;
+                if (ph == 0 && h0 == 0) {
+                    // ---- round 0 ----
+                    h1 = H0 < a.Mp ? H0 : a.Mp;
+                    const bool fin = last_ph && h1 == a.Mp;
+                    for (int base = wlo; base < whi; base += U * kWave) {
+                        float bq[U];
+                        uint32_t w[U][H0 / 4];
+                        if (base == wlo) {  // loaded ahead of time
+#pragma unroll
+                            for (int u = 0; u < U; ++u) {
+                                bq[u] = pbq[u];
+#pragma unroll
+                                for (int v = 0; v < H0 / 4; ++v) w[u][v] = pw[u][v];
+                            }
+                        } else {
+                            issue_loads(c0, base, whi, w, bq);
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const float sum = gather_add<H0 / 4>(0.0f, tab, w[u], __builtin_inff());
+                            const int cl = base + u * kWave + lane;
+                            const float thr = abandon_threshold(bq[u], sqrt_tau0);
+                            const bool valid = cl < whi;
+                            bool alive = valid && !(sum > thr);
+                            float keep = alive ? sum : __builtin_inff();
+                            if (fin && alive) {  // the whole bound fits in round 0
+                                keep = plb_from_s(sum, bq[u], a.two_gamma);
+                                if (keep <= tau0) atomicAdd(&cnt0[cl / a.batch], 1);
+                                alive = false;
+                            }
+                            if (valid) plbs[cl] = keep;
+                            const unsigned long long m = __ballot(alive);
+                            if (alive) qout[qnext + __popcll(m & lt_mask)] = (uint16_t)cl;
+                            qnext += __popcll(m);
+                        }
+                    }
+                    TRIM_TICK(6);
+                    if (c0 + a.span < c_end) {  // start loading the next span's first step
+                        const int c0n = c0 + a.span;
+                        int lo, hi;
+                        wave_slice(c0n + a.span < c_end ? a.span : c_end - c0n, lo, hi);
+                        issue_loads(c0n, lo, hi, pw, pbq);
+                    }
+                } else {
+                    // ---- later rounds: dense over the wave's queue ----
+                    h1 = h0 + 32 < a.Mp ? h0 + 32 : a.Mp;
+                    const bool fin = last_ph && h1 == a.Mp;
+                    for (int i0 = 0; i0 < qn; i0 += kWave) {
+                        const int i = i0 + lane;
+                        bool alive = i < qn;
+                        int cl = 0;
+                        if (alive) {
+                            cl = qin[i];
+                            const int pos = locate(c0 + cl);
+                            const float b = a.dlx[pos];
+                            const float thr = abandon_threshold(b, sqrt_tau0);
+                            const uint8_t *cp = a.codes + (size_t)pos * a.M + ph * a.Mp;
+                            float sum = plbs[cl];
+                            int j = h0;
+                            while (j < h1) {  // widest aligned load that fits, test after each
+                                if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
+                                    uint32_t w[4];
+                                    load_codes<4>(w, cp + j);
+                                    sum = gather_add<4>(sum, tab + j * kC, w, thr);
+                                    j += 16;
+                                } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= h1) {
+                                    uint32_t w[2];
+                                    load_codes<2>(w, cp + j);
+                                    sum = gather_add<2>(sum, tab + j * kC, w, thr);
+                                    j += 8;
+                                } else {
+                                    uint32_t w[1];
+                                    load_codes<1>(w, cp + j);
+                                    sum = gather_add<1>(sum, tab + j * kC, w, thr);
+                                    j += 4;
+                                }
+                                if (sum > thr) break;
+                            }
+                            if (sum > thr) {
+                                plbs[cl] = __builtin_inff();
+                                alive = false;
+                            } else if (fin) {
+                                const float g = plb_from_s(sum, b, a.two_gamma);
+                                plbs[cl] = g;
+                                if (g <= tau0) atomicAdd(&cnt0[cl / a.batch], 1);
+                                alive = false;
+                            } else {
+                                plbs[cl] = sum;
+                            }
+                        }
+                        const unsigned long long m = __ballot(alive);
+                        if (alive) qout[qnext + __popcll(m & lt_mask)] = (uint16_t)cl;
+                        qnext += __popcll(m);
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                TRIM_TICK(7);
+                qn = qnext;
+                uint16_t *t = qin; qin = qout; qout = t;
+                h0 = h1;
+                if (qn == 0) break;  // this wave has nobody left in this phase
+            }
+        }
+        __syncthreads();
+        TRIM_TICK(2);
+        for (int b = 0; b < nb; ++b) {
+            if (cnt0[b] == 0) continue;  // same value for every thread: no barrier needed
+            const float tau = ctl->tau;
+            const int l0 = b * a.batch;
+            const int blen = l0 + a.batch < span ? a.batch : span - l0;
+            for (int i0 = 0; i0 < blen; i0 += T) {
+                const int i = i0 + tid;
+                const bool live = i < blen && plbs[l0 + i] <= tau;
+                append(live, c0 + l0 + i);
+            }
+            __syncthreads();
+            const int ns = ctl->nsurv;
+            __syncthreads();  // nobody appends for the next batch before everyone has read ns
+            TRIM_TICK(3);
+            if (ns > 0) refine_and_select(ns);
+        }
+        TRIM_TICK(3);
+    }
+
+    TRIM_TICK(6);
     // ---- epilogue ----
     if (MODE == kKnn) {
-        const int rsize = ctl->rsize;
         for (int i = tid; i < a.k; i += T) {
-            a.out_ids[(size_t)q * a.k + i] = i < rsize ? rid[i] : -1;
-            a.out_d2[(size_t)q * a.k + i] = i < rsize ? rd2[i] : __builtin_inff();
+            const int32_t id = rid[i];
+            a.out_ids[(size_t)q * a.k + i] = id == kEmptyId ? -1 : id;
+            a.out_d2[(size_t)q * a.k + i] = rd2[i];
         }
         if (tid == 0) {
             if (a.n_scanned) a.n_scanned[q] = total;
@@ -336,6 +570,8 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         if (a.n_scanned && split == 0) a.n_scanned[q] = total;
         if (a.n_exact && ctl->nexact) atomicAdd(&a.n_exact[q], ctl->nexact);
     }
+    TRIM_TICK(7);
+    TRIM_TICK_FLUSH();
 }
 
 }  // namespace trim
