@@ -124,6 +124,9 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
  * queries [nq][d] device.  lut: device [nq][M][256] or NULL (tables are then built inside
  * the kernel from index->codebooks).  cand: host struct or NULL.  1 <= k <= TRIM_MAX_K,
  * 1 <= batch <= TRIM_MAX_BATCH, gamma >= 0.
+ * query_order: device [nq] or NULL; a permutation of 0..nq-1 giving the order in which
+ * queries are handed to the GPU (see trim_query_order).  It changes scheduling only: every
+ * query's results are written at its own row and do not depend on the order.
  * out_ids [nq][k], out_d2 [nq][k] device: ascending by (d2, id); rows with fewer than k
  * candidates are padded with id -1, d2 +inf.
  * stats: host struct or NULL.  survivor_mask: device or NULL; if given it must hold
@@ -133,8 +136,9 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
  */
 int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
                     const float *lut, const trim_candidates *cand, int32_t k, float gamma,
-                    int32_t batch, int32_t *out_ids, float *out_d2, const trim_stats *stats,
-                    uint32_t *survivor_mask, int64_t mask_words, void *stream);
+                    int32_t batch, const int32_t *query_order, int32_t *out_ids, float *out_d2,
+                    const trim_stats *stats, uint32_t *survivor_mask, int64_t mask_words,
+                    void *stream);
 
 /*
  * Approximate range search by the scan of Section 4.2 (problem statement: Section 2.1):
@@ -169,6 +173,15 @@ size_t trim_range_workspace_bytes(int64_t nq, int64_t max_candidates);
  */
 int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *centroids,
                    int32_t nlist, int32_t nprobe, int32_t *probes_out, void *stream);
+
+/*
+ * Scheduling aid for inverted-file search (the probed lists of Section 6.1): order_out [nq]
+ * device = the queries sorted by their first probed list, ties by query index.  Queries that
+ * scan the same lists then run next to each other and share the GPU's caches.
+ * probes [nq][nprobe] device as produced by trim_ivf_probe.
+ */
+int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t *order_out,
+                     void *stream);
 
 /* Text for a trim_status. */
 const char *trim_strerror(int status);

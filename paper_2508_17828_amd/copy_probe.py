@@ -1,4 +1,4 @@
-"""A plain device-to-device copy of known size.
+"""A plain elementwise pass of known size (dst = src + 1: SIZE bytes read, SIZE written).
 
 Run under `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE) to learn what those counters read
 for a kernel whose HBM traffic is known exactly (SIZE bytes read, SIZE bytes written); the
@@ -17,7 +17,7 @@ def main():
     dst = torch.empty_like(src)
     torch.cuda.synchronize()
     for _ in range(reps):
-        dst.copy_(src)
+        torch.add(src, 1.0, out=dst)
     torch.cuda.synchronize()
     print(f"copied {SIZE} bytes x {reps}")
 

@@ -40,7 +40,7 @@ struct Plan {
     size_t lds;
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
-    int span, wqcap;
+    int span, wqcap, cruise, poss_cap;
 };
 
 // Decide table phases, block size and LDS layout for a search launch.
@@ -59,12 +59,17 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     if (nbatch < 1) nbatch = 1;
     if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
     const int span = nbatch * batch;
+    // cruise stretches: up to 61440 candidates (16-bit queue entries) and 1024 batches
+    int cruise = 61440 < 1024 * (int64_t)batch ? 61440 : 1024 * batch;
+    cruise = cruise / batch * batch;
+    if (range || cruise < 2 * span) cruise = 0;
+    const int ncnt = cruise / batch > nbatch ? cruise / batch : nbatch;
     // two work-queue arrays of 16-bit entries; a wave's share of a span is rounded up to 64
     const size_t wq_bytes = up16((size_t)(span + 64 * 16) * 2 * 2);
     if (span > 65535) return false;
     size_t fixed = up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) + up16((size_t)nsegs * 4) +
                    up16((size_t)cap * 4) * (range ? 3 : 2) + up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
-                   up16((size_t)span * 4) + up16((size_t)nbatch * 4) + wq_bytes;
+                   up16((size_t)span * 4) + up16((size_t)ncnt * 4) + wq_bytes;
     for (int P = 1; P <= M / 4; ++P) {
         if (M % P) continue;
         const int Mp = M / P;
@@ -85,7 +90,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
         pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
         pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
         pl->off_plb = (uint32_t)off;  off += up16((size_t)span * 4);
-        pl->off_cnt = (uint32_t)off;  off += up16((size_t)nbatch * 4);
+        pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
         pl->off_wq = (uint32_t)off;   off += wq_bytes;
         pl->span = span;
         pl->lds = off;
@@ -94,6 +99,9 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
         pl->threads = per_cu >= 4 ? 256 : per_cu >= 2 ? 512 : 1024;
         const int nwaves = pl->threads / 64;
         pl->wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
+        pl->cruise = P == 1 ? cruise : 0;  // table phases need block-wide barriers
+        pl->poss_cap = span / 2;
+        if ((size_t)nwaves * kRing * 2 > wq_bytes) pl->cruise = 0;
         return true;
     }
     return false;
@@ -137,7 +145,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
                  uint32_t *mask, int64_t mask_words, const Plan &pl) {
     a.base = ix->base; a.codes = ix->codes; a.dlx = ix->dlx; a.ids = ix->ids;
     a.codebooks = ix->codebooks; a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
-    a.queries = queries; a.lut = lut;
+    a.queries = queries; a.lut = lut; a.order = nullptr;
     a.list_offsets = cand ? cand->list_offsets : nullptr;
     a.probes = cand ? cand->probes : nullptr;
     a.nlist = cand ? cand->nlist : 0;
@@ -155,7 +163,8 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
     a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
-    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap;
+    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap;
+    if (getenv("TRIM_NO_CRUISE")) a.cruise = 0;
 }
 
 int fill_u32(uint32_t *p, size_t count, uint32_t v, hipStream_t st) {
@@ -260,12 +269,13 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
 
 int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
                     const float *lut, const trim_candidates *cand, int32_t k, float gamma,
-                    int32_t batch, int32_t *out_ids, float *out_d2, const trim_stats *stats,
-                    uint32_t *survivor_mask, int64_t mask_words, void *stream) {
+                    int32_t batch, const int32_t *query_order, int32_t *out_ids, float *out_d2,
+                    const trim_stats *stats, uint32_t *survivor_mask, int64_t mask_words,
+                    void *stream) {
     int rc = check_index(index);
     if (rc) return rc;
     if ((rc = check_cand(cand))) return rc;
-    if (nq < 0 || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
+    if (nq < 0 || nq > 0x7fffffff - 8 || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
         return TRIM_INVALID_ARG;
     if (!(gamma >= 0.0f) || std::isinf(gamma)) return TRIM_INVALID_ARG;
     if (nq == 0) return TRIM_OK;
@@ -284,18 +294,9 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     a.k = k; a.batch = batch; a.radius2 = 0.0f;
     a.out_ids = out_ids; a.out_d2 = out_d2;
     a.chunk = 0; a.nsplit = 1;
-    for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
-        const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
-        SearchArgs b = a;
-        b.queries = queries + (size_t)q0 * index->d;
-        if (lut) b.lut = lut + (size_t)q0 * index->M * kC;
-        if (b.probes) b.probes += (size_t)q0 * b.nseg;
-        b.out_ids += (size_t)q0 * k; b.out_d2 += (size_t)q0 * k;
-        if (b.n_scanned) b.n_scanned += q0;
-        if (b.n_exact) b.n_exact += q0;
-        if (b.mask) b.mask += (size_t)q0 * mask_words;
-        if ((rc = launch_search<kKnn>(b, pl, dim3(1, (unsigned)cnt), st))) return rc;
-    }
+    a.nq = nq; a.order = query_order;
+    const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
+    if ((rc = launch_search<kKnn>(a, pl, dim3((unsigned)slots, 1), st))) return rc;
     return TRIM_OK;
 }
 
@@ -312,7 +313,7 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
     int rc = check_index(index);
     if (rc) return rc;
     if ((rc = check_cand(cand))) return rc;
-    if (nq < 0 || nq > 65535ll * 65535ll || capacity < 0) return TRIM_INVALID_ARG;
+    if (nq < 0 || nq > 0x7fffffff - 8 || capacity < 0) return TRIM_INVALID_ARG;
     if (!(gamma >= 0.0f) || std::isinf(gamma) || !(radius >= 0.0f)) return TRIM_INVALID_ARG;
     if (!out_offsets) return TRIM_INVALID_ARG;
     if (capacity > 0 && (!out_ids || !out_d2)) return TRIM_INVALID_ARG;
@@ -367,36 +368,18 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
     f.off_list = (uint32_t)off; off += 2048 * 4;
     const size_t fill_lds = off;
 
-    for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
-        const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
-        SearchArgs b = a;
-        b.queries = queries + (size_t)q0 * index->d;
-        if (lut) b.lut = lut + (size_t)q0 * index->M * kC;
-        if (b.probes) b.probes += (size_t)q0 * b.nseg;
-        if (b.n_scanned) b.n_scanned += q0;
-        if (b.n_exact) b.n_exact += q0;
-        if (b.mask) b.mask += (size_t)q0 * mask_words;
-        b.result_mask += (size_t)q0 * L.rmask_words;
-        b.chunk_counts += (size_t)q0 * L.nsplit;
-        if ((rc = launch_search<kRange>(b, pl, dim3((unsigned)L.nsplit, (unsigned)cnt), st))) return rc;
-    }
+    a.nq = nq;
+    const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
+    if ((rc = launch_search<kRange>(a, pl, dim3((unsigned)slots, (unsigned)L.nsplit), st))) return rc;
     hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(1024), 0, st, counts, nq, L.nsplit, cbase,
                        out_offsets, required);
     HIP_TRY(hipGetLastError());
     if (capacity > 0) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(range_fill_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)fill_lds));
-        for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
-            const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
-            RangeFillArgs g = f;
-            g.queries = queries + (size_t)q0 * index->d;
-            if (g.probes) g.probes += (size_t)q0 * g.nseg;
-            g.result_mask += (size_t)q0 * L.rmask_words;
-            g.chunk_base += (size_t)q0 * L.nsplit;
-            hipLaunchKernelGGL(range_fill_kernel, dim3((unsigned)L.nsplit, (unsigned)cnt), dim3(256),
-                               fill_lds, st, g);
-            HIP_TRY(hipGetLastError());
-        }
+        hipLaunchKernelGGL(range_fill_kernel, dim3((unsigned)nq, (unsigned)L.nsplit), dim3(256), fill_lds,
+                           st, f);
+        HIP_TRY(hipGetLastError());
     }
     return TRIM_OK;
 }
@@ -419,6 +402,25 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
     const int threads = npow2 >= 2048 ? 1024 : 256;
     hipLaunchKernelGGL(ivf_probe_kernel, dim3((unsigned)nq), dim3(threads), lds, st, queries, d,
                        centroids, nlist, npow2, nprobe, probes_out);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t *order_out,
+                     void *stream) {
+    if (nq < 0 || nq > 0x7fffffff - 8 || nprobe <= 0) return TRIM_INVALID_ARG;
+    if (nq == 0) return TRIM_OK;
+    if (!probes || !order_out) return TRIM_INVALID_ARG;
+    const int slab = 16384;
+    int npow2 = 1;
+    while (npow2 < (nq < slab ? (int)nq : slab)) npow2 <<= 1;
+    const size_t lds = (size_t)npow2 * 8;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(query_order_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(query_order_kernel, dim3((unsigned)((nq + slab - 1) / slab)),
+                       dim3(npow2 >= 2048 ? 1024 : 256), lds, st, probes, nq, nprobe, slab, npow2,
+                       order_out);
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }

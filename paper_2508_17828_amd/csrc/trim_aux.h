@@ -146,8 +146,8 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
 
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & (kWave - 1);
-    const int64_t q = blockIdx.y;
-    const int split = blockIdx.x;
+    const int64_t q = blockIdx.x;
+    const int split = blockIdx.y;
     const int nseg = a.nseg > 0 ? a.nseg : 1;
 
     for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
@@ -266,6 +266,40 @@ __global__ __launch_bounds__(1024) void ivf_probe_kernel(const float *__restrict
         }
     }
     for (int p = tid; p < nprobe; p += T) probes[(size_t)q * nprobe + p] = (int32_t)(keys[p] & 0xffffffffu);
+}
+
+// ---- processing order: queries sorted by their first probed list (ties by query index) ----
+// One workgroup sorts a slab of up to `slab` queries (bitonic sort of 64-bit keys in LDS).
+__global__ __launch_bounds__(1024) void query_order_kernel(const int32_t *__restrict__ probes,
+                                                           int64_t nq, int nprobe, int slab,
+                                                           int npow2, int32_t *__restrict__ order) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int64_t q0 = (int64_t)blockIdx.x * slab;
+    const int cnt = (int)(nq - q0 < slab ? nq - q0 : slab);
+    for (int i = tid; i < npow2; i += T) {
+        unsigned long long key = ~0ull;
+        if (i < cnt) {
+            const uint32_t l = (uint32_t)probes[(size_t)(q0 + i) * nprobe];
+            key = ((unsigned long long)l << 32) | (uint32_t)i;
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    for (int size = 2; size <= npow2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < npow2 >> 1; i += T) {
+                const int lo = ((i / stride) * stride << 1) + (i % stride);
+                const int hi = lo + stride;
+                const bool up = ((lo & size) == 0);
+                const unsigned long long x = keys[lo], y = keys[hi];
+                if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = tid; i < cnt; i += T) order[q0 + i] = (int32_t)(q0 + (int64_t)(keys[i] & 0xffffffffu));
 }
 
 }  // namespace trim

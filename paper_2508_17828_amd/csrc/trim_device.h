@@ -61,7 +61,27 @@ __device__ __forceinline__ void build_table_rows(float *__restrict__ out,
                                                  const float *__restrict__ q,
                                                  const float *__restrict__ codebooks, int dsub,
                                                  int j0, int nj) {
-    for (int e = threadIdx.x; e < nj * kC; e += blockDim.x) {
+    const int T = blockDim.x;
+    int e = threadIdx.x;
+    if (dsub == 4) {  // four entries per step so that four centroid loads are in flight
+        for (; e + 3 * T < nj * kC; e += 4 * T) {
+            float4 cv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                cv[u] = *reinterpret_cast<const float4 *>(codebooks + ((size_t)j0 * kC + e + u * T) * 4);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float4 xv = *reinterpret_cast<const float4 *>(q + (j0 + ((e + u * T) >> 8)) * 4);
+                float acc = 0.0f, t;
+                t = xv.x - cv[u].x; acc = __builtin_fmaf(t, t, acc);
+                t = xv.y - cv[u].y; acc = __builtin_fmaf(t, t, acc);
+                t = xv.z - cv[u].z; acc = __builtin_fmaf(t, t, acc);
+                t = xv.w - cv[u].w; acc = __builtin_fmaf(t, t, acc);
+                out[e + u * T] = acc;
+            }
+        }
+    }
+    for (; e < nj * kC; e += T) {
         const int j = j0 + (e >> 8);
         const int c = e & (kC - 1);
         out[e] = subvec_sqdist(q + j * dsub, codebooks + ((size_t)j * kC + c) * dsub, dsub);

@@ -22,6 +22,7 @@ __device__ unsigned long long g_phase_ticks[8];
 namespace trim {
 
 enum Mode { kKnn = 0, kRange = 1 };
+constexpr int kXcds = 8;  // accelerator dies of an MI355X, each with its own L2
 
 struct SearchArgs {
     // index (Section 3.3 preprocessing output)
@@ -32,8 +33,10 @@ struct SearchArgs {
     const float *codebooks;
     int64_t n;
     int32_t d, M, dsub;
-    // queries and (optional) prebuilt tables
+    // queries, optional processing order, optional prebuilt tables
     const float *queries;
+    int64_t nq;
+    const int32_t *order;
     const float *lut;
     // candidate structure (nseg == 0: all n positions)
     const int64_t *list_offsets;
@@ -63,6 +66,8 @@ struct SearchArgs {
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int32_t wqcap;     // entries per wave in each of the two work-queue arrays
+    int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
+    int32_t poss_cap;  // capacity of the possibles list
 };
 
 struct Ctl {
@@ -71,7 +76,9 @@ struct Ctl {
     float tau;
     int32_t nresult;     // range: results in this chunk
     int32_t nexact;
+    int32_t nposs;       // cruise: number of possibles found in the stretch
 };
+constexpr int kRing = 512;  // entries of a wave's ring queue in cruise mode
 
 // Load or build the table rows [j0, j0+nj) of query q into LDS.
 __device__ __forceinline__ void fill_table(float *tab, const SearchArgs &a, const float *q_lds,
@@ -200,7 +207,9 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // partial s, then d2
     int32_t *sidx = reinterpret_cast<int32_t *>(smem + a.off_sidx);  // range: scan-order number
     float *plbs = reinterpret_cast<float *>(smem + a.off_plb);       // [span] partial s, then bound
-    int *cnt0 = reinterpret_cast<int *>(smem + a.off_cnt);           // [span / batch]
+    int *cnt0 = reinterpret_cast<int *>(smem + a.off_cnt);           // per-batch counts
+    int *poss_cl = reinterpret_cast<int *>(smem + a.off_plb);        // cruise: possibles, aliasing
+    float *poss_g = plbs + a.poss_cap;                               //   plbs ([poss_cap] each)
     float *rd2 = reinterpret_cast<float *>(smem + a.off_rd2);
     int32_t *rid = reinterpret_cast<int32_t *>(smem + a.off_rid);
     Ctl *ctl = reinterpret_cast<Ctl *>(smem + a.off_ctl);
@@ -209,8 +218,15 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     const int tid = threadIdx.x;
     const int T = blockDim.x;
     const int lane = tid & (kWave - 1);
-    const int64_t q = blockIdx.y;
-    const int split = blockIdx.x;
+    // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of the
+    // (optionally sorted) query order so that concurrent workgroups of an XCD scan the same
+    // lists and share its L2.
+    const int64_t per_xcd = (a.nq + kXcds - 1) / kXcds;
+    const int64_t slot = (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (slot >= a.nq) return;  // the whole workgroup leaves together
+    const int64_t q = a.order ? a.order[slot] : slot;
+    if (q < 0 || q >= a.nq) return;  // not a permutation entry: nothing is done for it
+    const int split = blockIdx.y;
     const int nseg = a.nseg > 0 ? a.nseg : 1;
 
     TRIM_TICK_INIT();
@@ -384,24 +400,156 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
             }
         }
     };
-    // The first round-0 step of the NEXT span is loaded into these registers while the
-    // current span is still being finished, so that its memory latency is hidden.
-    uint32_t pw[U][H0 / 4];
-    float pbq[U];
-    if (c_begin + kseed < c_end) {
-        const int c0n = c_begin + kseed;
-        int lo, hi;
-        wave_slice(c0n + a.span < c_end ? a.span : c_end - c0n, lo, hi);
-        issue_loads(c0n, lo, hi, pw, pbq);
-    }
-
-    for (int c0 = c_begin + kseed; c0 < c_end; c0 += a.span) {
-        const int span = c0 + a.span < c_end ? a.span : c_end - c0;
-        const int nb = (span + a.batch - 1) / a.batch;
-        __syncthreads();  // every thread is done reading the previous super-chunk's counts
-        for (int b = tid; b < nb; b += T) cnt0[b] = 0;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
+    for (int c0 = c_begin + kseed; c0 < c_end;) {
+        __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
         const float sqrt_tau0 = trim::sqrt_rn(tau0);
+
+        // ---- cruise: once tau is finite, bound a long stretch of candidates with no block-wide
+        // barrier at all.  Every wave runs its own software pipeline over interleaved blocks of
+        // U x 64 candidates: the next block's loads are in flight while the current block is
+        // bounded over the first H0 subspaces; the few candidates not abandoned there go on
+        // the wave's ring queue and are finished 64 at a time.  Only candidates whose bound
+        // passes tau0 ("possibles": a superset of all later survivors, since thresholds only
+        // fall) are kept, as (number, bound) pairs in a shared list; the batches are then
+        // replayed in order over that list.  If the list overflows, nothing has been
+        // committed: the stretch is redone span by span below.
+        // (The first span after the seed is always taken span by span: it is what makes tau tight.)
+        if (cruise > 0 && c0 > c_begin + kseed && tau0 < __builtin_inff() && c_end - c0 > a.span) {
+            const int S = c0 + cruise < c_end ? cruise : c_end - c0;
+            const int nb = (S + a.batch - 1) / a.batch;
+            for (int b = tid; b < nb; b += T) cnt0[b] = 0;
+            if (tid == 0) ctl->nposs = 0;
+            __syncthreads();
+            {
+                uint16_t *ring = wq + (size_t)wave * kRing;
+                int head = 0, count = 0;  // same in every lane of the wave
+                // A drain takes up to 64 queued candidates, one per lane.  It is split in two so
+                // that its loads are in flight while the next block is bounded: drain_issue pops
+                // the entries and starts the loads of the landmark distance and the first code
+                // chunk; drain_finish redoes the table sum from the start (now with a test every
+                // 8 subspaces), evaluates Equation 3 and records the candidate if it passes tau0.
+                constexpr int DV = VEC;  // dwords of the first chunk
+                int d_n = 0, d_cl = 0, d_pos = 0;
+                float d_b = 0.0f;
+                uint32_t d_w[DV];
+                auto drain_issue = [&]() {
+                    d_n = count < kWave ? count : kWave;
+                    if (lane < d_n) {
+                        d_cl = ring[(head + lane) & (kRing - 1)];
+                        d_pos = locate(c0 + d_cl);
+                        d_b = a.dlx[d_pos];
+                        load_codes<DV>(d_w, a.codes + (size_t)d_pos * a.M);
+                    }
+                    head = (head + d_n) & (kRing - 1);
+                    count -= d_n;
+                };
+                auto drain_finish = [&]() {
+                    if (lane < d_n) {
+                        const float thr = abandon_threshold(d_b, sqrt_tau0);
+                        const uint8_t *cp = a.codes + (size_t)d_pos * a.M;
+                        float sum = gather_add<DV>(0.0f, tab, d_w, thr);
+                        int j = 4 * DV;
+                        while (j < a.M && !(sum > thr)) {  // widest aligned load that fits
+                            if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
+                                uint32_t w[4];
+                                load_codes<4>(w, cp + j);
+                                sum = gather_add<4>(sum, tab + j * kC, w, thr);
+                                j += 16;
+                            } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= a.M) {
+                                uint32_t w[2];
+                                load_codes<2>(w, cp + j);
+                                sum = gather_add<2>(sum, tab + j * kC, w, thr);
+                                j += 8;
+                            } else {
+                                uint32_t w[1];
+                                load_codes<1>(w, cp + j);
+                                sum = gather_add<1>(sum, tab + j * kC, w, thr);
+                                j += 4;
+                            }
+                        }
+                        if (!(sum > thr)) {
+                            const float g = plb_from_s(sum, d_b, a.two_gamma);
+                            if (g <= tau0) {
+                                const int at = atomicAdd(&ctl->nposs, 1);
+                                if (at < a.poss_cap) { poss_cl[at] = d_cl; poss_g[at] = g; }
+                                atomicAdd(&cnt0[d_cl / a.batch], 1);
+                            }
+                        }
+                    }
+                    d_n = 0;
+                };
+                const int nblk = (S + U * kWave - 1) / (U * kWave);
+                uint32_t pw[U][H0 / 4];
+                float pbq[U];
+                int blk = wave;
+                if (blk < nblk) issue_loads(c0, blk * U * kWave, S, pw, pbq);
+                for (; blk < nblk; blk += nwaves) {
+                    uint32_t w[U][H0 / 4];
+                    float bq[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        bq[u] = pbq[u];
+#pragma unroll
+                        for (int v = 0; v < H0 / 4; ++v) w[u][v] = pw[u][v];
+                    }
+                    if (blk + nwaves < nblk) issue_loads(c0, (blk + nwaves) * U * kWave, S, pw, pbq);
+                    while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
+                    if (count >= kWave) drain_issue();
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const float sum = gather_add<H0 / 4>(0.0f, tab, w[u], __builtin_inff());
+                        const int cl = blk * U * kWave + u * kWave + lane;
+                        const float thr = abandon_threshold(bq[u], sqrt_tau0);
+                        const bool alive = cl < S && !(sum > thr);
+                        const unsigned long long m = __ballot(alive);
+                        if (alive) ring[(head + count + __popcll(m & lt_mask)) & (kRing - 1)] = (uint16_t)cl;
+                        count += __popcll(m);
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    if (d_n > 0) drain_finish();
+                }
+                while (count > 0) { drain_issue(); drain_finish(); }
+            }
+            __syncthreads();
+            TRIM_TICK(6);
+            const int np = ctl->nposs;
+            if (np <= a.poss_cap) {
+                for (int b = 0; b < nb; ++b) {
+                    if (cnt0[b] == 0) continue;  // same value for every thread
+                    const float tau = ctl->tau;
+                    for (int i0 = 0; i0 < np; i0 += T) {
+                        const int i = i0 + tid;
+                        int cl = 0;
+                        bool live = false;
+                        if (i < np) {
+                            cl = poss_cl[i];
+                            live = cl / a.batch == b && poss_g[i] <= tau;
+                        }
+                        append(live, c0 + cl);
+                    }
+                    __syncthreads();
+                    const int ns = ctl->nsurv;
+                    __syncthreads();
+                    TRIM_TICK(3);
+                    if (ns > 0) refine_and_select(ns);
+                }
+                TRIM_TICK(3);
+                c0 += S;
+                continue;
+            }
+            // overflow: shorter stretches from now on (or none), and redo from c0 span by span
+            cruise = cruise / 2 >= 2 * a.span ? cruise / 2 / a.batch * a.batch : 0;
+            cur.init(segp, segd);
+            __syncthreads();
+        }
+
+        const int span = c0 + a.span < c_end ? a.span : c_end - c0;
+        const int nb = (span + a.batch - 1) / a.batch;
+        for (int b = tid; b < nb; b += T) cnt0[b] = 0;
         __syncthreads();
         // Rounds, wave by wave.  Each wave owns a contiguous slice of the span.  Round 0
         // bounds ALL its candidates over the first H0 subspaces, branch-free, U x 64
@@ -417,7 +565,6 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         uint16_t *qin = wq + (size_t)wave * a.wqcap;
         uint16_t *qout = wq + (size_t)(nwaves + wave) * a.wqcap;
         int qn = 0;  // length of this wave's queue (same in every lane)
-        const unsigned long long lt_mask = (1ull << lane) - 1ull;
         for (int ph = 0; ph < a.P; ++ph) {
             if (a.P > 1) {
                 __syncthreads();
@@ -435,16 +582,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     for (int base = wlo; base < whi; base += U * kWave) {
                         float bq[U];
                         uint32_t w[U][H0 / 4];
-                        if (base == wlo) {  // loaded ahead of time
-#pragma unroll
-                            for (int u = 0; u < U; ++u) {
-                                bq[u] = pbq[u];
-#pragma unroll
-                                for (int v = 0; v < H0 / 4; ++v) w[u][v] = pw[u][v];
-                            }
-                        } else {
-                            issue_loads(c0, base, whi, w, bq);
-                        }
+                        issue_loads(c0, base, whi, w, bq);
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
                             const float sum = gather_add<H0 / 4>(0.0f, tab, w[u], __builtin_inff());
@@ -465,16 +603,13 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                         }
                     }
                     TRIM_TICK(6);
-                    if (c0 + a.span < c_end) {  // start loading the next span's first step
-                        const int c0n = c0 + a.span;
-                        int lo, hi;
-                        wave_slice(c0n + a.span < c_end ? a.span : c_end - c0n, lo, hi);
-                        issue_loads(c0n, lo, hi, pw, pbq);
-                    }
                 } else {
                     // ---- later rounds: dense over the wave's queue ----
                     h1 = h0 + 32 < a.Mp ? h0 + 32 : a.Mp;
                     const bool fin = last_ph && h1 == a.Mp;
+#ifdef TRIM_EXP_NO_R1
+                    qn = 0;
+#endif
                     for (int i0 = 0; i0 < qn; i0 += kWave) {
                         const int i = i0 + lane;
                         bool alive = i < qn;
@@ -536,6 +671,9 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         TRIM_TICK(2);
         for (int b = 0; b < nb; ++b) {
             if (cnt0[b] == 0) continue;  // same value for every thread: no barrier needed
+#ifdef TRIM_EXP_NO_STAGEB
+            continue;
+#endif
             const float tau = ctl->tau;
             const int l0 = b * a.batch;
             const int blen = l0 + a.batch < span ? a.batch : span - l0;
@@ -551,9 +689,9 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
             if (ns > 0) refine_and_select(ns);
         }
         TRIM_TICK(3);
+        c0 += span;
     }
 
-    TRIM_TICK(6);
     // ---- epilogue ----
     if (MODE == kKnn) {
         for (int i = tid; i < a.k; i += T) {

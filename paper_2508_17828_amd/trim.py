@@ -21,7 +21,7 @@ TRIM_MAX_BATCH = 4096
 TRIM_MAX_NPROBE = 4096
 
 EXPORTS = ("trim_shape_supported", "trim_encode", "trim_build_lut", "trim_search_knn",
-           "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe",
+           "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_strerror", "trim_last_hip_error", "trim_version")
 
 
@@ -78,7 +78,8 @@ def lib() -> C.CDLL:
                                      C.c_void_p, C.c_int32, C.c_void_p]
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                       C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
-                                      C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_search_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -181,7 +182,8 @@ def trim_build_lut(queries: torch.Tensor, codebooks: torch.Tensor, mfma: bool = 
 
 def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, batch: int,
                     probes: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
-                    want_stats: bool = True, want_mask: bool = False, out=None):
+                    want_stats: bool = True, want_mask: bool = False, out=None,
+                    query_order: Optional[torch.Tensor] = None):
     """Returns dict(ids [nq][k] int32, d2 [nq][k] float32, n_scanned, n_exact, mask)."""
     nq = queries.shape[0]
     dev = queries.device
@@ -206,6 +208,7 @@ def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, b
     _check(lib().trim_search_knn(C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
                                  _ptr(lut, torch.float32, "lut"),
                                  C.byref(cand) if cand is not None else None, k, gamma, batch,
+                                 _ptr(query_order, torch.int32, "query_order"),
                                  _ptr(out_ids, torch.int32, "out_ids"),
                                  _ptr(out_d2, torch.float32, "out_d2"),
                                  C.byref(stats) if stats is not None else None,
@@ -277,3 +280,11 @@ def trim_ivf_probe(queries: torch.Tensor, centroids: torch.Tensor, nprobe: int) 
                                 nprobe, _ptr(probes, torch.int32, "probes"), _stream()),
            "trim_ivf_probe")
     return probes
+
+
+def trim_query_order(probes: torch.Tensor) -> torch.Tensor:
+    nq, nprobe = probes.shape
+    order = torch.empty((nq,), dtype=torch.int32, device=probes.device)
+    _check(lib().trim_query_order(_ptr(probes, torch.int32, "probes"), nq, nprobe,
+                                  _ptr(order, torch.int32, "order"), _stream()), "trim_query_order")
+    return order

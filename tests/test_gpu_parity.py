@@ -178,6 +178,31 @@ def test_knn_empty_and_repeated_lists(T, oracle):
     assert np.all(got["ids"].cpu().numpy() == -1)
 
 
+def test_query_order_changes_nothing_but_scheduling(T, oracle):
+    b = case("c5s")
+    gi, q, probes = to_dev(T, b)
+    order = T.trim_query_order(probes)
+    ref = np.lexsort((np.arange(b.probes.shape[0]), b.probes[:, 0]))
+    np.testing.assert_array_equal(order.cpu().numpy(), ref)
+    a = T.trim_search_knn(gi, q, 10, 0.5, 1024, probes=probes, want_mask=True)
+    c = T.trim_search_knn(gi, q, 10, 0.5, 1024, probes=probes, want_mask=True, query_order=order)
+    for key in ("ids", "d2", "n_exact", "n_scanned", "mask"):
+        assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy())
+    r = oracle.search_knn(b.index, b.queries, 10, 0.5, 1024, b.probes)
+    np.testing.assert_array_equal(c["ids"].cpu().numpy(), r["ids"])
+    # an order array with entries outside 0..nq-1: those slots do nothing, the rest is intact
+    import torch
+    bad = order.clone(); bad[3] = -5; bad[7] = 10 ** 6
+    out = (torch.full((q.shape[0], 10), -7, dtype=torch.int32, device="cuda"),
+           torch.zeros((q.shape[0], 10), dtype=torch.float32, device="cuda"))
+    T.trim_search_knn(gi, q, 10, 0.5, 1024, probes=probes, out=out, query_order=bad)
+    got = out[0].cpu().numpy()
+    skipped = [int(order[3]), int(order[7])]
+    keep = np.setdiff1d(np.arange(q.shape[0]), skipped)
+    np.testing.assert_array_equal(got[keep], r["ids"][keep])
+    assert np.all(got[skipped] == -7)
+
+
 def test_knn_is_deterministic(T, oracle):
     b = case("c5s")
     gi, q, probes = to_dev(T, b)
