@@ -153,19 +153,52 @@ __device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
     }
 }
 
+// 4 * (byte B of w): the byte offset of a table entry inside its 1 KB row.
+template <int B>
+__device__ __forceinline__ uint32_t byte_times4(uint32_t w) {
+    uint32_t r;
+    const uint32_t two = 2;
+    if constexpr (B == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(w));
+    else if constexpr (B == 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(two), "v"(w));
+    else if constexpr (B == 2)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(two), "v"(w));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(two), "v"(w));
+    return r;
+}
+
 // Sum of table entries selected by 4*VEC consecutive code bytes (VEC dwords), added to s
 // in subspace order.  tab points at the table row of the first of these subspaces.  Stops
 // early once s > thr; a stopped sum is a lower estimate of the full sum that is still > thr.
+// Read a float at a byte address of the workgroup's LDS.
+__device__ __forceinline__ float lds_f32(uint32_t byte_addr) {
+    typedef __attribute__((address_space(3))) const float lds_float;
+    return *reinterpret_cast<lds_float *>(static_cast<uintptr_t>(byte_addr));
+}
+
+// LDS byte address of a pointer into the workgroup's LDS.
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+    typedef __attribute__((address_space(3))) const char lds_char;
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_char *)p));
+}
+
+// tab_base is the LDS byte address of the table row of the first of these subspaces.
 template <int VEC>
-__device__ __forceinline__ float gather_add(float s, const float *__restrict__ tab,
-                                            const uint32_t (&w)[VEC], float thr) {
+__device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const uint32_t (&w)[VEC],
+                                            float thr) {
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const uint32_t code = (w[v] >> (8 * b)) & 0xffu;
-            s = s + tab[(v * 4 + b) * kC + code];
-        }
+        // byte b of the code word, times 4 (the byte offset inside table row v*4+b): one
+        // sub-dword-addressed shift each instead of extract + scale
+        const uint32_t o0 = byte_times4<0>(w[v]), o1 = byte_times4<1>(w[v]);
+        const uint32_t o2 = byte_times4<2>(w[v]), o3 = byte_times4<3>(w[v]);
+        const uint32_t row = tab_base + (v * 4) * kC * 4;
+        s = s + lds_f32(row + o0);
+        s = s + lds_f32(row + 1 * kC * 4 + o1);
+        s = s + lds_f32(row + 2 * kC * 4 + o2);
+        s = s + lds_f32(row + 3 * kC * 4 + o3);
         // early abandon every 8 subspaces (see abandon_threshold)
         if ((v & 1) == 1 && v + 1 < VEC && s > thr) return s;
     }

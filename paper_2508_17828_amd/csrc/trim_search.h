@@ -22,6 +22,9 @@ __device__ unsigned long long g_phase_ticks[8];
 namespace trim {
 
 enum Mode { kKnn = 0, kRange = 1 };
+// The distance table sits at the very start of the workgroup's LDS (the search kernel has no
+// static LDS), which lets table gathers use an immediate row offset.  Checked at kernel entry.
+constexpr uint32_t kTabLds = 0;
 constexpr int kXcds = 8;  // accelerator dies of an MI355X, each with its own L2
 
 struct SearchArgs {
@@ -229,6 +232,12 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     const int split = blockIdx.y;
     const int nseg = a.nseg > 0 ? a.nseg : 1;
 
+    {   // the table must sit at LDS address kTabLds; the value is laundered through an empty
+        // asm so that the compiler cannot fold the test (it assumes globals are never at 0)
+        uint32_t tab_at = lds_addr(tab);
+        asm volatile("" : "+v"(tab_at));
+        if (tab_at != kTabLds) return;
+    }
     TRIM_TICK_INIT();
     // ---- prologue: query, segment table, table ----
     for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
@@ -450,23 +459,23 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     if (lane < d_n) {
                         const float thr = abandon_threshold(d_b, sqrt_tau0);
                         const uint8_t *cp = a.codes + (size_t)d_pos * a.M;
-                        float sum = gather_add<DV>(0.0f, tab, d_w, thr);
+                        float sum = gather_add<DV>(0.0f, kTabLds, d_w, thr);
                         int j = 4 * DV;
                         while (j < a.M && !(sum > thr)) {  // widest aligned load that fits
                             if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
                                 uint32_t w[4];
                                 load_codes<4>(w, cp + j);
-                                sum = gather_add<4>(sum, tab + j * kC, w, thr);
+                                sum = gather_add<4>(sum, kTabLds + j * (kC * 4), w, thr);
                                 j += 16;
                             } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= a.M) {
                                 uint32_t w[2];
                                 load_codes<2>(w, cp + j);
-                                sum = gather_add<2>(sum, tab + j * kC, w, thr);
+                                sum = gather_add<2>(sum, kTabLds + j * (kC * 4), w, thr);
                                 j += 8;
                             } else {
                                 uint32_t w[1];
                                 load_codes<1>(w, cp + j);
-                                sum = gather_add<1>(sum, tab + j * kC, w, thr);
+                                sum = gather_add<1>(sum, kTabLds + j * (kC * 4), w, thr);
                                 j += 4;
                             }
                         }
@@ -500,7 +509,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     if (count >= kWave) drain_issue();
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const float sum = gather_add<H0 / 4>(0.0f, tab, w[u], __builtin_inff());
+                        const float sum = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
                         const int cl = blk * U * kWave + u * kWave + lane;
                         const float thr = abandon_threshold(bq[u], sqrt_tau0);
                         const bool alive = cl < S && !(sum > thr);
@@ -585,7 +594,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                         issue_loads(c0, base, whi, w, bq);
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
-                            const float sum = gather_add<H0 / 4>(0.0f, tab, w[u], __builtin_inff());
+                            const float sum = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
                             const int cl = base + u * kWave + lane;
                             const float thr = abandon_threshold(bq[u], sqrt_tau0);
                             const bool valid = cl < whi;
@@ -626,17 +635,17 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                                 if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
                                     uint32_t w[4];
                                     load_codes<4>(w, cp + j);
-                                    sum = gather_add<4>(sum, tab + j * kC, w, thr);
+                                    sum = gather_add<4>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 16;
                                 } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= h1) {
                                     uint32_t w[2];
                                     load_codes<2>(w, cp + j);
-                                    sum = gather_add<2>(sum, tab + j * kC, w, thr);
+                                    sum = gather_add<2>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 8;
                                 } else {
                                     uint32_t w[1];
                                     load_codes<1>(w, cp + j);
-                                    sum = gather_add<1>(sum, tab + j * kC, w, thr);
+                                    sum = gather_add<1>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 4;
                                 }
                                 if (sum > thr) break;
