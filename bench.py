@@ -75,7 +75,7 @@ def main():
                                      want_stats=False)["ids"]
 
     def order_for(pr):
-        return trim.trim_query_order(pr) if pr is not None and not args.no_order else None
+        return trim.trim_query_order(pr, w.nlist) if pr is not None and not args.no_order else None
 
     def run_once(gamma, want_stats=True):
         pr = probes_for(queries)

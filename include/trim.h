@@ -176,12 +176,14 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
 
 /*
  * Scheduling aid for inverted-file search (the probed lists of Section 6.1): order_out [nq]
- * device = the queries sorted by their first probed list, ties by query index.  Queries that
- * scan the same lists then run next to each other and share the GPU's caches.
- * probes [nq][nprobe] device as produced by trim_ivf_probe.
+ * device = a permutation of the queries in which queries with the same first probed list are
+ * adjacent, lists in ascending order (for nlist > 32768: ascending list id modulo 32768);
+ * the order inside one list is unspecified.  Queries that scan the same lists then run
+ * next to each other and share the GPU's caches.
+ * probes [nq][nprobe] device as produced by trim_ivf_probe (nlist is the number of lists).
  */
-int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t *order_out,
-                     void *stream);
+int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t nlist,
+                     int32_t *order_out, void *stream);
 
 /* Text for a trim_status. */
 const char *trim_strerror(int status);

@@ -391,35 +391,37 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
     if (d % 4) return TRIM_UNSUPPORTED_SHAPE;
     int npow2 = 1;
     while (npow2 < nlist) npow2 <<= 1;
-    const size_t lds = (size_t)npow2 * 8 + (size_t)d * 4;
+    // queries per workgroup: 4, fewer if their key arrays do not fit a quarter of the LDS
+    // (so that several workgroups share a CU)
+    int qt = 4;
+    while (qt > 1 && (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4) > kLdsBytes / 4) qt >>= 1;
+    const size_t lds = (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4);
     if (lds > kLdsBytes) return TRIM_UNSUPPORTED_SHAPE;
     if (nq == 0) return TRIM_OK;
     if (!queries || !centroids || !probes_out || !aligned16(centroids)) return TRIM_INVALID_ARG;
     if (nq > 0x7fffffff) return TRIM_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(ivf_probe_kernel),
+    void (*fn)(const float *, int64_t, int, const float *, int, int, int, int32_t *) =
+        qt == 4 ? ivf_probe_kernel<4> : qt == 2 ? ivf_probe_kernel<2> : ivf_probe_kernel<1>;
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    const int threads = npow2 >= 2048 ? 1024 : 256;
-    hipLaunchKernelGGL(ivf_probe_kernel, dim3((unsigned)nq), dim3(threads), lds, st, queries, d,
+    hipLaunchKernelGGL(fn, dim3((unsigned)((nq + qt - 1) / qt)), dim3(512), lds, st, queries, nq, d,
                        centroids, nlist, npow2, nprobe, probes_out);
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }
 
-int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t *order_out,
-                     void *stream) {
-    if (nq < 0 || nq > 0x7fffffff - 8 || nprobe <= 0) return TRIM_INVALID_ARG;
+int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t nlist,
+                     int32_t *order_out, void *stream) {
+    if (nq < 0 || nq > 0x7fffffff - 8 || nprobe <= 0 || nlist <= 0) return TRIM_INVALID_ARG;
     if (nq == 0) return TRIM_OK;
     if (!probes || !order_out) return TRIM_INVALID_ARG;
-    const int slab = 16384;
-    int npow2 = 1;
-    while (npow2 < (nq < slab ? (int)nq : slab)) npow2 <<= 1;
-    const size_t lds = (size_t)npow2 * 8;
+    const int nbucket = nlist < 32768 ? nlist : 32768;
+    const size_t lds = (size_t)nbucket * 4;
     hipStream_t st = static_cast<hipStream_t>(stream);
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(query_order_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(query_order_kernel, dim3((unsigned)((nq + slab - 1) / slab)),
-                       dim3(npow2 >= 2048 ? 1024 : 256), lds, st, probes, nq, nprobe, slab, npow2,
+    hipLaunchKernelGGL(query_order_kernel, dim3(1), dim3(1024), lds, st, probes, nq, nprobe, nbucket,
                        order_out);
     HIP_TRY(hipGetLastError());
     return TRIM_OK;

@@ -232,74 +232,129 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
 }
 
 // ---- coarse probe selection (Section 6.1: IVFPQ with C' lists, nprobe probed) ----
-// One workgroup per query: exact distances to all centroids (half wave each), then a
-// bitonic sort of (distance bits, list id) keys in LDS; the first nprobe ids are written.
-__global__ __launch_bounds__(1024) void ivf_probe_kernel(const float *__restrict__ queries, int d,
-                                                         const float *__restrict__ centroids,
-                                                         int nlist, int npow2, int nprobe,
-                                                         int32_t *__restrict__ probes) {
+// One workgroup handles QT queries: every centroid row is read once and measured against
+// all QT queries (exact distances by half waves, rounding order as in exact_d2_half), then
+// each query's (distance bits, list id) keys are sorted in LDS (bitonic) and the first
+// nprobe ids are written.
+template <int QT>
+__global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict__ queries,
+                                                        int64_t nq, int d,
+                                                        const float *__restrict__ centroids,
+                                                        int nlist, int npow2, int nprobe,
+                                                        int32_t *__restrict__ probes) {
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);  // [npow2]
-    float *q_lds = reinterpret_cast<float *>(smem + (size_t)npow2 * 8);
+    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);  // [QT][npow2]
+    float *q_lds = reinterpret_cast<float *>(smem + (size_t)QT * npow2 * 8);  // [QT][d]
     const int tid = threadIdx.x, T = blockDim.x;
-    const int64_t q = blockIdx.x;
-    for (int t = tid; t < d; t += T) q_lds[t] = queries[(size_t)q * d + t];
-    for (int i = nlist + tid; i < npow2; i += T) keys[i] = ~0ull;
+    const int64_t q0 = (int64_t)blockIdx.x * QT;
+    const int nqt = (int)(nq - q0 < QT ? nq - q0 : QT);
+    for (int t = tid; t < QT * d; t += T) {
+        const int qi = t / d;
+        q_lds[t] = qi < nqt ? queries[(size_t)q0 * d + t] : 0.0f;
+    }
+    for (int i = tid; i < QT * npow2; i += T) keys[i] = ~0ull;
     __syncthreads();
-    for (int l = tid >> 5; l < nlist; l += T >> 5) {
-        const float d2 = exact_d2_half(centroids + (size_t)l * d, q_lds, d, tid & 31);
-        // d2 >= 0 (or NaN): its bit pattern orders like its value
-        if ((tid & 31) == 0)
-            keys[l] = ((unsigned long long)__float_as_uint(d2) << 32) | (uint32_t)l;
+    const int lane32 = tid & 31;
+    const int ng = d >> 2;
+    const int nh = T >> 5;
+    for (int l0 = tid >> 5; l0 < nlist; l0 += 2 * nh) {   // two centroid rows in flight
+        const int l1 = l0 + nh;
+        const bool two = l1 < nlist;                       // same for the whole half wave
+        const float4 *ra = reinterpret_cast<const float4 *>(centroids + (size_t)l0 * d);
+        const float4 *rb = reinterpret_cast<const float4 *>(centroids + (size_t)(two ? l1 : l0) * d);
+        float acc[QT], bcc[QT];
+#pragma unroll
+        for (int qi = 0; qi < QT; ++qi) { acc[qi] = 0.0f; bcc[qi] = 0.0f; }
+        for (int g = lane32; g < ng; g += 32) {
+            const float4 xa = ra[g];
+            const float4 xb = rb[g];
+#pragma unroll
+            for (int qi = 0; qi < QT; ++qi) {
+                const float4 qv = *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * g);
+                float e;
+                e = qv.x - xa.x; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                e = qv.y - xa.y; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                e = qv.z - xa.z; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                e = qv.w - xa.w; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                e = qv.x - xb.x; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                e = qv.y - xb.y; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                e = qv.z - xb.z; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                e = qv.w - xb.w; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+            }
+        }
+#pragma unroll
+        for (int qi = 0; qi < QT; ++qi) {
+            const float da = half_reduce(acc[qi]);
+            const float db = half_reduce(bcc[qi]);
+            // a distance is >= 0 (or NaN): its bit pattern orders like its value
+            if (lane32 == 0) {
+                keys[(size_t)qi * npow2 + l0] = ((unsigned long long)__float_as_uint(da) << 32) | (uint32_t)l0;
+                if (two)
+                    keys[(size_t)qi * npow2 + l1] = ((unsigned long long)__float_as_uint(db) << 32) | (uint32_t)l1;
+            }
+        }
     }
     __syncthreads();
+    const int halfn = npow2 >> 1;
     for (int size = 2; size <= npow2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < npow2 >> 1; i += T) {
+            for (int w = tid; w < QT * halfn; w += T) {
+                const int qi = w / halfn, i = w - qi * halfn;
                 const int lo = ((i / stride) * stride << 1) + (i % stride);
                 const int hi = lo + stride;
                 const bool up = ((lo & size) == 0);
-                const unsigned long long x = keys[lo], y = keys[hi];
-                if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
+                unsigned long long *kq = keys + (size_t)qi * npow2;
+                const unsigned long long x = kq[lo], y = kq[hi];
+                if ((x > y) == up) { kq[lo] = y; kq[hi] = x; }
             }
             __syncthreads();
         }
     }
-    for (int p = tid; p < nprobe; p += T) probes[(size_t)q * nprobe + p] = (int32_t)(keys[p] & 0xffffffffu);
+    for (int w = tid; w < nqt * nprobe; w += T) {
+        const int qi = w / nprobe, p = w - qi * nprobe;
+        probes[(size_t)(q0 + qi) * nprobe + p] = (int32_t)(keys[(size_t)qi * npow2 + p] & 0xffffffffu);
+    }
 }
 
-// ---- processing order: queries sorted by their first probed list (ties by query index) ----
-// One workgroup sorts a slab of up to `slab` queries (bitonic sort of 64-bit keys in LDS).
+// ---- processing order: queries grouped by their first probed list ----
+// Single workgroup, counting sort with an LDS histogram (nbucket <= 32768 buckets; list ids
+// are folded modulo nbucket, which still puts equal lists together).  Lists appear in
+// ascending bucket order; the order of the queries inside a bucket is unspecified.
 __global__ __launch_bounds__(1024) void query_order_kernel(const int32_t *__restrict__ probes,
-                                                           int64_t nq, int nprobe, int slab,
-                                                           int npow2, int32_t *__restrict__ order) {
+                                                           int64_t nq, int nprobe, int nbucket,
+                                                           int32_t *__restrict__ order) {
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned long long *keys = reinterpret_cast<unsigned long long *>(smem);
+    int *hist = reinterpret_cast<int *>(smem);  // [nbucket], then running cursors
+    __shared__ int part[1024];
     const int tid = threadIdx.x, T = blockDim.x;
-    const int64_t q0 = (int64_t)blockIdx.x * slab;
-    const int cnt = (int)(nq - q0 < slab ? nq - q0 : slab);
-    for (int i = tid; i < npow2; i += T) {
-        unsigned long long key = ~0ull;
-        if (i < cnt) {
-            const uint32_t l = (uint32_t)probes[(size_t)(q0 + i) * nprobe];
-            key = ((unsigned long long)l << 32) | (uint32_t)i;
-        }
-        keys[i] = key;
+    for (int b = tid; b < nbucket; b += T) hist[b] = 0;
+    __syncthreads();
+    for (int64_t q = tid; q < nq; q += T) {
+        const uint32_t l = (uint32_t)probes[(size_t)q * nprobe];
+        atomicAdd(&hist[l % (uint32_t)nbucket], 1);
     }
     __syncthreads();
-    for (int size = 2; size <= npow2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < npow2 >> 1; i += T) {
-                const int lo = ((i / stride) * stride << 1) + (i % stride);
-                const int hi = lo + stride;
-                const bool up = ((lo & size) == 0);
-                const unsigned long long x = keys[lo], y = keys[hi];
-                if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
-            }
-            __syncthreads();
-        }
+    // exclusive prefix over the buckets: each thread owns a contiguous run
+    const int per = (nbucket + T - 1) / T;
+    const int lo = tid * per < nbucket ? tid * per : nbucket;
+    const int hi = lo + per < nbucket ? lo + per : nbucket;
+    int sum = 0;
+    for (int b = lo; b < hi; ++b) sum += hist[b];
+    part[tid] = sum;
+    __syncthreads();
+    for (int off = 1; off < T; off <<= 1) {
+        const int v = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
     }
-    for (int i = tid; i < cnt; i += T) order[q0 + i] = (int32_t)(q0 + (int64_t)(keys[i] & 0xffffffffu));
+    int run = part[tid] - sum;
+    for (int b = lo; b < hi; ++b) { const int c = hist[b]; hist[b] = run; run += c; }
+    __syncthreads();
+    for (int64_t q = tid; q < nq; q += T) {
+        const uint32_t l = (uint32_t)probes[(size_t)q * nprobe];
+        order[atomicAdd(&hist[l % (uint32_t)nbucket], 1)] = (int32_t)q;
+    }
 }
 
 }  // namespace trim

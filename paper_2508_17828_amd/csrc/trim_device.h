@@ -96,8 +96,22 @@ __device__ __forceinline__ float plb_from_s(float s, float b, float two_gamma) {
     return __builtin_fmaf(t, b, e * e);
 }
 
+// Sum over the 32 lanes of a half wave in the tree order p[l] += p[l+h], h = 16, 8, 4, 2, 1
+// (the result is exact in lane 0 of the half wave; the other lanes hold the same tree with
+// operands swapped, which is the same value).  Step 16 crosses 16-lane rows (swizzle:
+// lane ^ 16); steps 8..1 are rotations inside a row done by the data-parallel primitives
+// of the vector ALU, so only one LDS-crossbar operation is needed per reduction.
+__device__ __forceinline__ float half_reduce(float v) {
+    v = v + __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xf, 0xf, false));
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x122, 0xf, 0xf, false));
+    v = v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x121, 0xf, 0xf, false));
+    return v;
+}
+
 // Exact squared distance, computed by the 32 lanes of a half wave (all 32 must call it
-// together).  row: global, 16-byte aligned; q: LDS.  Every lane returns the result.
+// together).  row: global, 16-byte aligned; q: LDS.  Lane 0 of the half wave returns the result.
 __device__ __forceinline__ float exact_d2_half(const float *__restrict__ row,
                                                const float *__restrict__ q, int d, int lane32) {
     float acc = 0.0f;
@@ -113,9 +127,7 @@ __device__ __forceinline__ float exact_d2_half(const float *__restrict__ row,
         e = qv.z - xv.z; acc = __builtin_fmaf(e, e, acc);
         e = qv.w - xv.w; acc = __builtin_fmaf(e, e, acc);
     }
-#pragma unroll
-    for (int h = 16; h >= 1; h >>= 1) acc = acc + __shfl_xor(acc, h, 32);
-    return acc;
+    return half_reduce(acc);
 }
 
 // Four rows at once (same arithmetic per row as exact_d2_half; the four loads of each step
@@ -146,11 +158,7 @@ __device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
         }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int h = 16; h >= 1; h >>= 1) acc[u] = acc[u] + __shfl_xor(acc[u], h, 32);
-        out[u] = acc[u];
-    }
+    for (int u = 0; u < 4; ++u) out[u] = half_reduce(acc[u]);
 }
 
 // 4 * (byte B of w): the byte offset of a table entry inside its 1 KB row.

@@ -79,7 +79,7 @@ def lib() -> C.CDLL:
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                       C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
-        L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_search_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -282,9 +282,9 @@ def trim_ivf_probe(queries: torch.Tensor, centroids: torch.Tensor, nprobe: int) 
     return probes
 
 
-def trim_query_order(probes: torch.Tensor) -> torch.Tensor:
+def trim_query_order(probes: torch.Tensor, nlist: int) -> torch.Tensor:
     nq, nprobe = probes.shape
     order = torch.empty((nq,), dtype=torch.int32, device=probes.device)
-    _check(lib().trim_query_order(_ptr(probes, torch.int32, "probes"), nq, nprobe,
+    _check(lib().trim_query_order(_ptr(probes, torch.int32, "probes"), nq, nprobe, nlist,
                                   _ptr(order, torch.int32, "order"), _stream()), "trim_query_order")
     return order
