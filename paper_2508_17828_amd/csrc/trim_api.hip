@@ -101,7 +101,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
         pl->wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
         pl->cruise = P == 1 ? cruise : 0;  // table phases need block-wide barriers
         pl->poss_cap = span / 2;
-        if ((size_t)nwaves * kRing * 2 > wq_bytes) pl->cruise = 0;
+        if ((size_t)nwaves * kRing * 4 > wq_bytes) pl->cruise = 0;
         return true;
     }
     return false;

@@ -339,6 +339,9 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                 ok[u] = idx[u] < ns;              // uniform within the half wave
                 pos[u] = spos[ok[u] ? idx[u] : i];
             }
+            int32_t rid4[4];  // ids are fetched together with the rows, not after them
+#pragma unroll
+            for (int u = 0; u < 4; ++u) rid4[u] = (MODE == kKnn && a.ids) ? a.ids[pos[u]] : pos[u];
             float d2[4];
             exact_d2_half_x4(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
                              a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d, q_lds,
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     if (!ok[u]) continue;
                     if (MODE == kKnn) {
                         sd2[idx[u]] = d2[u];
-                        spos[idx[u]] = a.ids ? a.ids[pos[u]] : pos[u];
+                        spos[idx[u]] = rid4[u];
                     } else if (d2[u] <= a.radius2) {
                         const int c = sidx[idx[u]];
                         atomicOr(&a.result_mask[(size_t)q * a.rmask_words + (c >> 5)], 1u << (c & 31));
@@ -395,15 +398,18 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         hi = lo + wchunk < span_len ? lo + wchunk : span_len;
     };
     // Issue the loads (first H0 code bytes, landmark distance) of U x 64 candidates.
-    auto issue_loads = [&](int c0n, int base, int hi, uint32_t (&w)[U][H0 / 4], float (&bq)[U]) {
+    auto issue_loads = [&](int c0n, int base, int hi, uint32_t (&w)[U][H0 / 4], float (&bq)[U],
+                           int (&sg)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int cl = base + u * kWave + lane;
             bq[u] = 0.0f;
+            sg[u] = 0;
 #pragma unroll
             for (int v = 0; v < H0 / 4; ++v) w[u][v] = 0;
             if (cl < hi) {
                 const int pos = cur.pos(c0n + cl, segp, segd);
+                sg[u] = cur.seg;
                 load_codes<H0 / 4>(w[u], a.codes + (size_t)pos * a.M);
                 bq[u] = a.dlx[pos];
             }
@@ -433,24 +439,28 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
             if (tid == 0) ctl->nposs = 0;
             __syncthreads();
             {
-                uint16_t *ring = wq + (size_t)wave * kRing;
+                uint32_t *ring = reinterpret_cast<uint32_t *>(wq) + (size_t)wave * kRing;  // (segment << 16) | number
                 int head = 0, count = 0;  // same in every lane of the wave
                 // A drain takes up to 64 queued candidates, one per lane.  It is split in two so
                 // that its loads are in flight while the next block is bounded: drain_issue pops
                 // the entries and starts the loads of the landmark distance and the first code
                 // chunk; drain_finish redoes the table sum from the start (now with a test every
                 // 8 subspaces), evaluates Equation 3 and records the candidate if it passes tau0.
-                constexpr int DV = VEC;  // dwords of the first chunk
+                constexpr int DV = VEC;            // dwords per code chunk
+                const bool two_chunks = a.M >= 8 * DV;  // the first two chunks are loaded ahead
                 int d_n = 0, d_cl = 0, d_pos = 0;
                 float d_b = 0.0f;
-                uint32_t d_w[DV];
+                uint32_t d_w0[DV], d_w1[DV];
                 auto drain_issue = [&]() {
                     d_n = count < kWave ? count : kWave;
                     if (lane < d_n) {
-                        d_cl = ring[(head + lane) & (kRing - 1)];
-                        d_pos = locate(c0 + d_cl);
+                        const uint32_t e = ring[(head + lane) & (kRing - 1)];
+                        d_cl = (int)(e & 0xffffu);
+                        d_pos = c0 + d_cl + segd[e >> 16];
+                        const uint8_t *cp = a.codes + (size_t)d_pos * a.M;
                         d_b = a.dlx[d_pos];
-                        load_codes<DV>(d_w, a.codes + (size_t)d_pos * a.M);
+                        load_codes<DV>(d_w0, cp);
+                        if (two_chunks) load_codes<DV>(d_w1, cp + 4 * DV);
                     }
                     head = (head + d_n) & (kRing - 1);
                     count -= d_n;
@@ -459,8 +469,12 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     if (lane < d_n) {
                         const float thr = abandon_threshold(d_b, sqrt_tau0);
                         const uint8_t *cp = a.codes + (size_t)d_pos * a.M;
-                        float sum = gather_add<DV>(0.0f, kTabLds, d_w, thr);
+                        float sum = gather_add<DV>(0.0f, kTabLds, d_w0, thr);
                         int j = 4 * DV;
+                        if (two_chunks && !(sum > thr)) {
+                            sum = gather_add<DV>(sum, kTabLds + 4 * DV * (kC * 4), d_w1, thr);
+                            j = 8 * DV;
+                        }
                         while (j < a.M && !(sum > thr)) {  // widest aligned load that fits
                             if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
                                 uint32_t w[4];
@@ -491,20 +505,14 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     d_n = 0;
                 };
                 const int nblk = (S + U * kWave - 1) / (U * kWave);
-                uint32_t pw[U][H0 / 4];
-                float pbq[U];
-                int blk = wave;
-                if (blk < nblk) issue_loads(c0, blk * U * kWave, S, pw, pbq);
-                for (; blk < nblk; blk += nwaves) {
+                for (int blk = wave; blk < nblk; blk += nwaves) {
+                    // this block's loads fly while the previous drain is finished; the next
+                    // drain's loads fly while this block is bounded
                     uint32_t w[U][H0 / 4];
                     float bq[U];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        bq[u] = pbq[u];
-#pragma unroll
-                        for (int v = 0; v < H0 / 4; ++v) w[u][v] = pw[u][v];
-                    }
-                    if (blk + nwaves < nblk) issue_loads(c0, (blk + nwaves) * U * kWave, S, pw, pbq);
+                    int sg[U];
+                    issue_loads(c0, blk * U * kWave, S, w, bq, sg);
+                    if (d_n > 0) drain_finish();
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
                     if (count >= kWave) drain_issue();
 #pragma unroll
@@ -514,13 +522,15 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                         const float thr = abandon_threshold(bq[u], sqrt_tau0);
                         const bool alive = cl < S && !(sum > thr);
                         const unsigned long long m = __ballot(alive);
-                        if (alive) ring[(head + count + __popcll(m & lt_mask)) & (kRing - 1)] = (uint16_t)cl;
+                        if (alive)
+                            ring[(head + count + __popcll(m & lt_mask)) & (kRing - 1)] =
+                                ((uint32_t)sg[u] << 16) | (uint32_t)cl;
                         count += __popcll(m);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
-                    if (d_n > 0) drain_finish();
                 }
+                if (d_n > 0) drain_finish();
                 while (count > 0) { drain_issue(); drain_finish(); }
             }
             __syncthreads();
@@ -556,7 +566,10 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
             __syncthreads();
         }
 
-        const int span = c0 + a.span < c_end ? a.span : c_end - c0;
+        // The first stretch after the seed is a single batch: its threshold (from the k seeds)
+        // is loose, so nothing is abandoned early; one batch is enough to make tau tight.
+        const int span_len = c0 == c_begin + kseed ? a.batch : a.span;
+        const int span = c0 + span_len < c_end ? span_len : c_end - c0;
         const int nb = (span + a.batch - 1) / a.batch;
         for (int b = tid; b < nb; b += T) cnt0[b] = 0;
         __syncthreads();
@@ -591,7 +604,8 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     for (int base = wlo; base < whi; base += U * kWave) {
                         float bq[U];
                         uint32_t w[U][H0 / 4];
-                        issue_loads(c0, base, whi, w, bq);
+                        int sg_unused[U];
+                        issue_loads(c0, base, whi, w, bq, sg_unused);
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
                             const float sum = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
