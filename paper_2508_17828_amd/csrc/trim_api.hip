@@ -164,6 +164,8 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
     a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
     a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap;
+    a.small_addr = ix->n < (int64_t(1) << 24) && ix->n * (int64_t)ix->M < (int64_t(1) << 32) &&
+                   ix->M < (1 << 24);
     if (getenv("TRIM_NO_CRUISE")) a.cruise = 0;
 }
 

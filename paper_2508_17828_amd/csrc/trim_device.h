@@ -237,11 +237,20 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[VEC], const uint8_t *__
 // s > (b + sqrt(tau))^2 by a margin that covers all rounding, the finished bound is
 // certain to exceed tau and the remaining subspaces need not be read: the candidate is
 // pruned exactly as the full evaluation would prune it.  Margin: the computed chain
-// sqrt -> subtract -> square loses < 4 ulp (2.4e-7 relative); 1e-5 is used.  The floor keeps
-// the argument inside the normal range.  tau = +inf gives +inf (never abandons).
-__device__ __forceinline__ float abandon_threshold(float b, float sqrt_tau) {
-    const float r = b + sqrt_tau;
-    return fmaxf(r * r * 1.00001f, 1e-30f);
+// sqrt -> subtract -> square loses < 4 ulp (2.4e-7 relative); the threshold is inflated by
+// 1e-5.  tau = +inf gives +inf (never abandons).
+//
+// Per threshold tau:   st = abandon_scale(tau) = c * max(sqrt(tau), 1e-15), c = 1.000005
+// Per candidate:       thr = (c*b + st)^2 = c^2 (b + max(sqrt(tau),1e-15))^2 >= 1.00001 (b + sqrt(tau))^2
+// (the floor keeps thr >= 1e-30, inside the normal range, so the margin argument holds for
+// arbitrarily small tau as well).
+constexpr float kAbandonC = 1.000005f;
+__device__ __forceinline__ float abandon_scale(float tau) {
+    return kAbandonC * fmaxf(sqrt_rn(tau), 1e-15f);
+}
+__device__ __forceinline__ float abandon_threshold(float b, float st) {
+    const float r = __builtin_fmaf(b, kAbandonC, st);
+    return r * r;
 }
 
 }  // namespace trim

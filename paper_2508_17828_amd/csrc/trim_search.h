@@ -70,6 +70,7 @@ struct SearchArgs {
     uint32_t off_plb, off_cnt, off_wq;
     int32_t wqcap;     // entries per wave in each of the two work-queue arrays
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
+    int32_t small_addr;  // n < 2^24 and n*M < 2^32: 24-bit multiply and 32-bit offsets suffice
     int32_t poss_cap;  // capacity of the possibles list
 };
 
@@ -420,7 +421,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
-        const float sqrt_tau0 = trim::sqrt_rn(tau0);
+        const float sqrt_tau0 = abandon_scale(tau0);  // scaled: see abandon_threshold
 
         // ---- cruise: once tau is finite, bound a long stretch of candidates with no block-wide
         // barrier at all.  Every wave runs its own software pipeline over interleaved blocks of
@@ -511,20 +512,38 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     uint32_t w[U][H0 / 4];
                     float bq[U];
                     int sg[U];
-                    issue_loads(c0, blk * U * kWave, S, w, bq, sg);
+                    const int cb = blk * U * kWave;
+                    const bool full = a.small_addr && cb + U * kWave <= S;  // same for the wave
+                    if (full) {
+                        // whole block in range, 32-bit byte offsets from uniform bases
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const uint32_t pos = (uint32_t)cur.pos(c0 + cb + u * kWave + lane, segp, segd);
+                            sg[u] = cur.seg << 16;
+                            load_codes<H0 / 4>(w[u], a.codes + __umul24(pos, (uint32_t)a.M));
+                            bq[u] = *reinterpret_cast<const float *>(
+                                reinterpret_cast<const char *>(a.dlx) + (pos << 2));
+                        }
+                    } else {
+                        issue_loads(c0, cb, S, w, bq, sg);
+#pragma unroll
+                        for (int u = 0; u < U; ++u) sg[u] <<= 16;
+                    }
                     if (d_n > 0) drain_finish();
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
                     if (count >= kWave) drain_issue();
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         const float sum = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
-                        const int cl = blk * U * kWave + u * kWave + lane;
+                        const int cl = cb + u * kWave + lane;
                         const float thr = abandon_threshold(bq[u], sqrt_tau0);
-                        const bool alive = cl < S && !(sum > thr);
+                        const bool alive = full ? !(sum > thr) : (cl < S && !(sum > thr));
                         const unsigned long long m = __ballot(alive);
-                        if (alive)
-                            ring[(head + count + __popcll(m & lt_mask)) & (kRing - 1)] =
-                                ((uint32_t)sg[u] << 16) | (uint32_t)cl;
+                        if (alive) {
+                            const uint32_t below = __builtin_amdgcn_mbcnt_hi(
+                                (uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                            ring[(head + count + below) & (kRing - 1)] = (uint32_t)sg[u] | (uint32_t)cl;
+                        }
                         count += __popcll(m);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
