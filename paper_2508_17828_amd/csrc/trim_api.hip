@@ -251,12 +251,22 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
                    float *lut_out, int32_t mfma, void *stream) {
     if (nq < 0 || d <= 0 || M <= 0) return TRIM_INVALID_ARG;
     if (d % M) return TRIM_UNSUPPORTED_SHAPE;
-    if (mfma) return TRIM_UNSUPPORTED_SHAPE;
+    const int dsub = d / M;
+    if (mfma && dsub != 4 && dsub != 8) return TRIM_UNSUPPORTED_SHAPE;
     if (nq == 0) return TRIM_OK;
     if (!queries || !codebooks || !lut_out) return TRIM_INVALID_ARG;
     if (!aligned16(codebooks) || nq > 0x7fffffff) return TRIM_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int dsub = d / M;
+    if (mfma) {
+        const dim3 grid((unsigned)((nq + 15) / 16), (unsigned)((M + 3) / 4));
+        if (grid.y > 65535) return TRIM_UNSUPPORTED_SHAPE;
+        if (dsub == 4)
+            hipLaunchKernelGGL(lut_mfma_kernel<4>, grid, dim3(256), 0, st, queries, nq, d, codebooks, M, lut_out);
+        else
+            hipLaunchKernelGGL(lut_mfma_kernel<8>, grid, dim3(256), 0, st, queries, nq, d, codebooks, M, lut_out);
+        HIP_TRY(hipGetLastError());
+        return TRIM_OK;
+    }
     const int jper = 8;
     // grid.y is limited to 65535: walk the queries in slabs
     for (int64_t q0 = 0; q0 < nq; q0 += 65535) {

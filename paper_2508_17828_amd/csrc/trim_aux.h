@@ -85,6 +85,60 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
     build_table_rows(lut + ((size_t)q * M + j0) * kC, q_lds, codebooks, dsub, j0, nj);
 }
 
+// ---- distance table on the matrix cores (expanded form) ----
+// T[q][j][c] = max(0, (||q_j||^2 + ||c||^2) - 2 q_j.c).  One wave computes a tile of 16 queries
+// x 256 centroids of one subspace: the cross terms are 16 MFMA tiles 16x16 with depth 4
+// (v_mfma_f32_16x16x4_f32; two of them per tile for sub-vectors of length 8).
+// Operand layout of that instruction for lane l: A[row l%16][k l/16], B[k l/16][col l%16],
+// D[row 4*(l/16)+r][col l%16] in result register r.
+// The contraction depth is only d/M, so each MFMA (256 FMAs ... per 1 KB stored) leaves the
+// kernel bound by writing the table, not by the matrix cores.
+template <int DSUB>
+__global__ __launch_bounds__(256) void lut_mfma_kernel(const float *__restrict__ queries, int64_t nq,
+                                                       int d, const float *__restrict__ codebooks,
+                                                       int M, float *__restrict__ lut) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (j >= M) return;  // whole wave
+    const int64_t q0 = (int64_t)blockIdx.x * 16;
+    const int li = lane & 15, lg = lane >> 4;
+    // A operand: query row q0+li, elements k = lg (and lg+4 for DSUB == 8)
+    const int64_t qa = q0 + li < nq ? q0 + li : nq - 1;
+    const float *qrow = queries + (size_t)qa * d + (size_t)j * DSUB;
+    const float a0 = qrow[lg];
+    const float a1 = DSUB == 8 ? qrow[lg + 4] : 0.0f;
+    // squared norms of the 4 query rows this lane stores (rows 4*lg + r)
+    float qn[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int64_t qr = q0 + 4 * lg + r < nq ? q0 + 4 * lg + r : nq - 1;
+        const float *p = queries + (size_t)qr * d + (size_t)j * DSUB;
+        float acc = 0.0f;
+#pragma unroll
+        for (int t = 0; t < DSUB; ++t) acc = __builtin_fmaf(p[t], p[t], acc);
+        qn[r] = acc;
+    }
+    const float *cb = codebooks + (size_t)j * kC * DSUB;
+    for (int c0 = 0; c0 < kC; c0 += 16) {
+        const float *crow = cb + (size_t)(c0 + li) * DSUB;   // centroid column li of this tile
+        float cn = 0.0f;
+#pragma unroll
+        for (int t = 0; t < DSUB; ++t) cn = __builtin_fmaf(crow[t], crow[t], cn);
+        v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, crow[lg], acc, 0, 0, 0);
+        if (DSUB == 8) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, crow[lg + 4], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t q = q0 + 4 * lg + r;
+            if (q < nq) {
+                const float t = __builtin_fmaf(-2.0f, acc[r], qn[r] + cn);
+                lut[((size_t)q * M + j) * kC + c0 + li] = t > 0.0f ? t : 0.0f;
+            }
+        }
+    }
+}
+
 // ---- range search: offsets from per-chunk counts (single workgroup) ----
 // counts [nq*nsplit] -> chunk_base [nq*nsplit] (exclusive prefix), out_offsets [nq+1],
 // *required = total.

@@ -87,6 +87,28 @@ def test_build_lut(T, oracle, name):
     np.testing.assert_array_equal(lut.cpu().numpy().view(np.uint32), ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("name", ["c1", "c2s", "c3s", "c4s"])
+def test_build_lut_matrix_cores(T, oracle, name):
+    # expanded form on the MFMA units: equal to the direct form up to rounding of the
+    # cancelling terms, i.e. relative to ||q_j||^2 + ||c||^2 (not to the entry itself)
+    b = case(name)
+    gi, q, _ = to_dev(T, b)
+    lut = T.trim_build_lut(q, gi.codebooks, mfma=True).cpu().numpy()
+    ref = oracle.build_lut(b.queries, b.index.codebooks).astype(np.float64)
+    M, dsub = b.index.M, b.index.d // b.index.M
+    qn = (b.queries.astype(np.float64).reshape(-1, M, dsub) ** 2).sum(-1)          # [nq][M]
+    cn = (b.index.codebooks.astype(np.float64) ** 2).sum(-1)                       # [M][256]
+    scale = qn[:, :, None] + cn[None, :, :]
+    assert np.all(lut >= 0)
+    assert np.max(np.abs(lut - ref) / scale) < 2e-6
+    # and a strict scan fed with this table still returns the brute-force neighbours except
+    # where two candidates are tied to within that rounding
+    got = T.trim_search_knn(gi, q, 10, 0.0, 256, probes=to_dev(T, b)[2],
+                            lut=T.trim_build_lut(q, gi.codebooks, mfma=True))
+    bi, bd = oracle.brute_knn(b.index, b.queries, 10, b.probes)
+    assert (got["ids"].cpu().numpy() == bi).mean() > 0.999
+
+
 # ---- trim_ivf_probe ----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("name", ["c2s", "c4s", "c5s"])
