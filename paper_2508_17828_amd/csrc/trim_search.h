@@ -141,8 +141,8 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
         int32_t vi = r_id[0];
 #pragma unroll
         for (int s = 1; s < E; ++s) if (s == ks) { vd = r_d2[s]; vi = r_id[s]; }
-        t_d2 = __shfl(vd, kl);
-        t_id = __shfl(vi, kl);
+        t_d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vd), kl));  // kl is uniform
+        t_id = __builtin_amdgcn_readlane(vi, kl);
     };
     load_kth();
     for (int i0 = 0; i0 < ns; i0 += kWave) {
@@ -155,16 +155,18 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
             const unsigned long long m = __ballot(pending && hit_less(d2, id, t_d2, t_id));
             if (m == 0) break;
             const int src = __ffsll((long long)m) - 1;
-            const float xd2 = __shfl(d2, src);
-            const int32_t xid = __shfl(id, src);
+            const float xd2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d2), src));
+            const int32_t xid = __builtin_amdgcn_readlane(id, src);  // src is the same in all lanes
             if (lane == src) pending = false;
             // rank = number of entries that are not greater than the item (a prefix of R)
             int rank = 0;
 #pragma unroll
             for (int s = 0; s < E; ++s)
                 rank += __popcll(__ballot(!hit_less(xd2, xid, r_d2[s], r_id[s])));
-            const float c_d2 = __shfl_up(r_d2[E - 1], 1);
-            const int32_t c_id = __shfl_up(r_id[E - 1], 1);
+            // last slot of the lane below (whole-wave shift right by one lane; lane 0 unused)
+            const float c_d2 = __int_as_float(
+                __builtin_amdgcn_update_dpp(0, __float_as_int(r_d2[E - 1]), 0x138, 0xf, 0xf, false));
+            const int32_t c_id = __builtin_amdgcn_update_dpp(0, r_id[E - 1], 0x138, 0xf, 0xf, false);
 #pragma unroll
             for (int s = E - 1; s >= 0; --s) {
                 const int g = lane * E + s;
