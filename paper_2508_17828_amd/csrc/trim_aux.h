@@ -349,15 +349,19 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         }
     }
     __syncthreads();
-    const int halfn = npow2 >> 1;
-    for (int size = 2; size <= npow2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int w = tid; w < QT * halfn; w += T) {
-                const int qi = w / halfn, i = w - qi * halfn;
-                const int lo = ((i / stride) * stride << 1) + (i % stride);
+    // bitonic sort of each query's keys; all sizes are powers of two, so the index arithmetic
+    // is shifts and masks (lg_* are base-2 logarithms)
+    const int lg_n = 31 - __builtin_clz(npow2);
+    const int lg_half = lg_n - 1;
+    for (int lg_size = 1; lg_size <= lg_n; ++lg_size) {
+        for (int lg_stride = lg_size - 1; lg_stride >= 0; --lg_stride) {
+            const int stride = 1 << lg_stride;
+            for (int w = tid; w < (QT << lg_half); w += T) {
+                const int qi = w >> lg_half, i = w & ((1 << lg_half) - 1);
+                const int lo = ((i >> lg_stride) << (lg_stride + 1)) | (i & (stride - 1));
                 const int hi = lo + stride;
-                const bool up = ((lo & size) == 0);
-                unsigned long long *kq = keys + (size_t)qi * npow2;
+                const bool up = ((lo >> lg_size) & 1) == 0;
+                unsigned long long *kq = keys + ((size_t)qi << lg_n);
                 const unsigned long long x = kq[lo], y = kq[hi];
                 if ((x > y) == up) { kq[lo] = y; kq[hi] = x; }
             }
