@@ -107,19 +107,31 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     return false;
 }
 
-template <int MODE>
-int launch_search(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
+template <int MODE, int E>
+int launch_search_e(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
     void (*fn)(const SearchArgs) = nullptr;
     switch (pl.vec) {
-        case 4: fn = search_kernel<MODE, 4>; break;
-        case 2: fn = search_kernel<MODE, 2>; break;
-        default: fn = search_kernel<MODE, 1>; break;
+        case 4: fn = search_kernel<MODE, 4, E>; break;
+        case 2: fn = search_kernel<MODE, 2, E>; break;
+        default: fn = search_kernel<MODE, 1, E>; break;
     }
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds));
     hipLaunchKernelGGL(fn, grid, dim3(pl.threads), pl.lds, st, a);
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
+}
+
+// k decides how many result entries a lane of the merging wave holds (result_slots).
+template <int MODE>
+int launch_search(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
+    if (MODE == kRange) return launch_search_e<MODE, 1>(a, pl, grid, st);
+    switch (result_slots(a.k)) {
+        case 1: return launch_search_e<MODE, 1>(a, pl, grid, st);
+        case 2: return launch_search_e<MODE, 2>(a, pl, grid, st);
+        case 4: return launch_search_e<MODE, 4>(a, pl, grid, st);
+        default: return launch_search_e<MODE, 16>(a, pl, grid, st);
+    }
 }
 
 int check_index(const trim_index_view *ix) {

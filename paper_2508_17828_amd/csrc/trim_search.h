@@ -184,25 +184,9 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
     if (lane == 0) ctl->tau = t_d2;  // +inf while R holds fewer than k entries
 }
 
-// The wide variants are kept out of line so that their registers do not add to the
-// pressure of the scan loop.
-__device__ __attribute__((noinline)) void merge_batch_wide(const float *sd2, const int32_t *sid, int ns,
-                                                           float *rd2, int32_t *rid, Ctl *ctl, int k,
-                                                           int lane) {
-    if (result_slots(k) == 4) merge_batch<4>(sd2, sid, ns, rd2, rid, ctl, k, lane);
-    else merge_batch<16>(sd2, sid, ns, rd2, rid, ctl, k, lane);
-}
-
-__device__ __forceinline__ void merge_dispatch(const float *sd2, const int32_t *sid, int ns, float *rd2,
-                                               int32_t *rid, Ctl *ctl, int k, int lane) {
-    switch (result_slots(k)) {
-        case 1: merge_batch<1>(sd2, sid, ns, rd2, rid, ctl, k, lane); break;
-        case 2: merge_batch<2>(sd2, sid, ns, rd2, rid, ctl, k, lane); break;
-        default: merge_batch_wide(sd2, sid, ns, rd2, rid, ctl, k, lane); break;
-    }
-}
-
-template <int MODE, int VEC>
+// E = result_slots(k) is a template parameter of the kernel, so that the common small-k case
+// does not carry the registers of the wide result sets.
+template <int MODE, int VEC, int E>
 __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     float *tab = reinterpret_cast<float *>(smem);
@@ -245,7 +229,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
     // ---- prologue: query, segment table, table ----
     for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
     if (MODE == kKnn)
-        for (int g = tid; g < kWave * result_slots(a.k); g += T) { rd2[g] = __builtin_inff(); rid[g] = kEmptyId; }
+        for (int g = tid; g < kWave * E; g += T) { rd2[g] = __builtin_inff(); rid[g] = kEmptyId; }
     for (int p = tid; p < nseg; p += T) {
         int64_t s = 0, e = a.n;
         if (a.nseg > 0) {
@@ -366,7 +350,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         }
         __syncthreads();
         TRIM_TICK(4);
-        if (MODE == kKnn && tid < kWave) merge_dispatch(sd2, spos, ns, rd2, rid, ctl, a.k, lane);
+        if (MODE == kKnn && tid < kWave) merge_batch<E>(sd2, spos, ns, rd2, rid, ctl, a.k, lane);
         if (tid == 0) {
             ctl->nexact += ns;
             ctl->nsurv = 0;
