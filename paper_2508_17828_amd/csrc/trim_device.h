@@ -213,6 +213,34 @@ __device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const ui
     return s;
 }
 
+// Table sums of two candidates over the same 8 subspaces (2 code dwords each), with the
+// sixteen LDS reads issued before the first addition so that their latencies overlap.
+__device__ __forceinline__ void gather8_pair(uint32_t tab_base, const uint32_t (&wa)[2],
+                                             const uint32_t (&wb)[2], float &sa, float &sb) {
+    float ta[8], tb[8];
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+        const uint32_t row = tab_base + (v * 4) * kC * 4;
+        ta[4 * v + 0] = lds_f32(row + byte_times4<0>(wa[v]));
+        ta[4 * v + 1] = lds_f32(row + 1 * kC * 4 + byte_times4<1>(wa[v]));
+        ta[4 * v + 2] = lds_f32(row + 2 * kC * 4 + byte_times4<2>(wa[v]));
+        ta[4 * v + 3] = lds_f32(row + 3 * kC * 4 + byte_times4<3>(wa[v]));
+    }
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+        const uint32_t row = tab_base + (v * 4) * kC * 4;
+        tb[4 * v + 0] = lds_f32(row + byte_times4<0>(wb[v]));
+        tb[4 * v + 1] = lds_f32(row + 1 * kC * 4 + byte_times4<1>(wb[v]));
+        tb[4 * v + 2] = lds_f32(row + 2 * kC * 4 + byte_times4<2>(wb[v]));
+        tb[4 * v + 3] = lds_f32(row + 3 * kC * 4 + byte_times4<3>(wb[v]));
+    }
+    float a = 0.0f, b = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a = a + ta[i]; b = b + tb[i]; }
+    sa = a;
+    sb = b;
+}
+
 template <int VEC> struct CodeVec;
 template <> struct CodeVec<4> { using type = uint4; };
 template <> struct CodeVec<2> { using type = uint2; };

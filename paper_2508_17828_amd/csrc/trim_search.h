@@ -518,9 +518,19 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     if (d_n > 0) drain_finish();
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
                     if (count >= kWave) drain_issue();
+                    float sums[U];
+                    if constexpr (H0 == 8 && U % 2 == 0) {
+#pragma unroll
+                        for (int u = 0; u < U; u += 2)
+                            gather8_pair(kTabLds, w[u], w[u + 1], sums[u], sums[u + 1]);
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < U; ++u)
+                            sums[u] = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
+                    }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        const float sum = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
+                        const float sum = sums[u];
                         const int cl = cb + u * kWave + lane;
                         const float thr = abandon_threshold(bq[u], sqrt_tau0);
                         const bool alive = full ? !(sum > thr) : (cl < S && !(sum > thr));
