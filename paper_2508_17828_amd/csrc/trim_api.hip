@@ -6,8 +6,6 @@
 
 #include <cmath>
 #include <cstdio>
-#include <cstdlib>
-#include <mutex>
 
 #include "trim_aux.h"
 #include "trim_search.h"
@@ -52,10 +50,9 @@ constexpr int kSpanTarget = 4096;
 constexpr int kMaxBatchesPerSpan = 1024;
 
 bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
-    static const int span_target = getenv("TRIM_SPAN") ? atoi(getenv("TRIM_SPAN")) : kSpanTarget;
     if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
     const int nsegs = nseg > 0 ? nseg : 1;
-    int nbatch = span_target / batch;
+    int nbatch = kSpanTarget / batch;
     if (nbatch < 1) nbatch = 1;
     if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
     const int span = nbatch * batch;
@@ -178,7 +175,6 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap;
     a.small_addr = ix->n < (int64_t(1) << 24) && ix->n * (int64_t)ix->M < (int64_t(1) << 32) &&
                    ix->M < (1 << 24);
-    if (getenv("TRIM_NO_CRUISE")) a.cruise = 0;
 }
 
 int fill_u32(uint32_t *p, size_t count, uint32_t v, hipStream_t st) {

@@ -645,9 +645,6 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     // ---- later rounds: dense over the wave's queue ----
                     h1 = h0 + 32 < a.Mp ? h0 + 32 : a.Mp;
                     const bool fin = last_ph && h1 == a.Mp;
-#ifdef TRIM_EXP_NO_R1
-                    qn = 0;
-#endif
                     for (int i0 = 0; i0 < qn; i0 += kWave) {
                         const int i = i0 + lane;
                         bool alive = i < qn;
@@ -709,9 +706,7 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
         TRIM_TICK(2);
         for (int b = 0; b < nb; ++b) {
             if (cnt0[b] == 0) continue;  // same value for every thread: no barrier needed
-#ifdef TRIM_EXP_NO_STAGEB
-            continue;
-#endif
+
             const float tau = ctl->tau;
             const int l0 = b * a.batch;
             const int blen = l0 + a.batch < span ? a.batch : span - l0;
