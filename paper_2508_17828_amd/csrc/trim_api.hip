@@ -44,62 +44,91 @@ struct Plan {
 // Decide table phases, block size and LDS layout for a search launch.
 // cap = survivor-list capacity (max(batch,k) for kNN, round size for range).
 // batch = candidates per threshold update (range: = cap).  The span of candidates bounded
-// between two barriers is the largest multiple of batch up to kSpanTarget that fits
-// (at least one batch, at most kMaxBatchesPerSpan batches).
-constexpr int kSpanTarget = 4096;
+// between two barriers on the span-by-span path is the largest multiple of batch up to the
+// span target (at least one batch, at most kMaxBatchesPerSpan batches).  In kNN mode that
+// path only serves the first stretch after the seed and the rare overflow of a cruise
+// stretch, so its span is kept short and the LDS goes to residency instead: the layout is
+// fitted to the smallest footprint tier (most workgroups per CU) that holds it.
+constexpr int kSpanKnn = 1024;
+constexpr int kSpanRange = 4096;
 constexpr int kMaxBatchesPerSpan = 1024;
+constexpr int kPossMin = 512;    // smallest possibles list worth cruising with
+constexpr int kPossMax = 2048;
+
+// Block size and LDS bytes per workgroup for 4, 3, 2 and 1 workgroups per CU (LDS is handed
+// out in 1280-byte granules).  Three 512-thread workgroups are 6 waves per SIMD: only the
+// kernel instances built for that register budget (result_slots == 1) can use that tier.
+struct Tier { int threads; size_t lds; bool needs_6_waves; };
+constexpr Tier kTiers[] = {{256, 40960, false}, {512, 53760, true}, {512, 81920, false},
+                           {1024, kLdsBytes, false}};
 
 bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
     if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
     const int nsegs = nseg > 0 ? nseg : 1;
-    int nbatch = kSpanTarget / batch;
+    int nbatch = (range ? kSpanRange : kSpanKnn) / batch;
     if (nbatch < 1) nbatch = 1;
     if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
     const int span = nbatch * batch;
+    if (span > 65535) return false;
     // cruise stretches: up to 61440 candidates (16-bit queue entries) and 1024 batches
     int cruise = 61440 < 1024 * (int64_t)batch ? 61440 : 1024 * batch;
     cruise = cruise / batch * batch;
     if (range || cruise < 2 * span) cruise = 0;
     const int ncnt = cruise / batch > nbatch ? cruise / batch : nbatch;
-    // two work-queue arrays of 16-bit entries; a wave's share of a span is rounded up to 64
-    const size_t wq_bytes = up16((size_t)(span + 64 * 16) * 2 * 2);
-    if (span > 65535) return false;
-    size_t fixed = up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) + up16((size_t)nsegs * 4) +
-                   up16((size_t)cap * 4) * (range ? 3 : 2) + up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
-                   up16((size_t)span * 4) + up16((size_t)ncnt * 4) + wq_bytes;
     for (int P = 1; P <= M / 4; ++P) {
         if (M % P) continue;
         const int Mp = M / P;
         if (Mp % 4) continue;
         const size_t tab = (size_t)Mp * kC * 4;
-        if (tab + fixed > kLdsBytes) continue;
-        pl->P = P;
-        pl->Mp = Mp;
-        pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
-        size_t off = tab;
-        pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
-        pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
-        pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
-        pl->off_spos = (uint32_t)off; off += up16((size_t)cap * 4);
-        pl->off_sd2 = (uint32_t)off;  off += up16((size_t)cap * 4);
-        pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
-        pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
-        pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
-        pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
-        pl->off_plb = (uint32_t)off;  off += up16((size_t)span * 4);
-        pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
-        pl->off_wq = (uint32_t)off;   off += wq_bytes;
-        pl->span = span;
-        pl->lds = off;
-        // block size: enough waves per CU whatever the LDS footprint allows
-        const size_t per_cu = kLdsBytes / off;  // workgroups per CU by LDS
-        pl->threads = per_cu >= 4 ? 256 : per_cu >= 2 ? 512 : 1024;
-        const int nwaves = pl->threads / 64;
-        pl->wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
-        pl->cruise = P == 1 ? cruise : 0;  // table phases need block-wide barriers
-        pl->poss_cap = span / 2;
-        if ((size_t)nwaves * kRing * 4 > wq_bytes) pl->cruise = 0;
-        return true;
+        const bool can_cruise = cruise > 0 && P == 1;  // table phases need block-wide barriers
+        for (const Tier &tier : kTiers) {
+            if (tier.needs_6_waves && result_slots(k) != 1) continue;
+            const int nwaves = tier.threads / 64;
+            // a wave's share of a span is rounded up to 64; two queue arrays of 16-bit entries
+            const int wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
+            size_t wq_bytes = (size_t)2 * nwaves * wqcap * 2;
+            if (can_cruise && wq_bytes < (size_t)nwaves * kRing * 4) wq_bytes = (size_t)nwaves * kRing * 4;
+            // the exact distances of a batch's survivors reuse the queue area: queues are
+            // only live while bounds are computed, distances only afterwards
+            if (wq_bytes < (size_t)cap * 4) wq_bytes = (size_t)cap * 4;
+            wq_bytes = up16(wq_bytes);
+            const size_t rest = tab + up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) +
+                                up16((size_t)nsegs * 4) + up16((size_t)cap * 4) * (range ? 2 : 1) +
+                                up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
+                                up16((size_t)ncnt * 4) + wq_bytes;
+            // bounds of a span; in cruise mode the same area holds the possibles list
+            size_t plb = up16((size_t)span * 4);
+            if (can_cruise && plb < (size_t)kPossMin * 8) plb = (size_t)kPossMin * 8;
+            if (rest + plb > tier.lds) continue;
+            if (can_cruise) {
+                size_t room = (tier.lds - rest) / 16 * 16;
+                if (room > (size_t)kPossMax * 8) room = (size_t)kPossMax * 8;
+                if (room > plb) plb = room;
+            }
+            pl->P = P;
+            pl->Mp = Mp;
+            pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
+            size_t off = tab;
+            pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
+            pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
+            pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
+            pl->off_spos = (uint32_t)off; off += up16((size_t)cap * 4);
+            pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
+            pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+            pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+            pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
+            pl->off_plb = (uint32_t)off;  off += plb;
+            pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
+            pl->off_wq = (uint32_t)off;   off += wq_bytes;
+            pl->off_sd2 = pl->off_wq;
+            pl->span = span;
+            pl->lds = off;
+            pl->threads = tier.threads;
+            pl->wqcap = wqcap;
+            pl->cruise = can_cruise ? cruise : 0;
+            pl->poss_cap = (int)(plb / 8);
+            return true;
+        }
     }
     return false;
 }

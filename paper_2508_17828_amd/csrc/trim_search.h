@@ -82,7 +82,7 @@ struct Ctl {
     int32_t nexact;
     int32_t nposs;       // cruise: number of possibles found in the stretch
 };
-constexpr int kRing = 512;  // entries of a wave's ring queue in cruise mode
+constexpr int kRing = 256;  // entries of a wave's ring queue in cruise mode
 
 // Load or build the table rows [j0, j0+nj) of query q into LDS.
 __device__ __forceinline__ void fill_table(float *tab, const SearchArgs &a, const float *q_lds,
@@ -185,16 +185,19 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
 }
 
 // E = result_slots(k) is a template parameter of the kernel, so that the common small-k case
-// does not carry the registers of the wide result sets.
+// does not carry the registers of the wide result sets.  That instance is held to 80
+// registers (6 waves per SIMD), so that three 512-thread workgroups share a CU.
+constexpr int kSmallKWavesPerSimd = 6;
 template <int MODE, int VEC, int E>
-__global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(E == 1 ? kSmallKWavesPerSimd : 4)))
+void search_kernel(const SearchArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     float *tab = reinterpret_cast<float *>(smem);
     float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
     int *segp = reinterpret_cast<int *>(smem + a.off_segp);   // [nseg+1] prefix of lengths
     int *segd = reinterpret_cast<int *>(smem + a.off_segd);   // [nseg] start - prefix
     int32_t *spos = reinterpret_cast<int32_t *>(smem + a.off_spos);  // survivor position -> id
-    float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // partial s, then d2
+    float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // exact d2 (shares the queue area)
     int32_t *sidx = reinterpret_cast<int32_t *>(smem + a.off_sidx);  // range: scan-order number
     float *plbs = reinterpret_cast<float *>(smem + a.off_plb);       // [span] partial s, then bound
     int *cnt0 = reinterpret_cast<int *>(smem + a.off_cnt);           // per-batch counts
@@ -530,6 +533,12 @@ __global__ __launch_bounds__(1024) void search_kernel(const SearchArgs a) {
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
+                        if (u == U / 2 && count >= 2 * kWave) {
+                            // a ring holds 4 x 64 entries: make room half way through the block
+                            if (d_n > 0) drain_finish();
+                            drain_issue();
+                            drain_finish();
+                        }
                         const float sum = sums[u];
                         const int cl = cb + u * kWave + lane;
                         const float thr = abandon_threshold(bq[u], sqrt_tau0);
