@@ -64,6 +64,7 @@ typedef struct trim_index_view {
     const float *dlx;       /* [n] */
     const int32_t *ids;     /* [n] or NULL */
     const float *codebooks; /* [M][256][d/M] */
+    const void *scan_head;  /* [n] records of 12 bytes or NULL: see trim_pack_scan_head */
 } trim_index_view;
 
 /* Which stored positions a query scans, and in what order: the lists probes[q][0],
@@ -100,6 +101,20 @@ int trim_shape_supported(int32_t d, int32_t M);
  */
 int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
                 uint8_t *codes_out, float *dlx_out, void *stream);
+
+/*
+ * Storage layout for the scan (the stored landmark codes and distances of Section 3.3,
+ * preprocessing): head_out[x] = the 12 bytes {codes[x][0..7], dlx[x]}.  The kNN scan bounds
+ * every candidate over its first 8 subspaces before it looks at the rest of the code, and
+ * with this array it reads those 8 code bytes and the landmark distance as one contiguous
+ * record instead of from two arrays.  It is a copy: results do not depend on whether
+ * trim_index_view.scan_head is given, provided it was packed from the same codes and dlx
+ * (it is not checked against them).  Needs M % 8 == 0 (else TRIM_UNSUPPORTED_SHAPE).
+ * codes [n][M] device, dlx [n] device, head_out [n][12 bytes] device, 4-byte aligned.
+ */
+#define TRIM_SCAN_HEAD_BYTES 12
+int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32_t M,
+                        void *head_out, void *stream);
 
 /*
  * Query processing, operation 1 (Section 3.3; the distance table of Section 2.2):

@@ -168,6 +168,8 @@ int check_index(const trim_index_view *ix) {
     if (ix->n > 0 && (!ix->base || !ix->codes || !ix->dlx)) return TRIM_INVALID_ARG;
     if (!aligned16(ix->base) || !aligned16(ix->codes) || !aligned16(ix->codebooks))
         return TRIM_INVALID_ARG;
+    if (ix->scan_head && ((reinterpret_cast<uintptr_t>(ix->scan_head) & 3u) || ix->M % 8))
+        return TRIM_INVALID_ARG;
     return TRIM_OK;
 }
 
@@ -182,7 +184,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
                  const trim_candidates *cand, float gamma, const trim_stats *stats,
                  uint32_t *mask, int64_t mask_words, const Plan &pl) {
     a.base = ix->base; a.codes = ix->codes; a.dlx = ix->dlx; a.ids = ix->ids;
-    a.codebooks = ix->codebooks; a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
+    a.codebooks = ix->codebooks; a.head = static_cast<const uint32_t *>(ix->scan_head); a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
     a.queries = queries; a.lut = lut; a.order = nullptr;
     a.list_offsets = cand ? cand->list_offsets : nullptr;
     a.probes = cand ? cand->probes : nullptr;
@@ -280,6 +282,23 @@ int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks,
         hipLaunchKernelGGL(encode_kernel<8>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
     else
         hipLaunchKernelGGL(encode_kernel<0>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32_t M,
+                        void *head_out, void *stream) {
+    if (n < 0 || n >= (int64_t(1) << 31) || M <= 0) return TRIM_INVALID_ARG;
+    if (M % 8) return TRIM_UNSUPPORTED_SHAPE;
+    if (n == 0) return TRIM_OK;
+    if (!codes || !dlx || !head_out) return TRIM_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(codes) & 7u) || (reinterpret_cast<uintptr_t>(head_out) & 3u))
+        return TRIM_INVALID_ARG;
+    size_t blocks = ((size_t)n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(pack_scan_head_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), codes, dlx, n, M,
+                       static_cast<uint32_t *>(head_out));
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }
@@ -493,11 +512,11 @@ const char *trim_version(void) { return "0.1"; }
 
 #ifdef TRIM_PHASE_TIMING
 // Profiling builds only: read (and optionally clear) the per-phase cycle totals.
-int trim_debug_phase_ticks(unsigned long long *out8, int reset) {
+int trim_debug_phase_ticks(unsigned long long *out16, int reset) {
     HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_phase_ticks), 8 * sizeof(unsigned long long)));
+    HIP_TRY(hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_phase_ticks), 16 * sizeof(unsigned long long)));
     if (reset) {
-        unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        unsigned long long z[16] = {};
         HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_phase_ticks), z, sizeof(z)));
     }
     return TRIM_OK;

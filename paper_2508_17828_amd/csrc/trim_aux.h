@@ -13,6 +13,18 @@ __global__ void fill_u32_kernel(uint32_t *p, size_t count, uint32_t v) {
         p[i] = v;
 }
 
+// ---- scan head: {code bytes 0..7, landmark distance} of every vector as one 12-byte record ----
+__global__ void pack_scan_head_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ dlx,
+                                      int64_t n, int M, uint32_t *__restrict__ head) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * M);  // M % 8 == 0
+        head[3 * i + 0] = c.x;
+        head[3 * i + 1] = c.y;
+        head[3 * i + 2] = __float_as_uint(dlx[i]);
+    }
+}
+
 // ---- PQ encode (Section 3.3, preprocessing step 1) ----
 // One thread per vector; the block stages one subspace's 256 centroids in LDS at a time.
 // DSUB > 0: sub-vector length known at compile time (kept in registers); DSUB == 0: generic.

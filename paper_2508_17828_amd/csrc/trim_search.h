@@ -9,10 +9,10 @@
 
 // Optional per-phase cycle accounting (profiling builds only: -DTRIM_PHASE_TIMING).
 #ifdef TRIM_PHASE_TIMING
-__device__ unsigned long long g_phase_ticks[8];
-#define TRIM_TICK_INIT() unsigned long long _acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long _last = clock64();
+__device__ unsigned long long g_phase_ticks[16];
+#define TRIM_TICK_INIT() unsigned long long _acc[16] = {}; unsigned long long _last = clock64();
 #define TRIM_TICK(i) do { if (threadIdx.x == 0) { unsigned long long _n = clock64(); _acc[i] += _n - _last; _last = _n; } } while (0)
-#define TRIM_TICK_FLUSH() do { if (threadIdx.x == 0) { for (int _i = 0; _i < 8; ++_i) atomicAdd(&g_phase_ticks[_i], _acc[_i]); } } while (0)
+#define TRIM_TICK_FLUSH() do { if (threadIdx.x == 0) { for (int _i = 0; _i < 16; ++_i) atomicAdd(&g_phase_ticks[_i], _acc[_i]); } } while (0)
 #else
 #define TRIM_TICK_INIT()
 #define TRIM_TICK(i)
@@ -34,6 +34,7 @@ struct SearchArgs {
     const float *dlx;
     const int32_t *ids;
     const float *codebooks;
+    const uint32_t *head;  // optional [n][3]: code bytes 0..7 and dlx of each vector
     int64_t n;
     int32_t d, M, dsub;
     // queries, optional processing order, optional prebuilt tables
@@ -72,6 +73,12 @@ struct SearchArgs {
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
     int32_t small_addr;  // n < 2^24 and n*M < 2^32: 24-bit multiply and 32-bit offsets suffice
     int32_t poss_cap;  // capacity of the possibles list
+};
+
+// One record of the optional scan head.
+struct __attribute__((packed, aligned(4))) HeadRecord {
+    uint32_t w0, w1;  // code bytes 0..3, 4..7
+    float b;          // landmark distance
 };
 
 struct Ctl {
@@ -380,7 +387,8 @@ void search_kernel(const SearchArgs a) {
     // threshold, which reproduces the batch-by-batch rule exactly.
     constexpr int H0 = VEC >= 2 ? 8 : 4;   // subspaces bounded in round 0
     constexpr int U = 4;                   // candidates per lane in flight in round 0
-    const int wave = tid >> 6, nwaves = T >> 6;
+    // the wave number, in a scalar register: everything derived from it stays uniform
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = T >> 6;
     // This wave's slice [lo, hi) of a span of the given length.
     auto wave_slice = [&](int span_len, int &lo, int &hi) {
         const int wchunk = ((span_len + nwaves - 1) / nwaves + kWave - 1) & ~(kWave - 1);
@@ -495,6 +503,10 @@ void search_kernel(const SearchArgs a) {
                     d_n = 0;
                 };
                 const int nblk = (S + U * kWave - 1) / (U * kWave);
+                // the wave's own cursor into the segment table, in scalar registers
+                int s_seg = 0;
+                int s_end = __builtin_amdgcn_readfirstlane(segp[1]);
+                int s_delta = __builtin_amdgcn_readfirstlane(segd[0]);
                 for (int blk = wave; blk < nblk; blk += nwaves) {
                     // this block's loads fly while the previous drain is finished; the next
                     // drain's loads fly while this block is bounded
@@ -502,25 +514,52 @@ void search_kernel(const SearchArgs a) {
                     float bq[U];
                     int sg[U];
                     const int cb = blk * U * kWave;
-                    const bool full = a.small_addr && cb + U * kWave <= S;  // same for the wave
+                    // same for the whole wave
+                    const bool full = H0 == 8 && a.head && a.small_addr && cb + U * kWave <= S;
                     if (full) {
-                        // whole block in range, 32-bit byte offsets from uniform bases
+                        // whole block in range, 32-bit byte offsets from uniform bases; the
+                        // segment of 64 consecutive candidates is found with scalar arithmetic
+                        // unless they straddle a segment boundary
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
-                            const uint32_t pos = (uint32_t)cur.pos(c0 + cb + u * kWave + lane, segp, segd);
-                            sg[u] = cur.seg << 16;
-                            load_codes<H0 / 4>(w[u], a.codes + __umul24(pos, (uint32_t)a.M));
-                            bq[u] = *reinterpret_cast<const float *>(
-                                reinterpret_cast<const char *>(a.dlx) + (pos << 2));
+                            const int cf = c0 + cb + u * kWave;  // uniform
+                            while (cf >= s_end) {                // cf < total: terminates
+                                ++s_seg;
+                                s_end = __builtin_amdgcn_readfirstlane(segp[s_seg + 1]);
+                                s_delta = __builtin_amdgcn_readfirstlane(segd[s_seg]);
+                            }
+                            uint32_t pos;
+                            if (cf + kWave <= s_end) {
+                                pos = (uint32_t)(cf + s_delta) + (uint32_t)lane;
+                                sg[u] = s_seg << 16;
+                            } else {
+                                int seg = s_seg, end = s_end, delta = s_delta;
+                                const int c = cf + lane;
+                                while (c >= end) {
+                                    ++seg;
+                                    end = segp[seg + 1];
+                                    delta = segd[seg];
+                                }
+                                pos = (uint32_t)(c + delta);
+                                sg[u] = seg << 16;
+                            }
+                            const HeadRecord r = *reinterpret_cast<const HeadRecord *>(
+                                reinterpret_cast<const char *>(a.head) + (size_t)(uint32_t)__umul24(pos, 12u));
+                            w[u][0] = r.w0;
+                            w[u][H0 / 4 - 1] = r.w1;  // H0 == 8 here
+                            bq[u] = r.b;
                         }
                     } else {
                         issue_loads(c0, cb, S, w, bq, sg);
 #pragma unroll
                         for (int u = 0; u < U; ++u) sg[u] <<= 16;
                     }
+                    TRIM_TICK(8);
                     if (d_n > 0) drain_finish();
+                    TRIM_TICK(9);
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
                     if (count >= kWave) drain_issue();
+                    TRIM_TICK(10);
                     float sums[U];
                     if constexpr (H0 == 8 && U % 2 == 0) {
 #pragma unroll
@@ -531,6 +570,7 @@ void search_kernel(const SearchArgs a) {
                         for (int u = 0; u < U; ++u)
                             sums[u] = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
                     }
+                    TRIM_TICK(11);
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         if (u == U / 2 && count >= 2 * kWave) {
@@ -545,17 +585,20 @@ void search_kernel(const SearchArgs a) {
                         const bool alive = full ? !(sum > thr) : (cl < S && !(sum > thr));
                         const unsigned long long m = __ballot(alive);
                         if (alive) {
-                            const uint32_t below = __builtin_amdgcn_mbcnt_hi(
-                                (uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                            ring[(head + count + below) & (kRing - 1)] = (uint32_t)sg[u] | (uint32_t)cl;
+                            const uint32_t at = __builtin_amdgcn_mbcnt_hi(
+                                (uint32_t)(m >> 32),
+                                __builtin_amdgcn_mbcnt_lo((uint32_t)m, (uint32_t)(head + count)));
+                            ring[at & (kRing - 1)] = (uint32_t)sg[u] | (uint32_t)cl;
                         }
                         count += __popcll(m);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
+                    TRIM_TICK(12);
                 }
                 if (d_n > 0) drain_finish();
                 while (count > 0) { drain_issue(); drain_finish(); }
+                TRIM_TICK(13);
             }
             __syncthreads();
             TRIM_TICK(6);

@@ -79,8 +79,9 @@ def build_workload(w: synth.Workload, device: str = "cuda:0", pq_train: int = 65
         base = base[order].contiguous()
         ids = order.to(torch.int32)
     codes, dlx = trim.trim_encode(base, codebooks)
+    head = trim.trim_pack_scan_head(codes, dlx) if codes.shape[1] % 8 == 0 else None
     index = trim.Index(base, codes, dlx, codebooks, ids=ids, list_offsets=list_offsets,
-                       max_list_len=max_len)
+                       max_list_len=max_len, scan_head=head)
     return BuiltWorkload(w, index, queries, centroids)
 
 

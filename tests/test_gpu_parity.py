@@ -31,6 +31,8 @@ def to_dev(T, b):
     gi = T.Index(t(ix.base), t(ix.codes), t(ix.dlx), t(ix.codebooks), ids=t(ix.ids),
                  list_offsets=t(ix.list_offsets),
                  max_list_len=int(np.diff(ix.list_offsets).max()) if ix.list_offsets is not None else 0)
+    if ix.codes.shape[1] % 8 == 0:
+        gi.scan_head = T.trim_pack_scan_head(gi.codes, gi.dlx)
     return gi, t(b.queries), t(b.probes)
 
 
@@ -224,6 +226,31 @@ def test_query_order_changes_nothing_but_scheduling(T, oracle):
     keep = np.setdiff1d(np.arange(q.shape[0]), skipped)
     np.testing.assert_array_equal(got[keep], r["ids"][keep])
     assert np.all(got[skipped] == -7)
+
+
+def test_scan_head_is_a_copy_and_changes_no_result(T, oracle):
+    """trim_pack_scan_head lays out {code bytes 0..7, dlx} per vector; a search with and
+    without it returns the same bits (and both match the oracle).  c2s has candidate counts
+    far beyond one batch, so the long barrier-free stretches that use the head are run."""
+    import dataclasses
+    b = case("c2s")
+    gi, q, probes = to_dev(T, b)
+    head = gi.scan_head.cpu().numpy()
+    want = np.concatenate([b.index.codes[:, :8], b.index.dlx.view(np.uint8).reshape(-1, 4)], axis=1)
+    np.testing.assert_array_equal(head, want)
+    plain = dataclasses.replace(gi, scan_head=None)
+    for gamma, batch in ((0.0, 256), (0.5, 1024)):
+        a = T.trim_search_knn(gi, q, 10, gamma, batch, probes=probes, want_mask=True)
+        c = T.trim_search_knn(plain, q, 10, gamma, batch, probes=probes, want_mask=True)
+        for key in ("ids", "d2", "n_exact", "n_scanned", "mask"):
+            assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy()), key
+        r = oracle.search_knn(b.index, b.queries, 10, gamma, batch, b.probes)
+        np.testing.assert_array_equal(a["ids"].cpu().numpy(), r["ids"])
+        np.testing.assert_array_equal(u32(a["d2"]), r["d2"].view(np.uint32))
+    import torch
+    with pytest.raises(T.TrimError):   # M = 12: the record's 8 code bytes need M % 8 == 0
+        T.trim_pack_scan_head(torch.zeros((4, 12), dtype=torch.uint8, device="cuda"),
+                              torch.zeros((4,), dtype=torch.float32, device="cuda"))
 
 
 def test_knn_is_deterministic(T, oracle):
