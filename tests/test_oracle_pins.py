@@ -331,6 +331,48 @@ def test_batch_one_is_the_sequential_rule(oracle, tiny):
         assert nexact == r["n_exact"][qi]
 
 
+def test_batch_schedule_is_the_stated_doubling_rule(oracle, tiny):
+    """Batches of first_batch, 2*first_batch, ... capped at batch, each with tau frozen at its
+    start: replayed here candidate by candidate from the bound and the exact distance alone."""
+    b, k, gam = tiny, 5, 0.5
+    ix = b.index
+    lut = oracle.build_lut(b.queries, ix.codebooks)
+    for first, cap in ((3, 40), (1, 8), (16, 16)):
+        r = oracle.search_knn(ix, b.queries, k, gam, cap, want_mask=True, first_batch=first)
+        sizes = []
+        for qi in range(3):
+            q = b.queries[qi]
+            R = [(oracle.exact_d2(q, ix.base[pos]), pos) for pos in range(k)]
+            R.sort()
+            nexact, idx, size = k, k, first
+            while idx < ix.n:
+                tau = R[k - 1][0]
+                end = min(idx + size, ix.n)
+                if qi == 0:
+                    sizes.append(end - idx)
+                pos = np.arange(idx, end)
+                _, g = oracle.plb_pairs(lut, ix.codes, ix.dlx, np.full(len(pos), qi), pos, gam)
+                keep = pos[g <= tau]
+                got = np.array([(r["mask"][qi, p // 32] >> (p % 32)) & 1 for p in pos], bool)
+                np.testing.assert_array_equal(got, g <= tau)
+                R += [(oracle.exact_d2(q, ix.base[p]), int(p)) for p in keep]
+                R.sort(); R = R[:k]
+                nexact += len(keep)
+                idx, size = end, min(cap, 2 * size)
+            assert [p for _, p in R] == list(r["ids"][qi])
+            assert nexact == r["n_exact"][qi]
+        full = [x for x in sizes[:-1]]
+        assert full[0] == first and all(y == min(cap, 2 * x) for x, y in zip(full, full[1:]))
+    # first_batch = batch is the plain fixed-size rule; with gamma = 0 no schedule changes the result
+    a0 = oracle.search_knn(ix, b.queries, k, gam, 16, want_mask=True)
+    a1 = oracle.search_knn(ix, b.queries, k, gam, 16, want_mask=True, first_batch=16)
+    for key in ("ids", "d2", "n_exact", "mask"):
+        np.testing.assert_array_equal(a0[key], a1[key])
+    bi, _ = oracle.brute_knn(ix, b.queries, k)
+    for first, cap in ((1, 64), (5, 333), (64, 1024)):
+        np.testing.assert_array_equal(oracle.search_knn(ix, b.queries, k, 0.0, cap, first_batch=first)["ids"], bi)
+
+
 def test_short_candidate_lists_are_padded(oracle):
     w = synth.scaled(synth.WORKLOADS["C1"], 300, 3)
     b = helpers.build(w)
