@@ -30,6 +30,8 @@ def parse():
     ap.add_argument("--gamma", type=float, default=None,
                     help="relaxation to time (default: largest swept gamma with recall@k >= 0.95)")
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--first-batch", type=int, default=None,
+                    help="size of the first batch; later ones double up to --batch (0: all alike)")
     ap.add_argument("--truth-queries", type=int, default=1000,
                     help="queries used for the exact ground truth behind recall@k")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
@@ -56,6 +58,7 @@ def main():
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
     batch = args.batch or w.batch
+    first_batch = min(batch, w.first_batch if args.first_batch is None else args.first_batch)
     t0 = time.time()
     bw = index_setup.build_workload(w)
     ix, queries = bw.index, bw.queries
@@ -79,7 +82,7 @@ def main():
 
     def run_once(gamma, want_stats=True):
         pr = probes_for(queries)
-        return trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, want_stats=want_stats,
+        return trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, first_batch=first_batch, want_stats=want_stats,
                                     query_order=order_for(pr))
 
     # ---- sweep of the relaxation parameter (untimed quality numbers, short timing) ----
@@ -114,7 +117,7 @@ def main():
            torch.empty((nq, k), dtype=torch.float32, device="cuda"))
     for _ in range(args.warmup):
         pr = probes_for(queries)
-        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, want_stats=False, out=out,
+        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, first_batch=first_batch, want_stats=False, out=out,
                              query_order=order_for(pr))
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -124,7 +127,7 @@ def main():
         pr = probes_for(queries)
         order = order_for(pr)
         ev[s][1].record()
-        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, want_stats=False, out=out,
+        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, first_batch=first_batch, want_stats=False, out=out,
                              query_order=order)
         ev[s][2].record()
     torch.cuda.synchronize()
@@ -146,7 +149,8 @@ def main():
     traffic = None
     try:
         rec = json.load(open(os.path.join(ROOT, "profiles", "search_kernel_c2_traffic.json")))
-        if rec["workload"] == w.name and rec["gamma"] == gamma and rec["batch"] == batch:
+        if (rec["workload"] == w.name and rec["gamma"] == gamma and rec["batch"] == batch
+                and rec.get("first_batch", 0) == first_batch):
             traffic = rec["traffic_bytes_per_launch"]
     except (OSError, ValueError, KeyError):
         pass
@@ -172,7 +176,7 @@ def main():
             qs = np.ascontiguousarray(qh[lo:hi_])
             t1 = time.perf_counter()
             ph = trim_oracle.ivf_probe(qs, ch, w.nprobe) if w.nlist else None
-            ro = trim_oracle.search_knn(oix, qs, k, gamma, batch, ph)
+            ro = trim_oracle.search_knn(oix, qs, k, gamma, batch, ph, first_batch=first_batch or None)
             cpu_s += time.perf_counter() - t1
             same = same and bool(np.array_equal(ro["ids"], got[lo:hi_]))
             done += hi_ - lo
@@ -188,7 +192,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n} base x {nq} queries, d={w.d}, PQ M={w.M}x256, "
                                f"IVF nlist={w.nlist} nprobe={w.nprobe}, kNN k={k}",
-                   "gamma": gamma, "batch": batch, "recall_at_k": chosen["recall"],
+                   "gamma": gamma, "batch": batch, "first_batch": first_batch, "recall_at_k": chosen["recall"],
                    "recall_truth": f"exact kNN over all n for the first {nt} queries",
                    "pruning_ratio": chosen["pruning_ratio"],
                    "timed": "probe selection + query ordering + fused table/scan/refine/select, inputs in HBM",

@@ -131,14 +131,18 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
 /*
  * Approximate kNN by the scan of Section 4.2 (problem statement: Section 2.1).
  * Per query: the result set R (size k) is first filled with the first k candidates, all with
- * exact distances; the remaining candidates are taken in batches of `batch`; inside a batch
- * the threshold tau (k-th squared distance in R; +inf while |R| < k) is frozen; a candidate
+ * exact distances; the remaining candidates are taken in batches; inside a batch the
+ * threshold tau (k-th squared distance in R; +inf while |R| < k) is frozen; a candidate
  * survives iff g <= tau (Equation 3); survivors get exact distances and are merged into R.
- * batch = 1 is the paper's vector-at-a-time rule.
+ * The first batch holds `first_batch` candidates, every later one twice as many as the one
+ * before, up to `batch`; first_batch = 0 or = batch makes all batches `batch` long.
+ * batch = 1 is the paper's vector-at-a-time rule; short early batches stay close to it
+ * while R is still poor and tau falls fast, which spares most of the exact distances a
+ * long first batch would spend.
  *
  * queries [nq][d] device.  lut: device [nq][M][256] or NULL (tables are then built inside
  * the kernel from index->codebooks).  cand: host struct or NULL.  1 <= k <= TRIM_MAX_K,
- * 1 <= batch <= TRIM_MAX_BATCH, gamma >= 0.
+ * 1 <= batch <= TRIM_MAX_BATCH, 0 <= first_batch <= batch, gamma >= 0.
  * query_order: device [nq] or NULL; a permutation of 0..nq-1 giving the order in which
  * queries are handed to the GPU (see trim_query_order).  It changes scheduling only: every
  * query's results are written at its own row and do not depend on the order.
@@ -151,7 +155,8 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
  */
 int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
                     const float *lut, const trim_candidates *cand, int32_t k, float gamma,
-                    int32_t batch, const int32_t *query_order, int32_t *out_ids, float *out_d2,
+                    int32_t batch, int32_t first_batch, const int32_t *query_order,
+                    int32_t *out_ids, float *out_d2,
                     const trim_stats *stats, uint32_t *survivor_mask, int64_t mask_words,
                     void *stream);
 

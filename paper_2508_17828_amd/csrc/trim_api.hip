@@ -337,7 +337,8 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
 
 int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
                     const float *lut, const trim_candidates *cand, int32_t k, float gamma,
-                    int32_t batch, const int32_t *query_order, int32_t *out_ids, float *out_d2,
+                    int32_t batch, int32_t first_batch, const int32_t *query_order,
+                    int32_t *out_ids, float *out_d2,
                     const trim_stats *stats, uint32_t *survivor_mask, int64_t mask_words,
                     void *stream) {
     int rc = check_index(index);
@@ -345,6 +346,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     if ((rc = check_cand(cand))) return rc;
     if (nq < 0 || nq > 0x7fffffff - 8 || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
         return TRIM_INVALID_ARG;
+    if (first_batch < 0 || first_batch > batch) return TRIM_INVALID_ARG;
     if (!(gamma >= 0.0f) || std::isinf(gamma)) return TRIM_INVALID_ARG;
     if (nq == 0) return TRIM_OK;
     if (!queries || !out_ids || !out_d2) return TRIM_INVALID_ARG;
@@ -360,6 +362,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     SearchArgs a{};
     fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
     a.k = k; a.batch = batch; a.radius2 = 0.0f;
+    a.first_batch = first_batch > 0 ? first_batch : batch;
     a.out_ids = out_ids; a.out_d2 = out_d2;
     a.chunk = 0; a.nsplit = 1;
     a.nq = nq; a.order = query_order;
@@ -416,7 +419,7 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
 
     SearchArgs a{};
     fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
-    a.k = 1; a.batch = kRangeRound;
+    a.k = 1; a.batch = kRangeRound; a.first_batch = kRangeRound;
     a.radius2 = radius * radius;
     a.chunk = L.chunk; a.nsplit = L.nsplit;
     a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;

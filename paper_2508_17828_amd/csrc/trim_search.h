@@ -51,6 +51,7 @@ struct SearchArgs {
     int32_t P, Mp;
     // search parameters
     int32_t k, batch;  // range: batch = span = survivor-list capacity per round
+    int32_t first_batch;  // kNN: batches double from this size up to batch (= batch: no ramp)
     int32_t span;      // candidates bounded between two barriers (a multiple of batch)
     float two_gamma;
     float radius2;
@@ -415,10 +416,12 @@ void search_kernel(const SearchArgs a) {
     };
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
+    int ramp = MODE == kKnn ? a.first_batch : a.batch;  // next batch size while below a.batch
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
         const float sqrt_tau0 = abandon_scale(tau0);  // scaled: see abandon_threshold
+        const bool ramping = ramp < a.batch;  // the batches before the first full-size one
 
         // ---- cruise: once tau is finite, bound a long stretch of candidates with no block-wide
         // barrier at all.  Every wave runs its own software pipeline over interleaved blocks of
@@ -430,7 +433,8 @@ void search_kernel(const SearchArgs a) {
         // replayed in order over that list.  If the list overflows, nothing has been
         // committed: the stretch is redone span by span below.
         // (The first span after the seed is always taken span by span: it is what makes tau tight.)
-        if (cruise > 0 && c0 > c_begin + kseed && tau0 < __builtin_inff() && c_end - c0 > a.span) {
+        if (cruise > 0 && !ramping && c0 > c_begin + kseed && tau0 < __builtin_inff() &&
+            c_end - c0 > a.span) {
             const int S = c0 + cruise < c_end ? cruise : c_end - c0;
             const int nb = (S + a.batch - 1) / a.batch;
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
@@ -635,7 +639,9 @@ void search_kernel(const SearchArgs a) {
 
         // The first stretch after the seed is a single batch: its threshold (from the k seeds)
         // is loose, so nothing is abandoned early; one batch is enough to make tau tight.
-        const int span_len = c0 == c_begin + kseed ? a.batch : a.span;
+        // While the batches still grow, each is taken alone.
+        const int span_len = ramping ? ramp : c0 == c_begin + kseed ? a.batch : a.span;
+        if (ramping) ramp = 2 * ramp < a.batch ? 2 * ramp : a.batch;
         const int span = c0 + span_len < c_end ? span_len : c_end - c0;
         const int nb = (span + a.batch - 1) / a.batch;
         for (int b = tid; b < nb; b += T) cnt0[b] = 0;

@@ -79,7 +79,7 @@ def lib() -> C.CDLL:
         L.trim_build_lut.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                      C.c_void_p, C.c_int32, C.c_void_p]
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
-                                      C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_search_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -196,7 +196,7 @@ def trim_build_lut(queries: torch.Tensor, codebooks: torch.Tensor, mfma: bool = 
 def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, batch: int,
                     probes: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
                     want_stats: bool = True, want_mask: bool = False, out=None,
-                    query_order: Optional[torch.Tensor] = None):
+                    query_order: Optional[torch.Tensor] = None, first_batch: int = 0):
     """Returns dict(ids [nq][k] int32, d2 [nq][k] float32, n_scanned, n_exact, mask)."""
     nq = queries.shape[0]
     dev = queries.device
@@ -221,7 +221,7 @@ def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, b
     _check(lib().trim_search_knn(C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
                                  _ptr(lut, torch.float32, "lut"),
                                  C.byref(cand) if cand is not None else None, k, gamma, batch,
-                                 _ptr(query_order, torch.int32, "query_order"),
+                                 first_batch, _ptr(query_order, torch.int32, "query_order"),
                                  _ptr(out_ids, torch.int32, "out_ids"),
                                  _ptr(out_d2, torch.float32, "out_d2"),
                                  C.byref(stats) if stats is not None else None,

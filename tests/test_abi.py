@@ -57,11 +57,11 @@ def test_host_side_validation(L):
     assert L.trim_version().decode().count(".") == 1
     assert L.trim_range_workspace_bytes(100, 10_000) >= 100 * 10_000 // 8
     # null index / bad sizes are refused before any HIP call
-    assert L.trim_search_knn(None, None, 1, None, None, 10, 0.0, 64, None, None, None, None, None, 0, None) == -1
+    assert L.trim_search_knn(None, None, 1, None, None, 10, 0.0, 64, 0, None, None, None, None, None, 0, None) == -1
     view = trim._IndexView(10, 128, 32, None, None, None, None, None)
-    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, None, None, None, None, None, 0, None) == -1
+    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, 0, None, None, None, None, None, 0, None) == -1
     view = trim._IndexView(0, 128, 6, None, None, None, None, None)
-    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, None, None, None, None, None, 0, None) == -2
+    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, 0, None, None, None, None, None, 0, None) == -2
     assert L.trim_encode(None, 5, 128, None, 32, None, None, None) == -1
     assert L.trim_encode(None, 0, 128, None, 32, None, None, None) == 0
     assert L.trim_encode(None, 5, 128, None, 6, None, None, None) == -2

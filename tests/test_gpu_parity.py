@@ -126,11 +126,13 @@ def test_ivf_probe(T, oracle, name):
 
 # ---- trim_search_knn ---------------------------------------------------------------------------
 
-def check_knn(T, oracle, b, k, gamma, batch, prebuilt_lut=False):
+def check_knn(T, oracle, b, k, gamma, batch, prebuilt_lut=False, first_batch=0):
     gi, q, probes = to_dev(T, b)
     lut = T.trim_build_lut(q, gi.codebooks) if prebuilt_lut else None
-    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, lut=lut, want_mask=True)
-    ref = oracle.search_knn(b.index, b.queries, k, gamma, batch, b.probes, want_mask=True)
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, lut=lut, want_mask=True,
+                            first_batch=first_batch)
+    ref = oracle.search_knn(b.index, b.queries, k, gamma, batch, b.probes, want_mask=True,
+                            first_batch=first_batch or None)
     np.testing.assert_array_equal(got["n_scanned"].cpu().numpy(), ref["n_scanned"])
     mw = ref["mask"].shape[1]
     np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
@@ -156,6 +158,16 @@ def test_knn_shapes(T, oracle, name, k, batch, gamma):
     if gamma == 0.0:
         bi, _ = oracle.brute_knn(case(name).index, case(name).queries, k, case(name).probes)
         np.testing.assert_array_equal(got["ids"].cpu().numpy(), bi)
+
+
+@pytest.mark.parametrize("name,k,batch,first", [("c2s", 10, 1024, 64), ("c2s", 10, 1024, 1),
+                                                ("c2s", 70, 333, 5), ("c5s", 10, 1024, 128),
+                                                ("c3s", 100, 4096, 256), ("c4s", 10, 2048, 64),
+                                                ("c1", 10, 100, 7), ("c1", 10, 4096, 4096)])
+@pytest.mark.parametrize("gamma", [0.0, 0.5])
+def test_knn_growing_batches(T, oracle, name, k, batch, first, gamma):
+    """Batches that double from `first` up to `batch` (first = batch: the fixed-size rule)."""
+    check_knn(T, oracle, case(name), k, gamma, batch, first_batch=first)
 
 
 @pytest.mark.parametrize("name", ["c2s", "c4s"])
@@ -267,10 +279,11 @@ def test_argument_errors(T):
     b = case("c1")
     gi, q, _ = to_dev(T, b)
     for kw in (dict(k=0), dict(k=T.TRIM_MAX_K + 1), dict(batch=0), dict(batch=T.TRIM_MAX_BATCH + 1),
-               dict(gamma=-0.1), dict(gamma=float("nan"))):
-        args = dict(k=10, gamma=0.0, batch=64); args.update(kw)
+               dict(gamma=-0.1), dict(gamma=float("nan")), dict(first_batch=65), dict(first_batch=-1)):
+        args = dict(k=10, gamma=0.0, batch=64, first_batch=0); args.update(kw)
         with pytest.raises(T.TrimError):
-            T.trim_search_knn(gi, q, args["k"], args["gamma"], args["batch"])
+            T.trim_search_knn(gi, q, args["k"], args["gamma"], args["batch"],
+                              first_batch=args["first_batch"])
     assert not T.trim_shape_supported(130, 16) and not T.trim_shape_supported(128, 6)
     assert T.trim_shape_supported(128, 32) and T.trim_shape_supported(1536, 192)
     with pytest.raises(TypeError):
