@@ -660,7 +660,52 @@ void search_kernel(const SearchArgs a) {
         uint16_t *qin = wq + (size_t)wave * a.wqcap;
         uint16_t *qout = wq + (size_t)(nwaves + wave) * a.wqcap;
         int qn = 0;  // length of this wave's queue (same in every lane)
-        for (int ph = 0; ph < a.P; ++ph) {
+        // A batch that runs against a loose threshold (the first ones after the seed) abandons
+        // nobody, so the rounds would only add dependent memory latencies: its candidates are
+        // bounded in one go instead, two per lane, with all their loads issued together.
+        constexpr int kDirectChunks = 2;  // code chunks of 4*VEC bytes a lane keeps per candidate
+        const bool direct = MODE == kKnn && VEC == 4 && a.P == 1 && a.M <= 4 * VEC * kDirectChunks &&
+                            a.M % (4 * VEC) == 0 && (ramping || c0 == c_begin + kseed);
+        if (direct) {
+            constexpr int UD = 2;
+            for (int base = wlo; base < whi; base += UD * kWave) {
+                uint32_t w[UD][kDirectChunks][VEC];
+                float b[UD];
+#pragma unroll
+                for (int u = 0; u < UD; ++u) {
+                    const int cl = base + u * kWave + lane;
+                    b[u] = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < kDirectChunks; ++c)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) w[u][c][v] = 0;
+                    if (cl < whi) {
+                        const int pos = cur.pos(c0 + cl, segp, segd);
+                        const uint8_t *cp = a.codes + (size_t)pos * a.M;
+                        b[u] = a.dlx[pos];
+#pragma unroll
+                        for (int c = 0; c < kDirectChunks; ++c)
+                            if (c * 4 * VEC < a.M) load_codes<VEC>(w[u][c], cp + c * 4 * VEC);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UD; ++u) {
+                    const int cl = base + u * kWave + lane;
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < kDirectChunks; ++c)
+                        if (c * 4 * VEC < a.M)
+                            sum = gather_add<VEC>(sum, kTabLds + c * 4 * VEC * (kC * 4), w[u][c],
+                                                  __builtin_inff());
+                    if (cl < whi) {
+                        const float g = plb_from_s(sum, b[u], a.two_gamma);
+                        plbs[cl] = g;
+                        if (g <= tau0) atomicAdd(&cnt0[cl / a.batch], 1);
+                    }
+                }
+            }
+        }
+        for (int ph = 0; ph < (direct ? 0 : a.P); ++ph) {
             if (a.P > 1) {
                 __syncthreads();
                 fill_table(tab, a, q_lds, q, ph * a.Mp, a.Mp);
