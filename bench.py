@@ -147,16 +147,23 @@ def main():
     # HBM bytes per launch as measured with rocprofv3 counters (recorded profile of this kernel
     # on this workload; null when the timed configuration is not the profiled one)
     traffic = None
+    valu = None
     try:
         rec = json.load(open(os.path.join(ROOT, "profiles", "search_kernel_c2_traffic.json")))
         if (rec["workload"] == w.name and rec["gamma"] == gamma and rec["batch"] == batch
                 and rec.get("first_batch", 0) == first_batch):
             traffic = rec["traffic_bytes_per_launch"]
+            # vector-ALU view of the same launch: wave instructions (SQ_INSTS_VALU of the recorded
+            # profile) against 256 CUs x 4 SIMDs x one wave instruction per 4 cycles at 2.4 GHz
+            insts = rec["valu_wave_instructions_per_launch"]
+            peak = 256 * 4 * 2.4e9 / 4
+            valu = dict(wave_instructions=insts, peak_per_s=peak,
+                        frac=round(insts / (scan_ms * 1e-3) / peak, 4))
     except (OSError, ValueError, KeyError):
         pass
     roofline = dict(bound="hbm", kernel="search_kernel<knn>", achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=traffic, kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
+                    traffic=traffic, valu=valu, kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
                     scan_stream_gbs=round(scan_bytes / (scan_ms * 1e-3) / 1e9, 1),
                     candidates_per_s=round(chosen["n_scanned"] / (scan_ms * 1e-3), 1))
 
