@@ -82,7 +82,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
         const size_t tab = (size_t)Mp * kC * 4;
         const bool can_cruise = cruise > 0 && P == 1;  // table phases need block-wide barriers
         for (const Tier &tier : kTiers) {
-            if (tier.needs_6_waves && result_slots(k) != 1) continue;
+            if (tier.needs_6_waves && (range || result_slots(k) != 1)) continue;
             const int nwaves = tier.threads / 64;
             // a wave's share of a span is rounded up to 64; two queue arrays of 16-bit entries
             const int wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;

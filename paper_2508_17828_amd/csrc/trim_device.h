@@ -131,7 +131,9 @@ __device__ __forceinline__ float exact_d2_half(const float *__restrict__ row,
 }
 
 // Four rows at once (same arithmetic per row as exact_d2_half; the four loads of each step
-// are in flight together).
+// are in flight together).  PIPE: the next step's four loads are issued before the current
+// step is reduced (twice the registers; for long rows).
+template <bool PIPE>
 __device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
                                                  const float *__restrict__ r1,
                                                  const float *__restrict__ r2,
@@ -143,10 +145,24 @@ __device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
     const float4 *q4 = reinterpret_cast<const float4 *>(q);
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     const int ng = d >> 2;
+    float4 nxt[4];
+    if (PIPE && lane32 < ng) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) nxt[u] = rows[u][lane32];
+    }
     for (int g = lane32; g < ng; g += 32) {
         float4 xv[4];
+        if (PIPE) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) xv[u] = rows[u][g];
+            for (int u = 0; u < 4; ++u) xv[u] = nxt[u];
+            if (g + 32 < ng) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) nxt[u] = rows[u][g + 32];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xv[u] = rows[u][g];
+        }
         const float4 qv = q4[g];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

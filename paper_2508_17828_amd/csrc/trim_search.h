@@ -197,7 +197,8 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
 // registers (6 waves per SIMD), so that three 512-thread workgroups share a CU.
 constexpr int kSmallKWavesPerSimd = 6;
 template <int MODE, int VEC, int E>
-__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(E == 1 ? kSmallKWavesPerSimd : 4)))
+__global__ __launch_bounds__(1024)
+__attribute__((amdgpu_waves_per_eu(MODE == kKnn && E == 1 ? kSmallKWavesPerSimd : 4)))
 void search_kernel(const SearchArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     float *tab = reinterpret_cast<float *>(smem);
@@ -341,7 +342,7 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) rid4[u] = (MODE == kKnn && a.ids) ? a.ids[pos[u]] : pos[u];
             float d2[4];
-            exact_d2_half_x4(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
+            exact_d2_half_x4<(MODE != kKnn || E > 1)>(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
                              a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d, q_lds,
                              a.d, lane32, d2);
             if (lane32 == 0) {
@@ -715,7 +716,12 @@ void search_kernel(const SearchArgs a) {
             for (int h0 = 0; h0 < a.Mp;) {
                 int h1;
                 int qnext = 0;
-                if (ph == 0 && h0 == 0) {
+                // Long codes: the first 8 subspaces are a small share of the sum and abandon
+                // nobody, so the first round of phase 0 is a bulk round over the whole slice.
+                const bool slice_round = ph == 0 && h0 == 0;
+                constexpr int kPieces = (MODE == kKnn && E == 1) ? 0 : 6;
+                const bool bulk_first = kPieces > 0 && VEC == 4 && a.M >= 64;
+                if (slice_round && !bulk_first) {
                     // ---- round 0 ----
                     h1 = H0 < a.Mp ? H0 : a.Mp;
                     const bool fin = last_ph && h1 == a.Mp;
@@ -746,20 +752,49 @@ void search_kernel(const SearchArgs a) {
                     TRIM_TICK(6);
                 } else {
                     // ---- later rounds: dense over the wave's queue ----
-                    h1 = h0 + 32 < a.Mp ? h0 + 32 : a.Mp;
+                    // With 16-byte code loads a round takes up to 104 subspaces (an 8-byte piece
+                    // up to the next 16-byte boundary, then up to kPieces 16-byte pieces) and issues
+                    // all its loads together with the landmark distance: one memory latency per
+                    // queue entry instead of one per piece.  Otherwise: 32 subspaces, piece by piece.
+                    // (not in the 80-register kNN instance, which meets later rounds only on fallback)
+                    const bool lead8 = kPieces > 0 && VEC == 4 && (h0 & 15) == 8 && h0 + 8 <= a.Mp;
+                    const int ja = h0 + (lead8 ? 8 : 0);
+                    int n16 = kPieces > 0 && VEC == 4 && (ja & 15) == 0 ? (a.Mp - ja) / 16 : 0;
+                    if (n16 > kPieces) n16 = kPieces;
+                    const bool bulk = lead8 || n16 > 0;
+                    h1 = bulk ? ja + 16 * n16 : (h0 + 32 < a.Mp ? h0 + 32 : a.Mp);
                     const bool fin = last_ph && h1 == a.Mp;
-                    for (int i0 = 0; i0 < qn; i0 += kWave) {
+                    // entries: the wave's queue, or (first round of phase 0) its whole slice
+                    const int nent = slice_round ? (whi > wlo ? whi - wlo : 0) : qn;
+                    for (int i0 = 0; i0 < nent; i0 += kWave) {
                         const int i = i0 + lane;
-                        bool alive = i < qn;
+                        bool alive = i < nent;
                         int cl = 0;
                         if (alive) {
-                            cl = qin[i];
-                            const int pos = locate(c0 + cl);
+                            cl = slice_round ? wlo + i : qin[i];
+                            const int pos = slice_round ? cur.pos(c0 + cl, segp, segd) : locate(c0 + cl);
+                            const uint8_t *cp = a.codes + (size_t)pos * a.M + ph * a.Mp;
+                            uint32_t w8[2] = {0, 0};
+                            uint32_t w16[kPieces > 0 ? kPieces : 1][4];
+                            if (bulk) {
+                                if (lead8) load_codes<2>(w8, cp + h0);
+#pragma unroll
+                                for (int c = 0; c < kPieces; ++c)
+                                    if (c < n16) load_codes<4>(w16[c], cp + ja + 16 * c);
+                            }
                             const float b = a.dlx[pos];
                             const float thr = abandon_threshold(b, sqrt_tau0);
-                            const uint8_t *cp = a.codes + (size_t)pos * a.M + ph * a.Mp;
-                            float sum = plbs[cl];
+                            float sum = slice_round ? 0.0f : plbs[cl];
                             int j = h0;
+                            if (bulk) {
+                                if (lead8) sum = gather_add<2>(sum, kTabLds + h0 * (kC * 4), w8, thr);
+#pragma unroll
+                                for (int c = 0; c < kPieces; ++c)
+                                    if (c < n16 && !(sum > thr))
+                                        sum = gather_add<4>(sum, kTabLds + (ja + 16 * c) * (kC * 4),
+                                                            w16[c], thr);
+                                j = h1;
+                            }
                             while (j < h1) {  // widest aligned load that fits, test after each
                                 if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
                                     uint32_t w[4];
