@@ -65,6 +65,7 @@ typedef struct trim_index_view {
     const int32_t *ids;     /* [n] or NULL */
     const float *codebooks; /* [M][256][d/M] */
     const void *scan_head;  /* [n] records of 12 bytes or NULL: see trim_pack_scan_head */
+    const void *codes_tiled; /* tiled copy of codes or NULL: see trim_pack_codes_tiled */
 } trim_index_view;
 
 /* Which stored positions a query scans, and in what order: the lists probes[q][0],
@@ -115,6 +116,23 @@ int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks,
 #define TRIM_SCAN_HEAD_BYTES 12
 int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32_t M,
                         void *head_out, void *stream);
+
+/*
+ * Second storage layout of the landmark codes of Section 3.3 (preprocessing), for long codes:
+ * the vectors are taken in blocks of 64, and tiled_out holds, block after block, piece 0 of
+ * the block's 64 vectors, then piece 1, ... (piece p = code bytes 16p..16p+15; a block is
+ * 64*M bytes; rows beyond n are zero).  Lanes that bound 64 consecutive vectors then read
+ * one contiguous KB per piece instead of 64 strided rows, and no byte is fetched twice when
+ * the subspaces are processed in several table phases.  It is a copy:
+ * trim_index_view.codes stays mandatory, a search reads whichever of the two suits its
+ * launch (range searches and kNN with k > 64 read the tiled copy when it is given; kNN
+ * with k <= 64 always reads the row-major array), and results do not depend on it.  Worth
+ * it for long codes (M >= 64).  Needs M % 16 == 0 (else TRIM_UNSUPPORTED_SHAPE).
+ * codes [n][M] device; tiled_out device, 16-byte aligned, trim_codes_tiled_bytes(n, M) bytes.
+ */
+size_t trim_codes_tiled_bytes(int64_t n, int32_t M);
+int trim_pack_codes_tiled(const uint8_t *codes, int64_t n, int32_t M, void *tiled_out,
+                          void *stream);
 
 /*
  * Query processing, operation 1 (Section 3.3; the distance table of Section 2.2):

@@ -170,6 +170,7 @@ int check_index(const trim_index_view *ix) {
         return TRIM_INVALID_ARG;
     if (ix->scan_head && ((reinterpret_cast<uintptr_t>(ix->scan_head) & 3u) || ix->M % 8))
         return TRIM_INVALID_ARG;
+    if (ix->codes_tiled && (!aligned16(ix->codes_tiled) || ix->M % 16)) return TRIM_INVALID_ARG;
     return TRIM_OK;
 }
 
@@ -184,7 +185,8 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
                  const trim_candidates *cand, float gamma, const trim_stats *stats,
                  uint32_t *mask, int64_t mask_words, const Plan &pl) {
     a.base = ix->base; a.codes = ix->codes; a.dlx = ix->dlx; a.ids = ix->ids;
-    a.codebooks = ix->codebooks; a.head = static_cast<const uint32_t *>(ix->scan_head); a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
+    a.codebooks = ix->codebooks; a.head = static_cast<const uint32_t *>(ix->scan_head);
+    a.codes_tiled = static_cast<const uint8_t *>(ix->codes_tiled); a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
     a.queries = queries; a.lut = lut; a.order = nullptr;
     a.list_offsets = cand ? cand->list_offsets : nullptr;
     a.probes = cand ? cand->probes : nullptr;
@@ -299,6 +301,25 @@ int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32
     hipLaunchKernelGGL(pack_scan_head_kernel, dim3((unsigned)blocks), dim3(256), 0,
                        static_cast<hipStream_t>(stream), codes, dlx, n, M,
                        static_cast<uint32_t *>(head_out));
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+size_t trim_codes_tiled_bytes(int64_t n, int32_t M) {
+    if (n <= 0 || M <= 0) return 0;
+    return (size_t)((n + 63) / 64) * 64 * (size_t)M;
+}
+
+int trim_pack_codes_tiled(const uint8_t *codes, int64_t n, int32_t M, void *tiled_out, void *stream) {
+    if (n < 0 || n >= (int64_t(1) << 31) || M <= 0) return TRIM_INVALID_ARG;
+    if (M % 16) return TRIM_UNSUPPORTED_SHAPE;
+    if (n == 0) return TRIM_OK;
+    if (!codes || !tiled_out || !aligned16(codes) || !aligned16(tiled_out)) return TRIM_INVALID_ARG;
+    const size_t total = trim_codes_tiled_bytes(n, M) / 16;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(pack_codes_tiled_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), codes, n, M, static_cast<uint4 *>(tiled_out));
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }

@@ -25,6 +25,25 @@ __global__ void pack_scan_head_kernel(const uint8_t *__restrict__ codes, const f
     }
 }
 
+// ---- tiled codes: blocks of 64 vectors, 16-byte pieces of a block's vectors contiguous ----
+// One thread per (vector slot, piece); slots beyond n are written as zeros.
+__global__ void pack_codes_tiled_kernel(const uint8_t *__restrict__ codes, int64_t n, int M,
+                                        uint4 *__restrict__ tiled) {
+    const int npiece = M >> 4;
+    const int64_t total = ((n + 63) / 64) * 64 * npiece;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total;
+         t += (int64_t)gridDim.x * blockDim.x) {
+        // t enumerates the output in order: block, piece, lane
+        const int lane = (int)(t & 63);
+        const int64_t bp = t >> 6;
+        const int piece = (int)(bp % npiece);
+        const int64_t x = (bp / npiece) * 64 + lane;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (x < n) v = *reinterpret_cast<const uint4 *>(codes + (size_t)x * M + piece * 16);
+        tiled[t] = v;
+    }
+}
+
 // ---- PQ encode (Section 3.3, preprocessing step 1) ----
 // One thread per vector; the block stages one subspace's 256 centroids in LDS at a time.
 // DSUB > 0: sub-vector length known at compile time (kept in registers); DSUB == 0: generic.

@@ -209,22 +209,33 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) {
 }
 
 // tab_base is the LDS byte address of the table row of the first of these subspaces.
+// The reads of 8 subspaces are issued together, ahead of their additions, so that their LDS
+// latencies overlap; the additions stay in subspace order.
 template <int VEC>
 __device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const uint32_t (&w)[VEC],
                                             float thr) {
+    constexpr int kRow = kC * 4;  // bytes per table row
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-        // byte b of the code word, times 4 (the byte offset inside table row v*4+b): one
-        // sub-dword-addressed shift each instead of extract + scale
-        const uint32_t o0 = byte_times4<0>(w[v]), o1 = byte_times4<1>(w[v]);
-        const uint32_t o2 = byte_times4<2>(w[v]), o3 = byte_times4<3>(w[v]);
-        const uint32_t row = tab_base + (v * 4) * kC * 4;
-        s = s + lds_f32(row + o0);
-        s = s + lds_f32(row + 1 * kC * 4 + o1);
-        s = s + lds_f32(row + 2 * kC * 4 + o2);
-        s = s + lds_f32(row + 3 * kC * 4 + o3);
+    for (int v0 = 0; v0 < VEC; v0 += 2) {
+        float t[8];
+#pragma unroll
+        for (int dv = 0; dv < 2; ++dv) {
+            if (v0 + dv < VEC) {
+                // byte b of the code word, times 4 (the byte offset inside table row v*4+b): one
+                // sub-dword-addressed shift each instead of extract + scale
+                const uint32_t cw = w[v0 + dv < VEC ? v0 + dv : 0];
+                const uint32_t row = tab_base + ((v0 + dv) * 4) * kRow;
+                t[4 * dv + 0] = lds_f32(row + byte_times4<0>(cw));
+                t[4 * dv + 1] = lds_f32(row + 1 * kRow + byte_times4<1>(cw));
+                t[4 * dv + 2] = lds_f32(row + 2 * kRow + byte_times4<2>(cw));
+                t[4 * dv + 3] = lds_f32(row + 3 * kRow + byte_times4<3>(cw));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (v0 + i / 4 < VEC) s = s + t[i];
         // early abandon every 8 subspaces (see abandon_threshold)
-        if ((v & 1) == 1 && v + 1 < VEC && s > thr) return s;
+        if (v0 + 2 < VEC && s > thr) return s;
     }
     return s;
 }

@@ -35,6 +35,7 @@ struct SearchArgs {
     const int32_t *ids;
     const float *codebooks;
     const uint32_t *head;  // optional [n][3]: code bytes 0..7 and dlx of each vector
+    const uint8_t *codes_tiled;  // optional: codes in blocks of 64 vectors x 16-byte pieces
     int64_t n;
     int32_t d, M, dsub;
     // queries, optional processing order, optional prebuilt tables
@@ -90,6 +91,25 @@ struct Ctl {
     int32_t nexact;
     int32_t nposs;       // cruise: number of possibles found in the stretch
 };
+// Where the code bytes of one stored vector are.  Row-major: consecutive.  Tiled: the vectors
+// are grouped in blocks of 64, and piece p (code bytes 16p..16p+15) of the 64 vectors of a
+// block is contiguous (1 KB), so that 64 lanes reading the same piece of 64 consecutive
+// vectors read one contiguous KB.  at(j) is valid for a load of 4, 8 or 16 bytes at a
+// multiple of its size.
+struct CodeRow {
+    const uint8_t *p;
+    uint32_t step;  // bytes from one 16-byte piece to the next
+    __device__ __forceinline__ const uint8_t *at(int j) const {
+        return p + (size_t)(uint32_t)(j >> 4) * step + (j & 15);
+    }
+};
+template <bool TILED_OK>
+__device__ __forceinline__ CodeRow code_row(const SearchArgs &a, int pos) {
+    if (TILED_OK && a.codes_tiled)
+        return CodeRow{a.codes_tiled + (((size_t)(pos >> 6) * (uint32_t)(a.M >> 4)) << 10) + ((pos & 63) << 4), 1024u};
+    return CodeRow{a.codes + (size_t)pos * a.M, 16u};
+}
+
 constexpr int kRing = 256;  // entries of a wave's ring queue in cruise mode
 
 // Load or build the table rows [j0, j0+nj) of query q into LDS.
@@ -200,6 +220,9 @@ template <int MODE, int VEC, int E>
 __global__ __launch_bounds__(1024)
 __attribute__((amdgpu_waves_per_eu(MODE == kKnn && E == 1 ? kSmallKWavesPerSimd : 4)))
 void search_kernel(const SearchArgs a) {
+    // The tiled copy of the codes is read by the instances with 16-byte code loads, except the
+    // 80-register small-k kNN instance, whose codes are short (it reads the row-major array).
+    constexpr bool kTiledOk = VEC == 4 && !(MODE == kKnn && E == 1);
     extern __shared__ __align__(16) unsigned char smem[];
     float *tab = reinterpret_cast<float *>(smem);
     float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
@@ -410,7 +433,7 @@ void search_kernel(const SearchArgs a) {
             if (cl < hi) {
                 const int pos = cur.pos(c0n + cl, segp, segd);
                 sg[u] = cur.seg;
-                load_codes<H0 / 4>(w[u], a.codes + (size_t)pos * a.M);
+                load_codes<H0 / 4>(w[u], code_row<kTiledOk>(a, pos).at(0));
                 bq[u] = a.dlx[pos];
             }
         }
@@ -460,10 +483,10 @@ void search_kernel(const SearchArgs a) {
                         const uint32_t e = ring[(head + lane) & (kRing - 1)];
                         d_cl = (int)(e & 0xffffu);
                         d_pos = c0 + d_cl + segd[e >> 16];
-                        const uint8_t *cp = a.codes + (size_t)d_pos * a.M;
+                        const CodeRow cr = code_row<kTiledOk>(a, d_pos);
                         d_b = a.dlx[d_pos];
-                        load_codes<DV>(d_w0, cp);
-                        if (two_chunks) load_codes<DV>(d_w1, cp + 4 * DV);
+                        load_codes<DV>(d_w0, cr.at(0));
+                        if (two_chunks) load_codes<DV>(d_w1, cr.at(4 * DV));
                     }
                     head = (head + d_n) & (kRing - 1);
                     count -= d_n;
@@ -471,7 +494,7 @@ void search_kernel(const SearchArgs a) {
                 auto drain_finish = [&]() {
                     if (lane < d_n) {
                         const float thr = abandon_threshold(d_b, sqrt_tau0);
-                        const uint8_t *cp = a.codes + (size_t)d_pos * a.M;
+                        const CodeRow cr = code_row<kTiledOk>(a, d_pos);
                         float sum = gather_add<DV>(0.0f, kTabLds, d_w0, thr);
                         int j = 4 * DV;
                         if (two_chunks && !(sum > thr)) {
@@ -481,17 +504,17 @@ void search_kernel(const SearchArgs a) {
                         while (j < a.M && !(sum > thr)) {  // widest aligned load that fits
                             if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
                                 uint32_t w[4];
-                                load_codes<4>(w, cp + j);
+                                load_codes<4>(w, cr.at(j));
                                 sum = gather_add<4>(sum, kTabLds + j * (kC * 4), w, thr);
                                 j += 16;
                             } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= a.M) {
                                 uint32_t w[2];
-                                load_codes<2>(w, cp + j);
+                                load_codes<2>(w, cr.at(j));
                                 sum = gather_add<2>(sum, kTabLds + j * (kC * 4), w, thr);
                                 j += 8;
                             } else {
                                 uint32_t w[1];
-                                load_codes<1>(w, cp + j);
+                                load_codes<1>(w, cr.at(j));
                                 sum = gather_add<1>(sum, kTabLds + j * (kC * 4), w, thr);
                                 j += 4;
                             }
@@ -682,11 +705,11 @@ void search_kernel(const SearchArgs a) {
                         for (int v = 0; v < VEC; ++v) w[u][c][v] = 0;
                     if (cl < whi) {
                         const int pos = cur.pos(c0 + cl, segp, segd);
-                        const uint8_t *cp = a.codes + (size_t)pos * a.M;
+                        const CodeRow cr = code_row<kTiledOk>(a, pos);
                         b[u] = a.dlx[pos];
 #pragma unroll
                         for (int c = 0; c < kDirectChunks; ++c)
-                            if (c * 4 * VEC < a.M) load_codes<VEC>(w[u][c], cp + c * 4 * VEC);
+                            if (c * 4 * VEC < a.M) load_codes<VEC>(w[u][c], cr.at(c * 4 * VEC));
                     }
                 }
 #pragma unroll
@@ -773,14 +796,15 @@ void search_kernel(const SearchArgs a) {
                         if (alive) {
                             cl = slice_round ? wlo + i : qin[i];
                             const int pos = slice_round ? cur.pos(c0 + cl, segp, segd) : locate(c0 + cl);
-                            const uint8_t *cp = a.codes + (size_t)pos * a.M + ph * a.Mp;
+                            const CodeRow cr = code_row<kTiledOk>(a, pos);
+                            const int jp = ph * a.Mp;  // first subspace of this phase
                             uint32_t w8[2] = {0, 0};
                             uint32_t w16[kPieces > 0 ? kPieces : 1][4];
                             if (bulk) {
-                                if (lead8) load_codes<2>(w8, cp + h0);
+                                if (lead8) load_codes<2>(w8, cr.at(jp + h0));
 #pragma unroll
                                 for (int c = 0; c < kPieces; ++c)
-                                    if (c < n16) load_codes<4>(w16[c], cp + ja + 16 * c);
+                                    if (c < n16) load_codes<4>(w16[c], cr.at(jp + ja + 16 * c));
                             }
                             const float b = a.dlx[pos];
                             const float thr = abandon_threshold(b, sqrt_tau0);
@@ -798,17 +822,17 @@ void search_kernel(const SearchArgs a) {
                             while (j < h1) {  // widest aligned load that fits, test after each
                                 if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
                                     uint32_t w[4];
-                                    load_codes<4>(w, cp + j);
+                                    load_codes<4>(w, cr.at(jp + j));
                                     sum = gather_add<4>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 16;
                                 } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= h1) {
                                     uint32_t w[2];
-                                    load_codes<2>(w, cp + j);
+                                    load_codes<2>(w, cr.at(jp + j));
                                     sum = gather_add<2>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 8;
                                 } else {
                                     uint32_t w[1];
-                                    load_codes<1>(w, cp + j);
+                                    load_codes<1>(w, cr.at(jp + j));
                                     sum = gather_add<1>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 4;
                                 }

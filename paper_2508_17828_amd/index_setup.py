@@ -80,8 +80,10 @@ def build_workload(w: synth.Workload, device: str = "cuda:0", pq_train: int = 65
         ids = order.to(torch.int32)
     codes, dlx = trim.trim_encode(base, codebooks)
     head = trim.trim_pack_scan_head(codes, dlx) if codes.shape[1] % 8 == 0 else None
+    # long codes are also kept in the tiled layout (see trim_pack_codes_tiled)
+    tiled = trim.trim_pack_codes_tiled(codes) if codes.shape[1] >= 64 and codes.shape[1] % 16 == 0 else None
     index = trim.Index(base, codes, dlx, codebooks, ids=ids, list_offsets=list_offsets,
-                       max_list_len=max_len, scan_head=head)
+                       max_list_len=max_len, scan_head=head, codes_tiled=tiled)
     return BuiltWorkload(w, index, queries, centroids)
 
 

@@ -20,7 +20,8 @@ TRIM_MAX_K = 1024
 TRIM_MAX_BATCH = 4096
 TRIM_MAX_NPROBE = 4096
 
-EXPORTS = ("trim_shape_supported", "trim_encode", "trim_pack_scan_head", "trim_build_lut", "trim_search_knn",
+EXPORTS = ("trim_shape_supported", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
+           "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_strerror", "trim_last_hip_error", "trim_version")
 
@@ -43,7 +44,7 @@ class TrimCapacityError(RuntimeError):
 class _IndexView(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("M", C.c_int32), ("base", C.c_void_p),
                 ("codes", C.c_void_p), ("dlx", C.c_void_p), ("ids", C.c_void_p),
-                ("codebooks", C.c_void_p), ("scan_head", C.c_void_p)]
+                ("codebooks", C.c_void_p), ("scan_head", C.c_void_p), ("codes_tiled", C.c_void_p)]
 
 
 class _Candidates(C.Structure):
@@ -76,6 +77,9 @@ def lib() -> C.CDLL:
                                   C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_pack_scan_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
                                           C.c_void_p]
+        L.trim_codes_tiled_bytes.restype = C.c_size_t
+        L.trim_codes_tiled_bytes.argtypes = [C.c_int64, C.c_int32]
+        L.trim_pack_codes_tiled.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_build_lut.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                      C.c_void_p, C.c_int32, C.c_void_p]
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
@@ -128,6 +132,7 @@ class Index:
     list_offsets: Optional[torch.Tensor] = None   # [nlist+1] int64 (device)
     max_list_len: int = 0                 # host copy of the longest list's length
     scan_head: Optional[torch.Tensor] = None      # [n][12] uint8, from trim_pack_scan_head
+    codes_tiled: Optional[torch.Tensor] = None    # uint8, from trim_pack_codes_tiled
 
     @property
     def n(self): return self.base.shape[0]
@@ -141,7 +146,8 @@ class Index:
                           _ptr(self.codes, torch.uint8, "codes"), _ptr(self.dlx, torch.float32, "dlx"),
                           _ptr(self.ids, torch.int32, "ids"),
                           _ptr(self.codebooks, torch.float32, "codebooks"),
-                          _ptr(self.scan_head, torch.uint8, "scan_head"))
+                          _ptr(self.scan_head, torch.uint8, "scan_head"),
+                          _ptr(self.codes_tiled, torch.uint8, "codes_tiled"))
 
     def _cand(self, probes: Optional[torch.Tensor], max_candidates: int = 0):
         if probes is None:
@@ -178,6 +184,15 @@ def trim_pack_scan_head(codes: torch.Tensor, dlx: torch.Tensor) -> torch.Tensor:
                                      n, M, _ptr(head, torch.uint8, "head"), _stream()),
            "trim_pack_scan_head")
     return head
+
+
+def trim_pack_codes_tiled(codes: torch.Tensor) -> torch.Tensor:
+    n, M = codes.shape
+    tiled = torch.empty((int(lib().trim_codes_tiled_bytes(n, M)),), dtype=torch.uint8, device=codes.device)
+    _check(lib().trim_pack_codes_tiled(_ptr(codes, torch.uint8, "codes"), n, M,
+                                       _ptr(tiled, torch.uint8, "codes_tiled"), _stream()),
+           "trim_pack_codes_tiled")
+    return tiled
 
 
 def trim_build_lut(queries: torch.Tensor, codebooks: torch.Tensor, mfma: bool = False,

@@ -265,6 +265,47 @@ def test_scan_head_is_a_copy_and_changes_no_result(T, oracle):
                               torch.zeros((4,), dtype=torch.float32, device="cuda"))
 
 
+@pytest.mark.parametrize("name", ["c4s", "c2s"])
+def test_tiled_codes_are_a_copy_and_change_no_result(T, oracle, name):
+    """trim_pack_codes_tiled regroups the code bytes (blocks of 64 vectors, 16-byte pieces);
+    kNN and range searches that read the tiled copy return the same bits as the row-major ones
+    and match the oracle."""
+    import dataclasses
+    b = case(name)
+    gi, q, probes = to_dev(T, b)
+    codes = b.index.codes
+    n, M = codes.shape
+    tiled = T.trim_pack_codes_tiled(gi.codes)
+    nb = (n + 63) // 64
+    padded = np.zeros((nb * 64, M), np.uint8); padded[:n] = codes
+    want = padded.reshape(nb, 64, M // 16, 16).transpose(0, 2, 1, 3).reshape(-1)
+    np.testing.assert_array_equal(tiled.cpu().numpy(), want)
+    gt = dataclasses.replace(gi, codes_tiled=tiled)
+    for gamma, batch in ((0.0, 256), (0.5, 1024)):
+        a = T.trim_search_knn(gt, q, 10, gamma, batch, probes=probes, want_mask=True)
+        c = T.trim_search_knn(gi, q, 10, gamma, batch, probes=probes, want_mask=True)
+        for key in ("ids", "d2", "n_exact", "n_scanned", "mask"):
+            assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy()), key
+        r = oracle.search_knn(b.index, b.queries, 10, gamma, batch, b.probes)
+        np.testing.assert_array_equal(a["ids"].cpu().numpy(), r["ids"])
+    # k > 64: the kNN instance that reads the tiled copy
+    a = T.trim_search_knn(gt, q, 100, 0.5, 512, probes=probes, want_mask=True)
+    r = oracle.search_knn(b.index, b.queries, 100, 0.5, 512, b.probes, want_mask=True)
+    np.testing.assert_array_equal(a["ids"].cpu().numpy(), r["ids"])
+    np.testing.assert_array_equal(a["n_exact"].cpu().numpy(), r["n_exact"])
+    np.testing.assert_array_equal(u32(a["mask"])[:, :r["mask"].shape[1]], r["mask"])
+    radius = helpers.radius_at_percentile(b, 2.0, 20, 1000)
+    a = T.trim_search_range(gt, q, radius, 0.5, probes=probes, want_mask=True)
+    r = oracle.search_range(b.index, b.queries, radius, 0.5, b.probes, want_mask=True)
+    np.testing.assert_array_equal(a["offsets"].cpu().numpy(), r["offsets"])
+    np.testing.assert_array_equal(a["ids"].cpu().numpy(), r["ids"])
+    mw = r["mask"].shape[1]
+    np.testing.assert_array_equal(u32(a["mask"])[:, :mw], r["mask"])
+    import torch
+    with pytest.raises(T.TrimError):   # M = 24 is not a whole number of 16-byte pieces
+        T.trim_pack_codes_tiled(torch.zeros((4, 24), dtype=torch.uint8, device="cuda"))
+
+
 def test_knn_is_deterministic(T, oracle):
     b = case("c5s")
     gi, q, probes = to_dev(T, b)
