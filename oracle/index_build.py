@@ -7,6 +7,13 @@ objective never increases) and determinism.
 
 Random choices (training rows, initial centroids) are inputs, never drawn here.
 Distances inside k-means use a library matmul in float64 (a library primitive as a step).
+
+train_pq_fixed / train_ivf_fixed are the same Lloyd iterations with every rounding fixed, so
+that a second implementation can reproduce the centroids bit for bit: the assignment step
+is the binary32 nearest-centroid rule of the index itself (trim_oracle.encode for a PQ
+subspace, trim_oracle.ivf_probe with one probe for the coarse lists: smallest index on
+ties), and a centroid is the float64 sum of its member rows, added in ascending row order,
+divided by their number and rounded once to binary32; an empty cluster keeps its centroid.
 """
 from __future__ import annotations
 
@@ -86,3 +93,41 @@ def ivf_assign(base: np.ndarray, centroids: np.ndarray):
     list_offsets = np.zeros(nlist + 1, dtype=np.int64)
     np.cumsum(counts, out=list_offsets[1:])
     return order, list_offsets
+
+
+def _update_fixed(x: np.ndarray, a: np.ndarray, cent: np.ndarray) -> np.ndarray:
+    """Means in float64, rows added one by one in ascending row order."""
+    K, dim = cent.shape
+    sums = np.zeros((K, dim), dtype=np.float64)
+    np.add.at(sums, a, x.astype(np.float64))       # unbuffered: sequential in row order
+    cnt = np.bincount(a, minlength=K)
+    out = cent.copy()
+    nz = cnt > 0
+    out[nz] = (sums[nz] / cnt[nz, None].astype(np.float64)).astype(np.float32)
+    return out
+
+
+def train_pq_fixed(train: np.ndarray, M: int, iters: int, init_rows: np.ndarray) -> np.ndarray:
+    """PQ codebooks [M][256][d/M] by Lloyd iterations with the fixed roundings described in
+    the header (Section 2.2: one k-means with 256 centroids per subspace)."""
+    from . import trim_oracle
+    ns, d = train.shape
+    dsub = d // M
+    assert init_rows.shape[0] == 256
+    cb = np.ascontiguousarray(train[init_rows].reshape(256, M, dsub).transpose(1, 0, 2)).astype(np.float32)
+    for _ in range(iters):
+        codes, _ = trim_oracle.encode(train, cb)
+        for j in range(M):
+            cb[j] = _update_fixed(train[:, j * dsub:(j + 1) * dsub], codes[:, j].astype(np.int64), cb[j])
+    return cb
+
+
+def train_ivf_fixed(train: np.ndarray, nlist: int, iters: int, init_rows: np.ndarray) -> np.ndarray:
+    """Coarse centroids [nlist][d] (Section 6.1: C' lists), same fixed roundings."""
+    from . import trim_oracle
+    assert init_rows.shape[0] == nlist
+    cent = np.ascontiguousarray(train[init_rows]).astype(np.float32)
+    for _ in range(iters):
+        a = trim_oracle.ivf_probe(train, cent, 1)[:, 0].astype(np.int64)
+        cent = _update_fixed(train, a, cent)
+    return cent

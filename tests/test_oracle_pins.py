@@ -398,6 +398,54 @@ def test_kmeans_objective_never_increases_and_is_deterministic():
     assert obj[-1] < obj[0]
 
 
+def test_fixed_rounding_kmeans(oracle):
+    """train_pq_fixed / train_ivf_fixed: one Lloyd step replayed by hand (assignment = argmin of
+    float64 distances where no tie is near, mean = exact rational mean), the summation order
+    shown on values where it matters, the objective never increasing, empty clusters kept."""
+    from fractions import Fraction
+    from oracle import index_build
+    rng = np.random.default_rng(5)
+    # (a) one iteration against exact arithmetic on small integers (every sum is exact)
+    train = rng.integers(0, 64, size=(600, 8)).astype(np.float32)
+    init = rng.choice(600, 256, replace=False)
+    cb = index_build.train_pq_fixed(train, 2, 1, init)
+    for j in range(2):
+        sub = train[:, 4 * j:4 * j + 4].astype(np.float64)
+        c0 = sub[init]
+        d2 = ((sub[:, None, :] - c0[None, :, :]) ** 2).sum(-1)     # exact: small integers
+        a = d2.argmin(1)                                            # first minimum = smallest index
+        for c in range(256):
+            rows = np.flatnonzero(a == c)
+            if len(rows) == 0:
+                np.testing.assert_array_equal(cb[j, c], c0[c].astype(np.float32))
+                continue
+            for t in range(4):
+                mean = Fraction(int(sub[rows, t].sum()), len(rows))
+                assert cb[j, c, t] == np.float32(float(mean))       # float64 quotient, rounded once
+    # (b) rows are added in ascending row order, in float64
+    x = np.array([[1e16], [1.0], [-1e16], [1.0]], dtype=np.float64).astype(np.float32)
+    x32 = x.astype(np.float64)
+    seq = ((x32[0, 0] + x32[1, 0]) + x32[2, 0]) + x32[3, 0]
+    got = index_build._update_fixed(x, np.zeros(4, np.int64), np.zeros((2, 1), np.float32))
+    assert got[0, 0] == np.float32(seq / 4.0) and got[1, 0] == 0.0  # cluster 1 is empty: kept
+    # (c) Lloyd's invariant with the binary32 assignment rule, PQ and coarse
+    w = synth.scaled(synth.WORKLOADS["C2"], 6000, 4, nlist=32, nprobe=4)
+    base = synth.base_vectors(w)
+    def pq_objective(cb):
+        codes, dlx = oracle.encode(base, cb)
+        return float((dlx.astype(np.float64) ** 2).mean())
+    objs = [pq_objective(index_build.train_pq_fixed(base, 32, it, np.arange(256) * 7)) for it in (0, 1, 2, 4)]
+    assert all(b <= a * (1 + 1e-6) for a, b in zip(objs, objs[1:])) and objs[-1] < objs[0]
+    cen = [index_build.train_ivf_fixed(base, 32, it, np.arange(32) * 11) for it in (0, 1, 3)]
+    def ivf_objective(c):
+        a = oracle.ivf_probe(base, c, 1)[:, 0]
+        return float(((base.astype(np.float64) - c[a].astype(np.float64)) ** 2).sum(1).mean())
+    o = [ivf_objective(c) for c in cen]
+    assert o[1] <= o[0] * (1 + 1e-6) and o[2] <= o[1] * (1 + 1e-6) and o[2] < o[0]
+    # determinism
+    np.testing.assert_array_equal(cen[2], index_build.train_ivf_fixed(base, 32, 3, np.arange(32) * 11))
+
+
 def test_ivf_lists_and_probes(oracle, tiny_ivf):
     b = tiny_ivf
     ix = b.index
