@@ -104,6 +104,26 @@ int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks,
                 uint8_t *codes_out, float *dlx_out, void *stream);
 
 /*
+ * Index construction: centroid training by Lloyd's k-means (PQ codebooks: Sections 2.2 and
+ * 3.1, one k-means with 256 centroids per subspace, t iterations; coarse lists: Section 6.1).
+ * Every rounding is fixed, so that the centroids are reproducible bit for bit: the initial
+ * centroids are the rows train[init_rows[c]]; an iteration assigns every training row to its
+ * nearest centroid by the index's own binary32 rule (trim_encode for a PQ subspace,
+ * trim_ivf_probe with one probe for the coarse lists; smallest index on ties) and then
+ * replaces every centroid by the float64 sum of its rows, added in ascending row order,
+ * divided by their number and rounded once to binary32; a centroid without rows is kept.
+ * All arrays device.  train [ns][d]; init_rows: row numbers into train ([256] for PQ, [nlist]
+ * for the coarse lists; values outside [0, ns) are clamped).  The *_ws arrays are work space
+ * whose contents on return are the last iteration's assignment (codes_ws [ns][M] with dlx_ws
+ * [ns] for PQ, assign_ws [ns] for the coarse lists).  iters >= 0.
+ */
+int trim_train_pq(const float *train, int64_t ns, int32_t d, int32_t M, int32_t iters,
+                  const int32_t *init_rows, float *codebooks_out, uint8_t *codes_ws, float *dlx_ws,
+                  void *stream);
+int trim_train_ivf(const float *train, int64_t ns, int32_t d, int32_t nlist, int32_t iters,
+                   const int32_t *init_rows, float *centroids_out, int32_t *assign_ws, void *stream);
+
+/*
  * Storage layout for the scan (the stored landmark codes and distances of Section 3.3,
  * preprocessing): head_out[x] = the 12 bytes {codes[x][0..7], dlx[x]}.  The kNN scan bounds
  * every candidate over its first 8 subspaces before it looks at the rest of the code, and

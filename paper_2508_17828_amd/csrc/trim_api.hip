@@ -305,6 +305,53 @@ int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32
     return TRIM_OK;
 }
 
+int trim_train_pq(const float *train, int64_t ns, int32_t d, int32_t M, int32_t iters,
+                  const int32_t *init_rows, float *codebooks_out, uint8_t *codes_ws, float *dlx_ws,
+                  void *stream) {
+    if (ns <= 0 || d <= 0 || M <= 0 || iters < 0) return TRIM_INVALID_ARG;
+    if (d % M || M % 4 || M > 65535) return TRIM_UNSUPPORTED_SHAPE;
+    if (!train || !init_rows || !codebooks_out || !codes_ws || !dlx_ws) return TRIM_INVALID_ARG;
+    const int dsub = d / M;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int per = kC * dsub;  // centroid coordinates per subspace
+    for (int j = 0; j < M; ++j) {
+        hipLaunchKernelGGL(kmeans_init_kernel, dim3((per + 255) / 256), dim3(256), 0, st, train, ns,
+                           (int64_t)d, j * dsub, dsub, init_rows, kC, codebooks_out + (size_t)j * per);
+    }
+    HIP_TRY(hipGetLastError());
+    for (int it = 0; it < iters; ++it) {
+        const int rc = trim_encode(train, ns, d, codebooks_out, M, codes_ws, dlx_ws, stream);
+        if (rc) return rc;
+        hipLaunchKernelGGL(kmeans_update_kernel<1>, dim3((per + 255) / 256, M), dim3(256), 0, st, train,
+                           ns, (int64_t)d, 0, dsub, static_cast<const void *>(codes_ws), (int64_t)M, kC,
+                           codebooks_out);
+        HIP_TRY(hipGetLastError());
+    }
+    return TRIM_OK;
+}
+
+int trim_train_ivf(const float *train, int64_t ns, int32_t d, int32_t nlist, int32_t iters,
+                   const int32_t *init_rows, float *centroids_out, int32_t *assign_ws, void *stream) {
+    if (ns <= 0 || d <= 0 || nlist <= 0 || iters < 0) return TRIM_INVALID_ARG;
+    if (d % 4) return TRIM_UNSUPPORTED_SHAPE;
+    if (!train || !init_rows || !centroids_out || !assign_ws) return TRIM_INVALID_ARG;
+    if ((int64_t)nlist * d > 0x7fffffff) return TRIM_UNSUPPORTED_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int per = nlist * d;
+    hipLaunchKernelGGL(kmeans_init_kernel, dim3((per + 255) / 256), dim3(256), 0, st, train, ns,
+                       (int64_t)d, 0, d, init_rows, nlist, centroids_out);
+    HIP_TRY(hipGetLastError());
+    for (int it = 0; it < iters; ++it) {
+        const int rc = trim_ivf_probe(train, ns, d, centroids_out, nlist, 1, assign_ws, stream);
+        if (rc) return rc;
+        hipLaunchKernelGGL(kmeans_update_kernel<4>, dim3((per + 255) / 256), dim3(256), 0, st, train, ns,
+                           (int64_t)d, 0, d, static_cast<const void *>(assign_ws), (int64_t)1, nlist,
+                           centroids_out);
+        HIP_TRY(hipGetLastError());
+    }
+    return TRIM_OK;
+}
+
 size_t trim_codes_tiled_bytes(int64_t n, int32_t M) {
     if (n <= 0 || M <= 0) return 0;
     return (size_t)((n + 63) / 64) * 64 * (size_t)M;

@@ -44,6 +44,61 @@ __global__ void pack_codes_tiled_kernel(const uint8_t *__restrict__ codes, int64
     }
 }
 
+// ---- centroid training (Lloyd's k-means; Sections 2.2, 3.1, 6.1) ----
+// Initial centroids: cent[c][t] = x[init_rows[c]][col0 + t].
+__global__ void kmeans_init_kernel(const float *__restrict__ x, int64_t ns, int64_t stride, int col0,
+                                   int dim, const int32_t *__restrict__ init_rows, int K,
+                                   float *__restrict__ cent) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= K * dim) return;
+    int64_t r = init_rows[e / dim];
+    r = r < 0 ? 0 : (r >= ns ? ns - 1 : r);
+    cent[e] = x[(size_t)r * stride + col0 + e % dim];
+}
+
+// Update step with every rounding fixed: thread (c, t) walks the rows in ascending order and
+// adds, in float64, coordinate col0 + t of every row assigned to c; the centroid becomes
+// sum / count rounded once to binary32; a cluster without rows keeps its centroid.
+// Assignments are read as bytes (ABYTES = 1) or 32-bit integers (ABYTES = 4) with a stride,
+// staged through LDS a chunk at a time.  grid.x * blockDim.x >= K * dim; grid.y = number of
+// independent clusterings y (PQ subspaces): columns col0 + y*dim.., assignment element y of
+// every row, centroid block y.
+template <int ABYTES>
+__global__ __launch_bounds__(256) void kmeans_update_kernel(const float *__restrict__ x, int64_t ns,
+                                                            int64_t stride, int col0, int dim,
+                                                            const void *__restrict__ assign,
+                                                            int64_t astride, int K,
+                                                            float *__restrict__ cent) {
+    constexpr int kChunk = 2048;
+    __shared__ int32_t a_lds[kChunk];
+    const int y = blockIdx.y;
+    col0 += y * dim;
+    cent += (size_t)y * K * dim;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = e < K * dim;
+    const int c = live ? e / dim : -1;
+    const int t = live ? e % dim : 0;
+    double sum = 0.0;
+    int64_t count = 0;
+    for (int64_t i0 = 0; i0 < ns; i0 += kChunk) {
+        const int m = ns - i0 < kChunk ? (int)(ns - i0) : kChunk;
+        __syncthreads();
+        for (int i = threadIdx.x; i < m; i += blockDim.x) {
+            const size_t at = (size_t)(i0 + i) * astride + y;
+            a_lds[i] = ABYTES == 1 ? (int32_t) static_cast<const uint8_t *>(assign)[at]
+                                   : static_cast<const int32_t *>(assign)[at];
+        }
+        __syncthreads();
+        for (int i = 0; i < m; ++i) {
+            if (a_lds[i] == c) {
+                sum += (double)x[(size_t)(i0 + i) * stride + col0 + t];
+                ++count;
+            }
+        }
+    }
+    if (live && count > 0) cent[e] = (float)(sum / (double)count);
+}
+
 // ---- PQ encode (Section 3.3, preprocessing step 1) ----
 // One thread per vector; the block stages one subspace's 256 centroids in LDS at a time.
 // DSUB > 0: sub-vector length known at compile time (kept in registers); DSUB == 0: generic.

@@ -1,11 +1,10 @@
-"""Workload set-up on the GPU: train PQ / IVF centroids and lay the base set out in
-list order, then encode it with libtrim.
+"""Workload set-up on the GPU: train PQ / IVF centroids, lay the base set out in list
+order, encode it and pack the scan layouts, all with libtrim's kernels.
 
 Centroid training (Lloyd's k-means; the paper: Section 3.1, cost O(mCn(d/m)t), and
 Section 6.1, C = 256 centroids per subspace, C' coarse lists) is preparation of the
-index that the scan consumes, not part of the timed scan.  It is written with torch
-tensor ops purely as a convenience for building benchmark inputs; codes, landmark
-distances, probe selection and everything timed go through libtrim's kernels.
+index that the scan consumes, not part of the timed scan.  torch is used here only to hold
+the arrays and to sort / gather the base set into list order.
 """
 from __future__ import annotations
 
@@ -13,35 +12,6 @@ import numpy as np
 import torch
 
 from . import synth, trim
-
-
-def _lloyd(x: torch.Tensor, init: torch.Tensor, iters: int) -> torch.Tensor:
-    """Batched Lloyd iterations.  x [G][ns][dim], init [G][K][dim] -> centroids [G][K][dim]."""
-    cen = init.clone()
-    G, ns, dim = x.shape
-    K = cen.shape[1]
-    xn = (x * x).sum(-1, keepdim=True)
-    ar = torch.arange(G, device=x.device)[:, None].expand(G, ns)
-    for _ in range(iters):
-        dist = xn - 2.0 * torch.bmm(x, cen.transpose(1, 2)) + (cen * cen).sum(-1)[:, None, :]
-        a = dist.argmin(-1)                                       # [G][ns]
-        flat = (ar * K + a).reshape(-1)
-        sums = torch.zeros((G * K, dim), device=x.device, dtype=torch.float64)
-        sums.index_add_(0, flat, x.reshape(-1, dim).double())
-        cnt = torch.bincount(flat, minlength=G * K).double()[:, None]
-        new = (sums / cnt.clamp(min=1.0)).float().reshape(G, K, dim)
-        cen = torch.where((cnt > 0).reshape(G, K, 1), new, cen)
-    return cen
-
-
-def _assign(x: torch.Tensor, cen: torch.Tensor, chunk: int = 1 << 16) -> torch.Tensor:
-    out = torch.empty((x.shape[0],), dtype=torch.int64, device=x.device)
-    cn = (cen * cen).sum(-1)[None, :]
-    for lo in range(0, x.shape[0], chunk):
-        xs = x[lo:lo + chunk]
-        dist = (xs * xs).sum(-1, keepdim=True) - 2.0 * (xs @ cen.T) + cn
-        out[lo:lo + chunk] = dist.argmin(-1)
-    return out
 
 
 class BuiltWorkload:
@@ -57,20 +27,19 @@ def build_workload(w: synth.Workload, device: str = "cuda:0", pq_train: int = 65
     queries = torch.from_numpy(synth.query_vectors(w)).to(device)
     base = torch.from_numpy(base_h).to(device)
     del base_h
-    dsub = w.d // w.M
     tr, init = synth.kmeans_draws(w, pq_train, 256, stream=0)
-    tr_t = torch.from_numpy(tr).to(device)
-    xs = base[tr_t].reshape(tr.shape[0], w.M, dsub).permute(1, 0, 2).contiguous()
-    init_t = torch.from_numpy(init).to(device)
-    codebooks = _lloyd(xs, xs[:, init_t, :].contiguous(), w.kmeans_iters).contiguous()
+    train = base[torch.from_numpy(tr).to(device)].contiguous()
+    codebooks = trim.trim_train_pq(train, w.M, w.kmeans_iters,
+                                   torch.from_numpy(init.astype(np.int32)).to(device))
+    del train
     ids = list_offsets = centroids = None
     max_len = 0
     if w.nlist:
         tr, init = synth.kmeans_draws(w, ivf_train_per_list * w.nlist, w.nlist, stream=1)
-        xt = base[torch.from_numpy(tr).to(device)]
-        centroids = _lloyd(xt[None], xt[torch.from_numpy(init).to(device)][None],
-                           w.kmeans_iters)[0].contiguous()
-        a = _assign(base, centroids)
+        xt = base[torch.from_numpy(tr).to(device)].contiguous()
+        centroids = trim.trim_train_ivf(xt, w.nlist, w.kmeans_iters,
+                                        torch.from_numpy(init.astype(np.int32)).to(device))
+        a = trim.trim_ivf_probe(base, centroids, 1)[:, 0].long()
         order = torch.argsort(a, stable=True)
         counts = torch.bincount(a, minlength=w.nlist)
         list_offsets = torch.zeros((w.nlist + 1,), dtype=torch.int64, device=device)

@@ -20,7 +20,7 @@ TRIM_MAX_K = 1024
 TRIM_MAX_BATCH = 4096
 TRIM_MAX_NPROBE = 4096
 
-EXPORTS = ("trim_shape_supported", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
+EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_strerror", "trim_last_hip_error", "trim_version")
@@ -77,6 +77,10 @@ def lib() -> C.CDLL:
                                   C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_pack_scan_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
                                           C.c_void_p]
+        L.trim_train_pq.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.trim_train_ivf.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_codes_tiled_bytes.restype = C.c_size_t
         L.trim_codes_tiled_bytes.argtypes = [C.c_int64, C.c_int32]
         L.trim_pack_codes_tiled.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
@@ -163,6 +167,34 @@ class Index:
 
 def trim_shape_supported(d: int, M: int) -> bool:
     return bool(lib().trim_shape_supported(d, M))
+
+
+def trim_train_pq(train: torch.Tensor, M: int, iters: int, init_rows: torch.Tensor) -> torch.Tensor:
+    ns, d = train.shape
+    if d % M or init_rows.numel() != 256:
+        raise TypeError(f"trim_train_pq: need d % M == 0 and 256 initial rows, got d={d}, M={M}, "
+                        f"{init_rows.numel()} rows")
+    codebooks = torch.empty((M, 256, d // M), dtype=torch.float32, device=train.device)
+    codes = torch.empty((ns, M), dtype=torch.uint8, device=train.device)
+    dlx = torch.empty((ns,), dtype=torch.float32, device=train.device)
+    _check(lib().trim_train_pq(_ptr(train, torch.float32, "train"), ns, d, M, iters,
+                               _ptr(init_rows, torch.int32, "init_rows"),
+                               _ptr(codebooks, torch.float32, "codebooks"), _ptr(codes, torch.uint8, "codes_ws"),
+                               _ptr(dlx, torch.float32, "dlx_ws"), _stream()), "trim_train_pq")
+    return codebooks
+
+
+def trim_train_ivf(train: torch.Tensor, nlist: int, iters: int, init_rows: torch.Tensor) -> torch.Tensor:
+    ns, d = train.shape
+    if init_rows.numel() != nlist:
+        raise TypeError(f"trim_train_ivf: need {nlist} initial rows, got {init_rows.numel()}")
+    centroids = torch.empty((nlist, d), dtype=torch.float32, device=train.device)
+    assign = torch.empty((ns,), dtype=torch.int32, device=train.device)
+    _check(lib().trim_train_ivf(_ptr(train, torch.float32, "train"), ns, d, nlist, iters,
+                                _ptr(init_rows, torch.int32, "init_rows"),
+                                _ptr(centroids, torch.float32, "centroids"),
+                                _ptr(assign, torch.int32, "assign_ws"), _stream()), "trim_train_ivf")
+    return centroids
 
 
 def trim_encode(base: torch.Tensor, codebooks: torch.Tensor):

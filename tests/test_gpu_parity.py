@@ -111,6 +111,31 @@ def test_build_lut_matrix_cores(T, oracle, name):
     assert (got["ids"].cpu().numpy() == bi).mean() > 0.999
 
 
+# ---- trim_train_pq / trim_train_ivf ------------------------------------------------------------
+
+@pytest.mark.parametrize("wname,ns,M,nlist", [("C2", 5000, 32, 48), ("C1", 3000, 16, 20), ("C3", 1500, 120, 12)])
+def test_centroid_training_is_bit_equal_to_the_oracle(T, oracle, wname, ns, M, nlist):
+    """Lloyd iterations with fixed roundings: initial rows given, binary32 assignment, float64
+    means in row order.  Codebooks and coarse centroids must equal the oracle's bit for bit
+    (ragged row count, clusters that run empty, 0 iterations = the initial rows)."""
+    import torch
+    from oracle import index_build
+    w = synth.scaled(synth.WORKLOADS[wname], ns, 4)
+    train = synth.base_vectors(w)
+    g = torch.from_numpy(train).cuda()
+    init = synth.sample_indices(900, 0, ns, 256).astype(np.int32)
+    init[5] = init[4]                                   # a duplicate start: one cluster runs empty
+    for iters in (0, 3):
+        want = index_build.train_pq_fixed(train, M, iters, init)
+        got = T.trim_train_pq(g, M, iters, torch.from_numpy(init).cuda()).cpu().numpy()
+        np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+    init_l = synth.sample_indices(901, 0, ns, nlist).astype(np.int32)
+    for iters in (0, 4):
+        want = index_build.train_ivf_fixed(train, nlist, iters, init_l)
+        got = T.trim_train_ivf(g, nlist, iters, torch.from_numpy(init_l).cuda()).cpu().numpy()
+        np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
 # ---- trim_ivf_probe ----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("name", ["c2s", "c4s", "c5s"])
