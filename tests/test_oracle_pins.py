@@ -446,6 +446,83 @@ def test_fixed_rounding_kmeans(oracle):
     np.testing.assert_array_equal(cen[2], index_build.train_ivf_fixed(base, 32, 3, np.arange(32) * 11))
 
 
+def test_gamma_estimator_ties_confidence_to_equation_3(oracle, tiny):
+    """Section 3.2's lemma: with gamma = gamma_x(p) from the sample, the relaxed bound of
+    Equation 3 stays below the true squared distance for exactly m = ceil(p Q) of the Q sampled
+    queries (cosine theorem: g <= d^2  <=>  gamma <= 1 - cos(theta)); the global value is the
+    smallest gamma_x; p = 1 loses no query of the sample."""
+    from oracle import gamma_estimator as ge
+    b = tiny
+    ix = b.index
+    rng = np.random.default_rng(3)
+    rows = np.sort(rng.choice(ix.n, 12, replace=False))
+    queries = b.queries
+    Q = queries.shape[0]
+    lm = ge.landmarks(ix.codes[rows], ix.codebooks)
+    for p in (1.0, 0.9, 0.5):
+        gamma, gx = ge.estimate_gamma_empirical(ix.base, ix.codes, ix.codebooks, rows, queries, p)
+        assert gamma == gx.min()
+        m = min(Q, max(1, int(np.ceil(np.float32(p).astype(np.float64) * Q))))
+        for i, r in enumerate(rows):
+            x = ix.base[r].astype(np.float64)
+            a = np.sqrt(((queries.astype(np.float64) - lm[i]) ** 2).sum(1))     # Gamma(l, q)
+            bb = np.sqrt(((x - lm[i]) ** 2).sum())                              # Gamma(l, x)
+            d2 = ((queries.astype(np.float64) - x) ** 2).sum(1)
+            g = (a - bb) ** 2 + 2.0 * gx[i] * a * bb                            # Equation 3
+            valid = int((g <= d2 * (1 + 1e-12) + 1e-9).sum())
+            assert valid >= m
+            # a slightly larger gamma would already lose one more query
+            g2 = (a - bb) ** 2 + 2.0 * (gx[i] + 1e-7) * a * bb
+            assert int((g2 <= d2 * (1 - 1e-12) - 1e-9).sum()) < m or m == Q and valid == Q
+    # closed cases: orthogonal and opposite directions
+    l = np.zeros(4); x = np.array([1.0, 0, 0, 0])
+    qs = np.array([[0, 2.0, 0, 0], [-3.0, 0, 0, 0], [5.0, 0, 0, 0], [0, 0, 0, 0]])
+    np.testing.assert_allclose(ge.one_minus_cos(x, l, qs), [1.0, 2.0, 0.0, 1.0], atol=1e-15)
+    assert ge.rank_for_p(1.0, 10) == 0 and ge.rank_for_p(0.9, 1000) == 100 and ge.rank_for_p(0.0, 7) == 6
+
+
+def test_gamma_for_normal_queries_matches_direct_sampling(oracle):
+    """The Z^2 = A/(A+B+C) route with the transform theorem against 1 - Z computed directly
+    from d-dimensional standard-normal queries: same distribution (theorems of Section 3.2),
+    hence nearly the same gamma_x(p); also pins h1, h2 and the d - 2 terms of C."""
+    from oracle import gamma_estimator as ge
+    rng = np.random.default_rng(11)
+    d = 24
+    x = rng.normal(size=d) * 0.7 + 0.3
+    l = x + rng.normal(size=d) * 0.25
+    qn = rng.normal(size=(60000, d))
+    direct = np.sort(ge.one_minus_cos(x, l, qn))
+    normals = rng.normal(size=(60000, d))
+    h1, h2 = ge.h1_h2(x, l)
+    u = x - l
+    assert abs(h1 - (u @ l) / np.linalg.norm(u)) < 1e-12 and abs(h1 * h1 + h2 * h2 - l @ l) < 1e-9
+    z2 = np.sort(ge.z2_samples(h1, h2, normals))
+    y = np.linspace(0.0, 2.0, 401)
+    f_route = ge.cdf_one_minus_z_from_z2(z2, y)
+    f_direct = np.searchsorted(direct, y, side="right") / direct.shape[0]
+    # |Z| has the same law on both sides; the transform theorem itself treats Z as symmetric
+    # (its proof halves P(Z^2 >= .)), so the comparison is made on Z^2, and on 1 - Z where that
+    # symmetry holds: a landmark at the origin
+    z2_direct = np.sort((1.0 - direct) ** 2)
+    grid = np.linspace(0, 1, 201)
+    ks = np.abs(np.searchsorted(z2, grid) / z2.shape[0] - np.searchsorted(z2_direct, grid) / z2_direct.shape[0]).max()
+    assert ks < 0.012
+    # one term fewer in C (the text's chi_{d-3}) is visibly different at this sample size
+    z2_wrong = np.sort(ge.z2_samples(h1, h2, normals[:, :d - 1]))
+    ks_wrong = np.abs(np.searchsorted(z2_wrong, grid) / z2.shape[0] - np.searchsorted(z2_direct, grid) / z2_direct.shape[0]).max()
+    assert ks_wrong > 2 * ks
+    l0 = np.zeros(d)
+    direct0 = np.sort(ge.one_minus_cos(x, l0, qn))
+    z20 = np.sort(ge.z2_samples(*ge.h1_h2(x, l0), normals))
+    f0 = ge.cdf_one_minus_z_from_z2(z20, y)
+    assert np.abs(f0 - np.searchsorted(direct0, y, side="right") / direct0.shape[0]).max() < 0.012
+    for p in (0.99, 0.9, 0.6):
+        g_route = ge.gamma_normal_queries(x, l0, normals, p)
+        g_direct = ge.gamma_from_sample(direct0, p)
+        assert abs(g_route - g_direct) < 0.02
+    assert f_route[0] <= 0.5 and abs(f_route[-1] - 1.0) < 1e-12
+
+
 def test_ivf_lists_and_probes(oracle, tiny_ivf):
     b = tiny_ivf
     ix = b.index
