@@ -124,6 +124,24 @@ int trim_train_ivf(const float *train, int64_t ns, int32_t d, int32_t nlist, int
                    const int32_t *init_rows, float *centroids_out, int32_t *assign_ws, void *stream);
 
 /*
+ * Relaxation parameter from a confidence level (Section 3.2, the sampling route for queries
+ * without a known distribution): by the section's lemma, p = P(gamma <= 1 - cos(theta)) with
+ * theta the angle at x's landmark between x and the query.  For each sampled data vector
+ * (position sample_rows[s] of the index) the value 1 - cos(theta) is computed against the Q
+ * sampled queries; gamma_x = its m-th largest value, m = min(Q, max(1, ceil(p * Q))), so that
+ * m of the Q sampled queries keep Equation 3 below the true squared distance; the global
+ * gamma is the smallest gamma_x (end of Section 3.2).  A vector equal to its landmark, or a
+ * query equal to the landmark, counts as cos = 0.
+ * index needs base, codes, codebooks.  sample_rows [S] device (clamped to [0, n)),
+ * sample_queries [Q][d] device, 1 <= Q <= 16384, 0 <= p <= 1; gamma_x_out [S] device or NULL;
+ * gamma_out device, one float.  Arithmetic is binary32 (values agree with a float64
+ * evaluation to about 1e-6).
+ */
+int trim_estimate_gamma(const trim_index_view *index, const int32_t *sample_rows, int32_t S,
+                        const float *sample_queries, int32_t Q, float p, float *gamma_x_out,
+                        float *gamma_out, void *stream);
+
+/*
  * Storage layout for the scan (the stored landmark codes and distances of Section 3.3,
  * preprocessing): head_out[x] = the 12 bytes {codes[x][0..7], dlx[x]}.  The kNN scan bounds
  * every candidate over its first 8 subspaces before it looks at the rest of the code, and

@@ -352,6 +352,39 @@ int trim_train_ivf(const float *train, int64_t ns, int32_t d, int32_t nlist, int
     return TRIM_OK;
 }
 
+int trim_estimate_gamma(const trim_index_view *index, const int32_t *sample_rows, int32_t S,
+                        const float *sample_queries, int32_t Q, float p, float *gamma_x_out,
+                        float *gamma_out, void *stream) {
+    if (!index || index->n <= 0 || index->d <= 0 || index->M <= 0) return TRIM_INVALID_ARG;
+    if (index->d % 4 || index->d % index->M) return TRIM_UNSUPPORTED_SHAPE;
+    if (S <= 0 || Q <= 0 || !(p >= 0.0f && p <= 1.0f)) return TRIM_INVALID_ARG;
+    if (Q > 16384) return TRIM_UNSUPPORTED_SHAPE;
+    if (!index->base || !index->codes || !index->codebooks || !sample_rows || !sample_queries || !gamma_out)
+        return TRIM_INVALID_ARG;
+    if (!aligned16(sample_queries)) return TRIM_INVALID_ARG;
+    int npow2 = 1;
+    while (npow2 < Q) npow2 <<= 1;
+    const size_t lds = ((size_t)2 * index->d + npow2) * 4;
+    if (lds + 1024 > kLdsBytes) return TRIM_UNSUPPORTED_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = fill_u32(reinterpret_cast<uint32_t *>(gamma_out), 1, 0x7f800000u, st);  // +inf
+    if (rc) return rc;
+    GammaArgs a{};
+    a.base = index->base; a.codes = index->codes; a.codebooks = index->codebooks;
+    a.rows = sample_rows; a.queries = sample_queries; a.n = index->n; a.d = index->d; a.M = index->M;
+    a.Q = Q; a.npow2 = npow2;
+    long m = (long)std::ceil((double)p * (double)Q);
+    if (m < 1) m = 1;
+    if (m > Q) m = Q;
+    a.rank = (int32_t)(Q - m);
+    a.gamma_x = gamma_x_out; a.gamma_bits = reinterpret_cast<uint32_t *>(gamma_out);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gamma_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(gamma_kernel, dim3((unsigned)S), dim3(256), lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
 size_t trim_codes_tiled_bytes(int64_t n, int32_t M) {
     if (n <= 0 || M <= 0) return 0;
     return (size_t)((n + 63) / 64) * 64 * (size_t)M;

@@ -99,6 +99,94 @@ __global__ __launch_bounds__(256) void kmeans_update_kernel(const float *__restr
     if (live && count > 0) cent[e] = (float)(sum / (double)count);
 }
 
+// ---- gamma from a confidence level p (Section 3.2), empirical route ----
+// One workgroup per sampled data vector x: landmark l = PQ reconstruction of x; for every
+// sampled query the value 1 - cos(x - l, q - l) (half waves, 16 bytes per lane and step);
+// the values are sorted in LDS (bitonic) and the one of the given rank is gamma_x; the
+// global gamma is the minimum over x (values are >= 0, so their bit patterns order like
+// the numbers and a 32-bit atomic minimum does it).
+struct GammaArgs {
+    const float *base;
+    const uint8_t *codes;
+    const float *codebooks;
+    const int32_t *rows;
+    const float *queries;
+    int64_t n;
+    int32_t d, M, Q, npow2, rank;
+    float *gamma_x;
+    uint32_t *gamma_bits;
+};
+
+__global__ __launch_bounds__(256) void gamma_kernel(const GammaArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *l = reinterpret_cast<float *>(smem);   // [d]
+    float *u = l + a.d;                           // [d]
+    float *vals = u + a.d;                        // [npow2]
+    __shared__ float red[256];
+    const int tid = threadIdx.x;
+    int64_t r = a.rows[blockIdx.x];
+    r = r < 0 ? 0 : (r >= a.n ? a.n - 1 : r);
+    const int dsub = a.d / a.M;
+    float part = 0.0f;
+    for (int t = tid; t < a.d; t += blockDim.x) {
+        const int j = t / dsub;
+        const float lt = a.codebooks[((size_t)j * kC + a.codes[(size_t)r * a.M + j]) * dsub + t % dsub];
+        const float ut = a.base[(size_t)r * a.d + t] - lt;
+        l[t] = lt;
+        u[t] = ut;
+        part = __builtin_fmaf(ut, ut, part);
+    }
+    red[tid] = part;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+        if (tid < h) red[tid] += red[tid + h];
+        __syncthreads();
+    }
+    const float nu = trim::sqrt_rn(red[0]);
+    const int half = tid >> 5, lane32 = tid & 31, nhalf = blockDim.x >> 5;
+    const float4 *l4 = reinterpret_cast<const float4 *>(l);
+    const float4 *u4 = reinterpret_cast<const float4 *>(u);
+    const int ng = a.d >> 2;
+    for (int qi = half; qi < a.Q; qi += nhalf) {
+        const float4 *q4 = reinterpret_cast<const float4 *>(a.queries + (size_t)qi * a.d);
+        float dot = 0.0f, nn = 0.0f;
+        for (int g = lane32; g < ng; g += 32) {
+            const float4 qv = q4[g], lv = l4[g], uv = u4[g];
+            float w;
+            w = qv.x - lv.x; dot = __builtin_fmaf(w, uv.x, dot); nn = __builtin_fmaf(w, w, nn);
+            w = qv.y - lv.y; dot = __builtin_fmaf(w, uv.y, dot); nn = __builtin_fmaf(w, w, nn);
+            w = qv.z - lv.z; dot = __builtin_fmaf(w, uv.z, dot); nn = __builtin_fmaf(w, w, nn);
+            w = qv.w - lv.w; dot = __builtin_fmaf(w, uv.w, dot); nn = __builtin_fmaf(w, w, nn);
+        }
+        dot = half_reduce(dot);
+        nn = half_reduce(nn);
+        if (lane32 == 0) {
+            const float den = trim::sqrt_rn(nn) * nu;
+            vals[qi] = 1.0f - (den > 0.0f ? dot / den : 0.0f);
+        }
+    }
+    for (int i = a.Q + tid; i < a.npow2; i += blockDim.x) vals[i] = __builtin_inff();
+    __syncthreads();
+    for (int k = 2; k <= a.npow2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < a.npow2; i += blockDim.x) {
+                const int p = i ^ j;
+                if (p > i) {
+                    const float x = vals[i], y = vals[p];
+                    const bool up = (i & k) == 0;
+                    if ((x > y) == up) { vals[i] = y; vals[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        const float g = vals[a.rank];
+        if (a.gamma_x) a.gamma_x[blockIdx.x] = g;
+        atomicMin(a.gamma_bits, __float_as_uint(g < 0.0f ? 0.0f : g));
+    }
+}
+
 // ---- PQ encode (Section 3.3, preprocessing step 1) ----
 // One thread per vector; the block stages one subspace's 256 centroids in LDS at a time.
 // DSUB > 0: sub-vector length known at compile time (kept in registers); DSUB == 0: generic.

@@ -20,7 +20,7 @@ TRIM_MAX_K = 1024
 TRIM_MAX_BATCH = 4096
 TRIM_MAX_NPROBE = 4096
 
-EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
+EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_strerror", "trim_last_hip_error", "trim_version")
@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_train_ivf.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.trim_estimate_gamma.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float,
+                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_codes_tiled_bytes.restype = C.c_size_t
         L.trim_codes_tiled_bytes.argtypes = [C.c_int64, C.c_int32]
         L.trim_pack_codes_tiled.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
@@ -195,6 +197,19 @@ def trim_train_ivf(train: torch.Tensor, nlist: int, iters: int, init_rows: torch
                                 _ptr(centroids, torch.float32, "centroids"),
                                 _ptr(assign, torch.int32, "assign_ws"), _stream()), "trim_train_ivf")
     return centroids
+
+
+def trim_estimate_gamma(index: "Index", sample_rows: torch.Tensor, sample_queries: torch.Tensor, p: float):
+    """Returns (gamma [1] float32 on the device, gamma_x [S] float32)."""
+    S, Q = sample_rows.numel(), sample_queries.shape[0]
+    gx = torch.empty((S,), dtype=torch.float32, device=sample_queries.device)
+    g = torch.empty((1,), dtype=torch.float32, device=sample_queries.device)
+    view = index._view()
+    _check(lib().trim_estimate_gamma(C.byref(view), _ptr(sample_rows, torch.int32, "sample_rows"), S,
+                                     _ptr(sample_queries, torch.float32, "sample_queries"), Q, p,
+                                     _ptr(gx, torch.float32, "gamma_x"), _ptr(g, torch.float32, "gamma"),
+                                     _stream()), "trim_estimate_gamma")
+    return g, gx
 
 
 def trim_encode(base: torch.Tensor, codebooks: torch.Tensor):

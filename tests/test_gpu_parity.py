@@ -136,6 +136,32 @@ def test_centroid_training_is_bit_equal_to_the_oracle(T, oracle, wname, ns, M, n
         np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
+# ---- trim_estimate_gamma -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["c2s", "c3s", "c1"])
+def test_gamma_from_confidence_level(T, oracle, name):
+    """gamma_x(p) is an order statistic of 1 - cos(theta) over the sampled queries, so an error of
+    eps in every value moves it by at most eps: binary32 on the GPU against float64 in the
+    oracle must agree to a few 1e-6 (asserted at 2e-5), for every sampled vector and for the
+    global minimum; Q is not a power of two and spans several sort tiles."""
+    import torch
+    from oracle import gamma_estimator as ge
+    b = case(name)
+    gi, q, _ = to_dev(T, b)
+    w = synth.scaled(b.w, b.index.n, 1500)
+    queries = synth.query_vectors(w)[:1337]
+    rows = np.sort(synth.sample_indices(77, 3, b.index.n, 40)).astype(np.int32)
+    gq = torch.from_numpy(queries).cuda()
+    for p in (1.0, 0.95, 0.5, 0.0):
+        want, want_x = ge.estimate_gamma_empirical(b.index.base, b.index.codes, b.index.codebooks,
+                                                   rows, queries, p)
+        g, gx = T.trim_estimate_gamma(gi, torch.from_numpy(rows).cuda(), gq, p)
+        np.testing.assert_allclose(gx.cpu().numpy(), want_x, atol=2e-5, rtol=0)
+        assert abs(float(g.item()) - want) <= 2e-5
+    with pytest.raises(T.TrimError):
+        T.trim_estimate_gamma(gi, torch.from_numpy(rows).cuda(), gq, 1.5)
+
+
 # ---- trim_ivf_probe ----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("name", ["c2s", "c4s", "c5s"])
