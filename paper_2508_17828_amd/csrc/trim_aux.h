@@ -462,8 +462,8 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
 // ---- coarse probe selection (Section 6.1: IVFPQ with C' lists, nprobe probed) ----
 // One workgroup handles QT queries: every centroid row is read once and measured against
 // all QT queries (exact distances by half waves, rounding order as in exact_d2_half), then
-// each query's (distance bits, list id) keys are sorted in LDS (bitonic) and the first
-// nprobe ids are written.
+// the nprobe smallest of each query's (distance bits, list id) keys are selected in LDS
+// (bitonic runs and pairwise merges) and their ids are written in ascending key order.
 template <int QT>
 __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict__ queries,
                                                         int64_t nq, int d,
@@ -523,11 +523,19 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         }
     }
     __syncthreads();
-    // bitonic sort of each query's keys; all sizes are powers of two, so the index arithmetic
-    // is shifts and masks (lg_* are base-2 logarithms)
+    // Selection of the nprobe smallest keys of each query with bitonic networks; all sizes are
+    // powers of two, so the index arithmetic is shifts and masks (lg_* are base-2 logarithms).
+    // (1) runs of R >= nprobe keys are sorted, ascending and descending in turn;
+    // (2) neighbouring runs are merged pairwise, keeping only the R smallest of the two: the
+    //     element-wise minimum of an ascending and a descending run holds them as a bitonic
+    //     sequence, which log2(R) exchange stages sort (again ascending / descending in turn);
+    //     the surviving run stays where the pair's first run was, so after round r the live
+    //     runs sit at multiples of R << r.  The last survivor, at 0, is ascending.
     const int lg_n = 31 - __builtin_clz(npow2);
     const int lg_half = lg_n - 1;
-    for (int lg_size = 1; lg_size <= lg_n; ++lg_size) {
+    int lg_r = 0;
+    while ((1 << lg_r) < nprobe) ++lg_r;
+    for (int lg_size = 1; lg_size <= lg_r; ++lg_size) {
         for (int lg_stride = lg_size - 1; lg_stride >= 0; --lg_stride) {
             const int stride = 1 << lg_stride;
             for (int w = tid; w < (QT << lg_half); w += T) {
@@ -538,6 +546,36 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
                 unsigned long long *kq = keys + ((size_t)qi << lg_n);
                 const unsigned long long x = kq[lo], y = kq[hi];
                 if ((x > y) == up) { kq[lo] = y; kq[hi] = x; }
+            }
+            __syncthreads();
+        }
+    }
+    const int R = 1 << lg_r;
+    for (int lg_gap = lg_r; lg_gap < lg_n; ++lg_gap) {   // partner run = first run + (1 << lg_gap)
+        const int lg_pairs = lg_n - lg_gap - 1;          // pairs per query in this round
+        // element-wise minimum into the first run of each pair
+        for (int w = tid; w < ((QT << lg_pairs) << lg_r); w += T) {
+            const int i = w & (R - 1);
+            const int pr = (w >> lg_r) & ((1 << lg_pairs) - 1);
+            const int qi = w >> (lg_r + lg_pairs);
+            unsigned long long *kq = keys + ((size_t)qi << lg_n) + ((size_t)pr << (lg_gap + 1));
+            const unsigned long long x = kq[i], y = kq[(1 << lg_gap) + i];
+            if (y < x) kq[i] = y;
+        }
+        __syncthreads();
+        // sort the bitonic survivors: ascending for even pairs, descending for odd ones
+        for (int lg_stride = lg_r - 1; lg_stride >= 0; --lg_stride) {
+            const int stride = 1 << lg_stride;
+            const int lg_ce = lg_r - 1;                  // exchanges per run and stage = R / 2
+            for (int w = tid; w < ((QT << lg_pairs) << lg_ce); w += T) {
+                const int i = w & ((1 << lg_ce) - 1);
+                const int pr = (w >> lg_ce) & ((1 << lg_pairs) - 1);
+                const int qi = w >> (lg_ce + lg_pairs);
+                const int lo = ((i >> lg_stride) << (lg_stride + 1)) | (i & (stride - 1));
+                const bool up = (pr & 1) == 0;
+                unsigned long long *kq = keys + ((size_t)qi << lg_n) + ((size_t)pr << (lg_gap + 1));
+                const unsigned long long x = kq[lo], y = kq[lo + stride];
+                if ((x > y) == up) { kq[lo] = y; kq[lo + stride] = x; }
             }
             __syncthreads();
         }
