@@ -52,6 +52,7 @@ typedef enum trim_status {
 #define TRIM_MAX_K 1024       /* kNN result size */
 #define TRIM_MAX_BATCH 4096   /* kNN batch size */
 #define TRIM_MAX_NPROBE 4096  /* probed lists per query */
+#define TRIM_MAX_QUERIES 4194296 /* queries per search call (a launch holds < 2^32 threads) */
 
 /* The stored index of Section 3.3 (preprocessing): raw vectors, their landmark codes and
  * landmark distances, and the PQ centroids.  All arrays device, read-only. */
@@ -197,7 +198,8 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
  * long first batch would spend.
  *
  * queries [nq][d] device.  lut: device [nq][M][256] or NULL (tables are then built inside
- * the kernel from index->codebooks).  cand: host struct or NULL.  1 <= k <= TRIM_MAX_K,
+ * the kernel from index->codebooks).  cand: host struct or NULL.  nq <= TRIM_MAX_QUERIES,
+ * 1 <= k <= TRIM_MAX_K,
  * 1 <= batch <= TRIM_MAX_BATCH, 0 <= first_batch <= batch, gamma >= 0.
  * query_order: device [nq] or NULL; a permutation of 0..nq-1 giving the order in which
  * queries are handed to the GPU (see trim_query_order).  It changes scheduling only: every

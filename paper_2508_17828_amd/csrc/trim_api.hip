@@ -445,7 +445,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     int rc = check_index(index);
     if (rc) return rc;
     if ((rc = check_cand(cand))) return rc;
-    if (nq < 0 || nq > 0x7fffffff - 8 || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
+    if (nq < 0 || nq > TRIM_MAX_QUERIES || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
         return TRIM_INVALID_ARG;
     if (first_batch < 0 || first_batch > batch) return TRIM_INVALID_ARG;
     if (!(gamma >= 0.0f) || std::isinf(gamma)) return TRIM_INVALID_ARG;
@@ -468,6 +468,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     a.chunk = 0; a.nsplit = 1;
     a.nq = nq; a.order = query_order;
     const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
+    if (slots * pl.threads >= (int64_t(1) << 32)) return TRIM_INVALID_ARG;  // threads per launch
     if ((rc = launch_search<kKnn>(a, pl, dim3((unsigned)slots, 1), st))) return rc;
     return TRIM_OK;
 }
@@ -485,7 +486,7 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
     int rc = check_index(index);
     if (rc) return rc;
     if ((rc = check_cand(cand))) return rc;
-    if (nq < 0 || nq > 0x7fffffff - 8 || capacity < 0) return TRIM_INVALID_ARG;
+    if (nq < 0 || nq > TRIM_MAX_QUERIES || capacity < 0) return TRIM_INVALID_ARG;
     if (!(gamma >= 0.0f) || std::isinf(gamma) || !(radius >= 0.0f)) return TRIM_INVALID_ARG;
     if (!out_offsets) return TRIM_INVALID_ARG;
     if (capacity > 0 && (!out_ids || !out_d2)) return TRIM_INVALID_ARG;
@@ -542,6 +543,7 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
 
     a.nq = nq;
     const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
+    if (slots * pl.threads >= (int64_t(1) << 32)) return TRIM_INVALID_ARG;  // threads per launch
     if ((rc = launch_search<kRange>(a, pl, dim3((unsigned)slots, (unsigned)L.nsplit), st))) return rc;
     hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(1024), 0, st, counts, nq, L.nsplit, cbase,
                        out_offsets, required);
@@ -577,9 +579,15 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
         qt == 4 ? ivf_probe_kernel<4> : qt == 2 ? ivf_probe_kernel<2> : ivf_probe_kernel<1>;
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(fn, dim3((unsigned)((nq + qt - 1) / qt)), dim3(512), lds, st, queries, nq, d,
-                       centroids, nlist, npow2, nprobe, probes_out);
-    HIP_TRY(hipGetLastError());
+    // a launch holds fewer than 2^32 threads: walk the queries in slabs
+    const int64_t slab = (int64_t)qt * (1 << 22);
+    for (int64_t q0 = 0; q0 < nq; q0 += slab) {
+        const int64_t cnt = nq - q0 < slab ? nq - q0 : slab;
+        hipLaunchKernelGGL(fn, dim3((unsigned)((cnt + qt - 1) / qt)), dim3(512), lds, st,
+                           queries + (size_t)q0 * d, cnt, d, centroids, nlist, npow2, nprobe,
+                           probes_out + (size_t)q0 * nprobe);
+        HIP_TRY(hipGetLastError());
+    }
     return TRIM_OK;
 }
 
