@@ -403,10 +403,10 @@ void search_kernel(const SearchArgs a) {
     }
 
     TRIM_TICK(1);
-    // ---- main loop over super-chunks of `span` candidates (a whole number of batches) ----
-    // Stage A bounds every candidate of the super-chunk with no barrier in between and
+    // ---- main loop over spans of candidates (a whole number of batches each) ----
+    // Stage A bounds every candidate of the span with no barrier in between and
     // keeps the bounds in LDS; it counts, per batch, the candidates that pass the
-    // threshold in force at the start of the super-chunk.  Thresholds only fall, so that
+    // threshold in force at the start of the span.  Thresholds only fall, so that
     // set contains every later survivor, and batches whose count is zero are skipped
     // outright.  Stage B walks the remaining batches in order with the up-to-date
     // threshold, which reproduces the batch-by-batch rule exactly.
