@@ -426,7 +426,7 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int cl = base + u * kWave + lane;
-            bq[u] = 0.0f;
+            bq[u] = __builtin_nanf("");  // out of range: never passes a threshold test
             sg[u] = 0;
 #pragma unroll
             for (int v = 0; v < H0 / 4; ++v) w[u][v] = 0;
@@ -610,8 +610,10 @@ void search_kernel(const SearchArgs a) {
                         const float sum = sums[u];
                         const int cl = cb + u * kWave + lane;
                         const float thr = abandon_threshold(bq[u], sqrt_tau0);
-                        const bool alive = full ? !(sum > thr) : (cl < S && !(sum > thr));
-                        const unsigned long long m = __ballot(alive);
+                        // lanes beyond the stretch carry a NaN landmark distance (issue_loads):
+                        // their threshold is NaN and the comparison is false
+                        const bool alive = sum <= thr;
+                        const unsigned long long m = __builtin_amdgcn_ballot_w64(alive);
                         if (alive) {
                             const uint32_t at = __builtin_amdgcn_mbcnt_hi(
                                 (uint32_t)(m >> 32),
