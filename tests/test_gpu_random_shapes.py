@@ -1,0 +1,89 @@
+"""GPU parity on seeded random configurations: dimensions, subspace counts, result sizes,
+batch schedules, candidate structures and relaxation drawn at random (within the library's
+limits), each checked bit for bit against the oracle for kNN and for range search.  The
+fixed cases elsewhere aim at known corners; these walk the plan space (table phases, block
+sizes, residency tiers, code-load widths, growing batches, tiled codes, scan head)."""
+import numpy as np
+import pytest
+
+from paper_2508_17828_amd import synth
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+LAWS = {"clip255": "C2", "aniso01": "C3", "unit": "C4"}
+
+
+def draw(seed):
+    r = np.random.default_rng([2024, seed])
+    M = int(r.choice([4, 8, 12, 16, 24, 32, 48, 64, 96, 120, 160, 192]))
+    dsub = int(r.choice([4, 8] if M > 64 else [4, 8, 16]))
+    law = str(r.choice(list(LAWS)))
+    n = int(r.integers(700, 9000))
+    nq = int(r.integers(3, 20))
+    use_ivf = bool(r.integers(0, 2))
+    nlist = int(r.integers(4, 40)) if use_ivf else 0
+    nprobe = int(r.integers(1, nlist + 1)) if use_ivf else 0
+    k = int(r.choice([1, 3, 10, 64, 65, 100, 200, 300]))
+    batch = int(r.choice([1, 7, 64, 100, 256, 1000, 1024, 2048, 4096]))
+    first = int(r.choice([0, 0, 1, 5, 64, batch])) if batch > 1 else 0
+    first = min(first, batch)
+    gamma = float(r.choice([0.0, 0.3, 0.6, 0.9]))
+    base = synth.WORKLOADS[LAWS[law]]
+    w = synth.scaled(base, n, nq, d=M * dsub, M=M, nlist=nlist, nprobe=nprobe, k=k,
+                     ncomp=int(r.integers(4, 40)), seed=1000 + seed, kmeans_iters=3)
+    return w, k, batch, first, gamma
+
+
+def draw_long(seed):
+    """Long candidate lists: several barrier-free stretches per query, ring queues, possibles
+    lists that overflow at loose thresholds."""
+    r = np.random.default_rng([2025, seed])
+    M = int(r.choice([16, 32, 64]))
+    dsub = int(r.choice([4, 8]))
+    n = int(r.integers(90_000, 260_000))
+    k = int(r.choice([10, 64, 100]))
+    batch = int(r.choice([128, 256, 1024, 2048]))
+    first = int(r.choice([0, 32, batch]))
+    gamma = float(r.choice([0.0, 0.4, 0.8]))
+    law = str(r.choice(["clip255", "aniso01"]))
+    w = synth.scaled(synth.WORKLOADS[LAWS[law]], n, 3, d=M * dsub, M=M, nlist=0, nprobe=0, k=k,
+                     ncomp=int(r.integers(8, 60)), seed=3000 + seed, kmeans_iters=2)
+    return w, k, batch, first, gamma
+
+
+@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(6)])
+def test_random_configuration(oracle, seed):
+    import torch
+    from paper_2508_17828_amd import trim as T
+    T.lib()
+    w, k, batch, first, gamma = draw(seed) if seed < 1000 else draw_long(seed - 1000)
+    b = helpers.build(w, pq_train_max=4096, ivf_train_per_list=32)
+    ix = b.index
+    t = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    gi = T.Index(t(ix.base), t(ix.codes), t(ix.dlx), t(ix.codebooks), ids=t(ix.ids),
+                 list_offsets=t(ix.list_offsets),
+                 max_list_len=int(np.diff(ix.list_offsets).max()) if ix.list_offsets is not None else 0)
+    if w.M % 8 == 0:
+        gi.scan_head = T.trim_pack_scan_head(gi.codes, gi.dlx)
+    if w.M % 16 == 0 and seed % 2 == 0:
+        gi.codes_tiled = T.trim_pack_codes_tiled(gi.codes)
+    q, probes = t(b.queries), t(b.probes)
+    what = f"seed {seed}: n={w.n} d={w.d} M={w.M} k={k} batch={batch} first={first} gamma={gamma} " \
+           f"nlist={w.nlist} nprobe={w.nprobe} law={w.law}"
+    print(what, flush=True)
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True, first_batch=first)
+    ref = oracle.search_knn(ix, b.queries, k, gamma, batch, b.probes, want_mask=True,
+                            first_batch=first or None)
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(got["mask"].cpu().numpy().view(np.uint32)[:, :mw], ref["mask"], err_msg=what)
+    np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"], err_msg=what)
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"], err_msg=what)
+    np.testing.assert_array_equal(got["d2"].cpu().numpy().view(np.uint32), ref["d2"].view(np.uint32), err_msg=what)
+    radius = helpers.radius_at_percentile(b, 3.0, min(8, w.nq), 500)
+    gr = T.trim_search_range(gi, q, radius, gamma, probes=probes, want_mask=True)
+    rr = oracle.search_range(ix, b.queries, radius, gamma, b.probes, want_mask=True)
+    np.testing.assert_array_equal(gr["offsets"].cpu().numpy(), rr["offsets"], err_msg=what)
+    np.testing.assert_array_equal(gr["ids"].cpu().numpy(), rr["ids"], err_msg=what)
+    np.testing.assert_array_equal(gr["d2"].cpu().numpy().view(np.uint32), rr["d2"].view(np.uint32), err_msg=what)
+    np.testing.assert_array_equal(gr["mask"].cpu().numpy().view(np.uint32)[:, :mw], rr["mask"], err_msg=what)
