@@ -173,12 +173,33 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
         t_id = __builtin_amdgcn_readlane(vi, kl);
     };
     load_kth();
+    // A long list (the first batch after the seed) is pre-filtered: lane l takes the minimum of
+    // entries l, l+64, ...; the k-th smallest of these 64 minima (distinct entries) is an upper
+    // bound on the k-th distance after the merge, so entries above it never enter R and skip
+    // the one-at-a-time insertion below.  (One entry per lane: result sets up to 64.)
+    float cut = __builtin_inff();
+    if constexpr (E == 1) {
+        if (ns > 2 * kWave) {
+            float cmin = __builtin_inff();
+            for (int i = lane; i < ns; i += kWave) cmin = __builtin_fminf(cmin, sd2[i]);
+#pragma unroll
+            for (int size = 2; size <= kWave; size <<= 1) {
+#pragma unroll
+                for (int j = size >> 1; j > 0; j >>= 1) {   // bitonic network across the lanes
+                    const float other = __shfl_xor(cmin, j);
+                    const bool keep_min = ((lane & j) == 0) == ((lane & size) == 0);
+                    cmin = keep_min ? __builtin_fminf(cmin, other) : __builtin_fmaxf(cmin, other);
+                }
+            }
+            cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cmin), k - 1));
+        }
+    }
     for (int i0 = 0; i0 < ns; i0 += kWave) {
         const int i = i0 + lane;
         bool pending = i < ns;
         float d2 = 0.0f;
         int32_t id = 0;
-        if (pending) { d2 = sd2[i]; id = sid[i]; }
+        if (pending) { d2 = sd2[i]; id = sid[i]; pending = d2 <= cut; }
         for (;;) {
             const unsigned long long m = __ballot(pending && hit_less(d2, id, t_d2, t_id));
             if (m == 0) break;
