@@ -38,7 +38,7 @@ struct Plan {
     size_t lds;
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
-    int span, wqcap, cruise, poss_cap;
+    int span, wqcap, cruise, poss_cap, scap;
 };
 
 // Decide table phases, block size and LDS layout for a search launch.
@@ -86,48 +86,53 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
             const int nwaves = tier.threads / 64;
             // a wave's share of a span is rounded up to 64; two queue arrays of 16-bit entries
             const int wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
-            size_t wq_bytes = (size_t)2 * nwaves * wqcap * 2;
-            if (can_cruise && wq_bytes < (size_t)nwaves * kRing * 4) wq_bytes = (size_t)nwaves * kRing * 4;
-            // the exact distances of a batch's survivors reuse the queue area: queues are
-            // only live while bounds are computed, distances only afterwards
-            if (wq_bytes < (size_t)cap * 4) wq_bytes = (size_t)cap * 4;
-            wq_bytes = up16(wq_bytes);
+            size_t wq_min = (size_t)2 * nwaves * wqcap * 2;
+            if (can_cruise && wq_min < (size_t)nwaves * kRing * 4) wq_min = (size_t)nwaves * kRing * 4;
             const size_t rest = tab + up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) +
-                                up16((size_t)nsegs * 4) + up16((size_t)cap * 4) * (range ? 2 : 1) +
+                                up16((size_t)nsegs * 4) + (range ? up16((size_t)cap * 4) : 0) +
                                 up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
-                                up16((size_t)ncnt * 4) + wq_bytes;
-            // bounds of a span; in cruise mode the same area holds the possibles list
-            size_t plb = up16((size_t)span * 4);
-            if (can_cruise && plb < (size_t)kPossMin * 8) plb = (size_t)kPossMin * 8;
-            if (rest + plb > tier.lds) continue;
-            if (can_cruise) {
-                size_t room = (tier.lds - rest) / 16 * 16;
-                if (room > (size_t)kPossMax * 8) room = (size_t)kPossMax * 8;
-                if (room > plb) plb = room;
+                                up16((size_t)ncnt * 4);
+            // The possibles list of a cruise stretch takes what is left, largest first.  Its
+            // capacity p also sizes the arrays of the stretch's replay: spos[] holds p entries,
+            // and the queue area holds p exact distances and p bounds (queues are only live
+            // while bounds are computed, distances and bounds only afterwards).
+            static const int kPossTry[] = {kPossMax, 1536, 1024, 768, kPossMin, 0};
+            for (int p : kPossTry) {
+                if (p > 0 && !can_cruise) continue;
+                if (p == 0 && can_cruise && tier.lds < kLdsBytes) continue;  // try the next tier first
+                const int scap = cap > p ? cap : p;
+                size_t wq_bytes = wq_min;
+                if (wq_bytes < (size_t)(scap + p) * 4) wq_bytes = (size_t)(scap + p) * 4;
+                wq_bytes = up16(wq_bytes);
+                size_t plb = up16((size_t)span * 4);             // bounds of a span / the possibles list
+                if (plb < (size_t)p * 8) plb = (size_t)p * 8;
+                const size_t total = rest + up16((size_t)scap * 4) + plb + wq_bytes;
+                if (total > tier.lds) continue;
+                pl->P = P;
+                pl->Mp = Mp;
+                pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
+                size_t off = tab;
+                pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
+                pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
+                pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
+                pl->off_spos = (uint32_t)off; off += up16((size_t)scap * 4);
+                pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
+                pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+                pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+                pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
+                pl->off_plb = (uint32_t)off;  off += plb;
+                pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
+                pl->off_wq = (uint32_t)off;   off += wq_bytes;
+                pl->off_sd2 = pl->off_wq;
+                pl->span = span;
+                pl->lds = off;
+                pl->threads = tier.threads;
+                pl->wqcap = wqcap;
+                pl->cruise = p > 0 ? cruise : 0;
+                pl->poss_cap = p;
+                pl->scap = scap;
+                return true;
             }
-            pl->P = P;
-            pl->Mp = Mp;
-            pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
-            size_t off = tab;
-            pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
-            pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
-            pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
-            pl->off_spos = (uint32_t)off; off += up16((size_t)cap * 4);
-            pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
-            pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
-            pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
-            pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
-            pl->off_plb = (uint32_t)off;  off += plb;
-            pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
-            pl->off_wq = (uint32_t)off;   off += wq_bytes;
-            pl->off_sd2 = pl->off_wq;
-            pl->span = span;
-            pl->lds = off;
-            pl->threads = tier.threads;
-            pl->wqcap = wqcap;
-            pl->cruise = can_cruise ? cruise : 0;
-            pl->poss_cap = (int)(plb / 8);
-            return true;
         }
     }
     return false;
@@ -205,7 +210,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
     a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
-    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap;
+    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap; a.scap = pl.scap;
     a.small_addr = ix->n < (int64_t(1) << 24) && ix->n * (int64_t)ix->M < (int64_t(1) << 32) &&
                    ix->M < (1 << 24);
 }

@@ -75,6 +75,7 @@ struct SearchArgs {
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
     int32_t small_addr;  // n < 2^24 and n*M < 2^32: 24-bit multiply and 32-bit offsets suffice
     int32_t poss_cap;  // capacity of the possibles list
+    int32_t scap;      // entries of spos[] and of sd2[] (>= survivor capacity and >= poss_cap)
 };
 
 // One record of the optional scan head.
@@ -154,52 +155,38 @@ __host__ __device__ inline int result_slots(int k) { return k <= 64 ? 1 : k <= 1
 // entries, ascending by (d2,id), unused slots = (+inf, kEmptyId)); during the call lane l
 // keeps entries l*E .. l*E+E-1 in registers, so an insertion is a ballot (rank), one
 // cross-lane shift and a few selects, with no LDS round trip.
+// The result set R in one wave's registers: 64*E entries ascending by (d2,id), lane l holding
+// entries l*E .. l*E+E-1, unused slots = (+inf, kEmptyId).  R lives in LDS between uses.
 template <int E>
-__device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid, int ns,
-                                            float *rd2, int32_t *rid, Ctl *ctl, int k, int lane) {
+struct ResultRegs {
     float r_d2[E];
     int32_t r_id[E];
-#pragma unroll
-    for (int s = 0; s < E; ++s) { r_d2[s] = rd2[lane * E + s]; r_id[s] = rid[lane * E + s]; }
-    const int kl = (k - 1) / E, ks = (k - 1) % E;  // lane and slot of the k-th entry
-    float t_d2;
+    float t_d2;      // the k-th entry (tau): +inf while R holds fewer than k entries
     int32_t t_id;
-    auto load_kth = [&]() {
+    int k, lane, kl, ks;
+
+    __device__ __forceinline__ void load(const float *rd2, const int32_t *rid, int k_, int lane_) {
+        k = k_; lane = lane_;
+        kl = (k - 1) / E; ks = (k - 1) % E;  // lane and slot of the k-th entry
+#pragma unroll
+        for (int s = 0; s < E; ++s) { r_d2[s] = rd2[lane * E + s]; r_id[s] = rid[lane * E + s]; }
+        load_kth();
+    }
+    __device__ __forceinline__ void store(float *rd2, int32_t *rid) const {
+#pragma unroll
+        for (int s = 0; s < E; ++s) { rd2[lane * E + s] = r_d2[s]; rid[lane * E + s] = r_id[s]; }
+    }
+    __device__ __forceinline__ void load_kth() {
         float vd = r_d2[0];
         int32_t vi = r_id[0];
 #pragma unroll
         for (int s = 1; s < E; ++s) if (s == ks) { vd = r_d2[s]; vi = r_id[s]; }
         t_d2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vd), kl));  // kl is uniform
         t_id = __builtin_amdgcn_readlane(vi, kl);
-    };
-    load_kth();
-    // A long list (the first batch after the seed) is pre-filtered: lane l takes the minimum of
-    // entries l, l+64, ...; the k-th smallest of these 64 minima (distinct entries) is an upper
-    // bound on the k-th distance after the merge, so entries above it never enter R and skip
-    // the one-at-a-time insertion below.  (One entry per lane: result sets up to 64.)
-    float cut = __builtin_inff();
-    if constexpr (E == 1) {
-        if (ns > 2 * kWave) {
-            float cmin = __builtin_inff();
-            for (int i = lane; i < ns; i += kWave) cmin = __builtin_fminf(cmin, sd2[i]);
-#pragma unroll
-            for (int size = 2; size <= kWave; size <<= 1) {
-#pragma unroll
-                for (int j = size >> 1; j > 0; j >>= 1) {   // bitonic network across the lanes
-                    const float other = __shfl_xor(cmin, j);
-                    const bool keep_min = ((lane & j) == 0) == ((lane & size) == 0);
-                    cmin = keep_min ? __builtin_fminf(cmin, other) : __builtin_fmaxf(cmin, other);
-                }
-            }
-            cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cmin), k - 1));
-        }
     }
-    for (int i0 = 0; i0 < ns; i0 += kWave) {
-        const int i = i0 + lane;
-        bool pending = i < ns;
-        float d2 = 0.0f;
-        int32_t id = 0;
-        if (pending) { d2 = sd2[i]; id = sid[i]; pending = d2 <= cut; }
+    // Insert the lanes' items (one per lane with `pending` set) that beat the k-th entry, one at
+    // a time: an insertion is a ballot (rank), one cross-lane shift and a few selects.
+    __device__ __forceinline__ void insert_pending(bool pending, float d2, int32_t id) {
         for (;;) {
             const unsigned long long m = __ballot(pending && hit_less(d2, id, t_d2, t_id));
             if (m == 0) break;
@@ -228,9 +215,95 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
             load_kth();
         }
     }
+};
+
+// Merge the refined survivors of a batch into R and publish tau (the "result queue update"
+// of Section 4.2).  Executed by ONE whole wave.
+template <int E>
+__device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid, int ns,
+                                            float *rd2, int32_t *rid, Ctl *ctl, int k, int lane) {
+    ResultRegs<E> R;
+    R.load(rd2, rid, k, lane);
+    // A long list (the first batch after the seed) is pre-filtered: lane l takes the minimum of
+    // entries l, l+64, ...; the k-th smallest of these 64 minima (distinct entries) is an upper
+    // bound on the k-th distance after the merge, so entries above it never enter R and skip
+    // the one-at-a-time insertion below.  (One entry per lane: result sets up to 64.)
+    float cut = __builtin_inff();
+    if constexpr (E == 1) {
+        if (ns > 2 * kWave) {
+            float cmin = __builtin_inff();
+            for (int i = lane; i < ns; i += kWave) cmin = __builtin_fminf(cmin, sd2[i]);
 #pragma unroll
-    for (int s = 0; s < E; ++s) { rd2[lane * E + s] = r_d2[s]; rid[lane * E + s] = r_id[s]; }
-    if (lane == 0) ctl->tau = t_d2;  // +inf while R holds fewer than k entries
+            for (int size = 2; size <= kWave; size <<= 1) {
+#pragma unroll
+                for (int j = size >> 1; j > 0; j >>= 1) {   // bitonic network across the lanes
+                    const float other = __shfl_xor(cmin, j);
+                    const bool keep_min = ((lane & j) == 0) == ((lane & size) == 0);
+                    cmin = keep_min ? __builtin_fminf(cmin, other) : __builtin_fmaxf(cmin, other);
+                }
+            }
+            cut = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(cmin), k - 1));
+        }
+    }
+    for (int i0 = 0; i0 < ns; i0 += kWave) {
+        const int i = i0 + lane;
+        bool pending = i < ns;
+        float d2 = 0.0f;
+        int32_t id = 0;
+        if (pending) { d2 = sd2[i]; id = sid[i]; pending = d2 <= cut; }
+        R.insert_pending(pending, d2, id);
+    }
+    R.store(rd2, rid);
+    if (lane == 0) ctl->tau = R.t_d2;  // +inf while R holds fewer than k entries
+}
+
+// Replay of the batch rule over the possibles of a stretch (Section 4.2's threshold update,
+// taken batch by batch), by ONE wave, with no barrier.  The entries 0..np-1 are grouped by
+// batch in ascending batch order (any order inside a batch) and carry their candidate number
+// (relative to the stretch), bound, exact distance and id.  For each batch in turn the threshold
+// is frozen at the current k-th distance; the batch's entries whose bound passes it are its
+// survivors: they are counted, marked, and merged into R.  Returns the number of survivors.
+template <int E>
+__device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *s_g, const float *s_d2,
+                                              const int32_t *s_id, int np, int batch, int c0,
+                                              uint32_t *mask_row, int64_t mask_words, float *rd2,
+                                              int32_t *rid, Ctl *ctl, int k, int lane) {
+    ResultRegs<E> R;
+    R.load(rd2, rid, k, lane);
+    int frozen_b = -1;
+    float tau_f = R.t_d2;
+    int total = 0;
+    for (int i0 = 0; i0 < np; i0 += kWave) {
+        const int i = i0 + lane;
+        bool pending = i < np;
+        int cl = 0, b = 0;
+        int32_t id = 0;
+        float g = __builtin_inff(), d2 = 0.0f;
+        if (pending) { cl = s_cl[i]; g = s_g[i]; d2 = s_d2[i]; id = s_id[i]; b = cl / batch; }
+        for (;;) {
+            // thresholds only fall: an entry of a batch not yet begun whose bound exceeds the
+            // current k-th distance can no longer survive
+            pending = pending && (b == frozen_b || g <= R.t_d2);
+            const unsigned long long m = __ballot(pending);
+            if (m == 0) break;
+            const int first = __ffsll((long long)m) - 1;   // lowest pending batch (entries are grouped)
+            const int fb = __builtin_amdgcn_readlane(b, first);
+            if (fb != frozen_b) { frozen_b = fb; tau_f = R.t_d2; }
+            const bool grp = pending && b == fb;
+            const bool sel = grp && g <= tau_f;
+            total += __popcll(__ballot(sel));
+            if (sel && mask_row) {
+                const int c = c0 + cl;
+                const int64_t wi = c >> 5;
+                if (wi < mask_words) atomicOr(&mask_row[wi], 1u << (c & 31));
+            }
+            R.insert_pending(sel, d2, id);
+            pending = pending && !grp;
+        }
+    }
+    R.store(rd2, rid);
+    if (lane == 0) ctl->tau = R.t_d2;
+    return total;
 }
 
 // E = result_slots(k) is a template parameter of the kernel, so that the common small-k case
@@ -369,10 +442,10 @@ void search_kernel(const SearchArgs a) {
         }
     };
 
-    // Refine the listed survivors (one half wave per raw row, two rows in flight), then
-    // select: merge into R and publish the new tau.  Called by the whole block after a
-    // barrier that made the survivor list visible; ends with a barrier.
-    auto refine_and_select = [&](int ns) {
+    // Exact distances of `ns` listed candidates: one half wave per raw row, four rows in flight
+    // per half wave.  pos_of(i) gives the storage position of entry i; put(i, d2, id or
+    // position) stores the result (called by one lane of the half wave).
+    auto refine_rows = [&](int ns, auto pos_of, auto put) {
         for (int i = half; i < ns; i += 4 * nhalf) {
             int idx[4], pos[4];
             bool ok[4];
@@ -380,7 +453,7 @@ void search_kernel(const SearchArgs a) {
             for (int u = 0; u < 4; ++u) {
                 idx[u] = i + u * nhalf;
                 ok[u] = idx[u] < ns;              // uniform within the half wave
-                pos[u] = spos[ok[u] ? idx[u] : i];
+                pos[u] = pos_of(ok[u] ? idx[u] : i);
             }
             int32_t rid4[4];  // ids are fetched together with the rows, not after them
 #pragma unroll
@@ -391,19 +464,27 @@ void search_kernel(const SearchArgs a) {
                              a.d, lane32, d2);
             if (lane32 == 0) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (!ok[u]) continue;
-                    if (MODE == kKnn) {
-                        sd2[idx[u]] = d2[u];
-                        spos[idx[u]] = rid4[u];
-                    } else if (d2[u] <= a.radius2) {
-                        const int c = sidx[idx[u]];
-                        atomicOr(&a.result_mask[(size_t)q * a.rmask_words + (c >> 5)], 1u << (c & 31));
-                        atomicAdd(&ctl->nresult, 1);
-                    }
-                }
+                for (int u = 0; u < 4; ++u)
+                    if (ok[u]) put(idx[u], d2[u], rid4[u]);
             }
         }
+    };
+
+    // Refine the listed survivors, then select: merge into R and publish the new tau.  Called
+    // by the whole block after a barrier that made the survivor list visible; ends with a
+    // barrier.
+    auto refine_and_select = [&](int ns) {
+        refine_rows(ns, [&](int i) { return spos[i]; },
+                    [&](int i, float d2, int32_t id) {
+                        if (MODE == kKnn) {
+                            sd2[i] = d2;
+                            spos[i] = id;
+                        } else if (d2 <= a.radius2) {
+                            const int c = sidx[i];
+                            atomicOr(&a.result_mask[(size_t)q * a.rmask_words + (c >> 5)], 1u << (c & 31));
+                            atomicAdd(&ctl->nresult, 1);
+                        }
+                    });
         __syncthreads();
         TRIM_TICK(4);
         if (MODE == kKnn && tid < kWave) merge_batch<E>(sd2, spos, ns, rd2, rid, ctl, a.k, lane);
@@ -413,6 +494,50 @@ void search_kernel(const SearchArgs a) {
         }
         __syncthreads();
         TRIM_TICK(5);
+    };
+
+    // ---- stage B by replay (k <= 64): the possibles of a stretch or span, already laid out in
+    // batch order in spos[] (candidate number relative to c0) and s_g[] (bound), ALL get their
+    // exact distance in one parallel pass, and one wave then replays the batch rule over them
+    // without any barrier.  A possible that turns out not to survive its batch has had its
+    // distance computed in vain; that is the price of dropping the barriers (and the refine
+    // latency) of every single batch.  Called after a barrier; the caller's next barrier waits
+    // for the replaying wave.
+    auto counts_to_offsets = [&](int nb) {   // cnt0[0..nb): counts -> exclusive prefix; total -> nposs
+        if (tid < kWave) {
+            const int per = (nb + kWave - 1) / kWave;
+            int sum = 0;
+            for (int e = 0; e < per; ++e) {
+                const int idx = lane * per + e;
+                if (idx < nb) sum += cnt0[idx];
+            }
+            int incl = sum;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int t = __shfl_up(incl, off);
+                if (lane >= off) incl += t;
+            }
+            int run = incl - sum;
+            for (int e = 0; e < per; ++e) {
+                const int idx = lane * per + e;
+                if (idx < nb) { const int v = cnt0[idx]; cnt0[idx] = run; run += v; }
+            }
+            if (lane == kWave - 1) ctl->nposs = incl;
+        }
+    };
+    auto refine_and_replay = [&](int np, int c0) {
+        float *s_g = sd2 + a.scap;                                 // bounds, in batch order
+        int32_t *s_id = reinterpret_cast<int32_t *>(smem + a.off_plb);  // ids (that area is dead by now)
+        refine_rows(np, [&](int i) { return locate(c0 + spos[i]); },
+                    [&](int i, float d2, int32_t id) { sd2[i] = d2; s_id[i] = id; });
+        __syncthreads();
+        TRIM_TICK(14);
+        if (tid < kWave) {
+            const int n = replay_batches<E>(spos, s_g, sd2, s_id, np, a.batch, c0,
+                                            a.mask ? a.mask + (size_t)q * a.mask_words : nullptr,
+                                            a.mask_words, rd2, rid, ctl, a.k, lane);
+            if (lane == 0) ctl->nexact += n;
+        }
     };
 
     TRIM_TICK(0);
@@ -462,6 +587,8 @@ void search_kernel(const SearchArgs a) {
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
     int ramp = MODE == kKnn ? a.first_batch : a.batch;  // next batch size while below a.batch
+    // next span length while the spans of a small-batch search still grow (a multiple of batch)
+    int small_span = (MODE == kKnn && E == 1 && a.batch < 64) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
@@ -478,8 +605,10 @@ void search_kernel(const SearchArgs a) {
         // replayed in order over that list.  If the list overflows, nothing has been
         // committed: the stretch is redone span by span below.
         // (The first span after the seed is always taken span by span: it is what makes tau tight.)
-        if (cruise > 0 && !ramping && c0 > c_begin + kseed && tau0 < __builtin_inff() &&
-            c_end - c0 > a.span) {
+        int replay_np = -1;  // >= 0: the candidates [c0, c0 + advance) end in a replay of that many possibles
+        int advance = 0;
+        if (cruise > 0 && !ramping && small_span >= a.span && c0 > c_begin + kseed &&
+            tau0 < __builtin_inff() && c_end - c0 > a.span) {
             const int S = c0 + cruise < c_end ? cruise : c_end - c0;
             const int nb = (S + a.batch - 1) / a.batch;
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
@@ -655,40 +784,67 @@ void search_kernel(const SearchArgs a) {
             TRIM_TICK(6);
             const int np = ctl->nposs;
             if (np <= a.poss_cap) {
-                for (int b = 0; b < nb; ++b) {
-                    if (cnt0[b] == 0) continue;  // same value for every thread
-                    const float tau = ctl->tau;
-                    for (int i0 = 0; i0 < np; i0 += T) {
-                        const int i = i0 + tid;
-                        int cl = 0;
-                        bool live = false;
-                        if (i < np) {
-                            cl = poss_cl[i];
-                            live = cl / a.batch == b && poss_g[i] <= tau;
+                // Stage B of a stretch.  The possibles are put in batch order (counting sort on
+                // the per-batch counts), ALL get their exact distance in one parallel pass, and
+                // one wave then replays the batch rule over them without any barrier.  A possible
+                // that turns out not to survive its batch has had its distance computed in vain;
+                // thresholds fall slowly this deep into the scan, so these are few.
+                if (E > 1) {
+                    // wide result sets: batch by batch, each with its own refine and merge
+                    for (int b = 0; b < nb; ++b) {
+                        if (cnt0[b] == 0) continue;  // same value for every thread
+                        const float tau = ctl->tau;
+                        for (int i0 = 0; i0 < np; i0 += T) {
+                            const int i = i0 + tid;
+                            int cl = 0;
+                            bool live = false;
+                            if (i < np) {
+                                cl = poss_cl[i];
+                                live = cl / a.batch == b && poss_g[i] <= tau;
+                            }
+                            append(live, c0 + cl);
                         }
-                        append(live, c0 + cl);
+                        __syncthreads();
+                        const int ns = ctl->nsurv;
+                        __syncthreads();
+                        if (ns > 0) refine_and_select(ns);
                     }
-                    __syncthreads();
-                    const int ns = ctl->nsurv;
-                    __syncthreads();
-                    TRIM_TICK(3);
-                    if (ns > 0) refine_and_select(ns);
+                    c0 += S;
+                    continue;
                 }
-                TRIM_TICK(3);
-                c0 += S;
-                continue;
+                replay_np = np;
+                advance = S;
+                if (np > 0) {
+                    counts_to_offsets(nb);
+                    __syncthreads();
+                    float *s_g = sd2 + a.scap;
+                    for (int i = tid; i < np; i += T) {
+                        const int cl = poss_cl[i];
+                        const int slot = atomicAdd(&cnt0[cl / a.batch], 1);
+                        spos[slot] = cl;
+                        s_g[slot] = poss_g[i];
+                    }
+                }
+            } else {
+                // overflow: shorter stretches from now on (or none), and redo from c0 span by span
+                cruise = cruise / 2 >= 2 * a.span ? cruise / 2 / a.batch * a.batch : 0;
+                cur.init(segp, segd);
+                __syncthreads();
             }
-            // overflow: shorter stretches from now on (or none), and redo from c0 span by span
-            cruise = cruise / 2 >= 2 * a.span ? cruise / 2 / a.batch * a.batch : 0;
-            cur.init(segp, segd);
-            __syncthreads();
         }
+        if (replay_np < 0) {
 
         // The first stretch after the seed is a single batch: its threshold (from the k seeds)
         // is loose, so nothing is abandoned early; one batch is enough to make tau tight.
         // While the batches still grow, each is taken alone.
-        const int span_len = ramping ? ramp : c0 == c_begin + kseed ? a.batch : a.span;
+        // Small batches: the first spans are short too (64 candidates, then doubling), so that
+        // tau is tight before a full span's possibles have to fit the replay.
+        int span_len = ramping ? ramp : c0 == c_begin + kseed ? a.batch : a.span;
         if (ramping) ramp = 2 * ramp < a.batch ? 2 * ramp : a.batch;
+        if (!ramping && small_span < a.span) {
+            span_len = small_span;
+            small_span *= 2;
+        }
         const int span = c0 + span_len < c_end ? span_len : c_end - c0;
         const int nb = (span + a.batch - 1) / a.batch;
         for (int b = tid; b < nb; b += T) cnt0[b] = 0;
@@ -889,8 +1045,34 @@ void search_kernel(const SearchArgs a) {
         }
         __syncthreads();
         TRIM_TICK(2);
-        for (int b = 0; b < nb; ++b) {
-            if (cnt0[b] == 0) continue;  // same value for every thread: no barrier needed
+        // Several batches in the span and a result set of at most 64: replay (see above), unless
+        // the possibles do not fit its arrays (a loose threshold: then batch by batch as below).
+        int np_span = -1;
+        if (MODE == kKnn && E == 1 && nb > 1) {
+            counts_to_offsets(nb);
+            __syncthreads();
+            np_span = ctl->nposs;
+            if (np_span <= a.scap) {
+                replay_np = np_span;
+                advance = span;
+                if (np_span > 0) {
+                    float *s_g = sd2 + a.scap;
+                    for (int i = tid; i < span; i += T) {
+                        const float g = plbs[i];
+                        if (g <= tau0) {
+                            const int slot = atomicAdd(&cnt0[i / a.batch], 1);
+                            spos[slot] = i;
+                            s_g[slot] = g;
+                        }
+                    }
+                }
+            }
+        }
+        for (int b = 0; replay_np < 0 && b < nb; ++b) {
+            // same value for every thread: no barrier needed (np_span >= 0: counts were turned
+            // into start offsets above)
+            const int cb = np_span < 0 ? cnt0[b] : (b + 1 < nb ? cnt0[b + 1] : np_span) - cnt0[b];
+            if (cb == 0) continue;
 
             const float tau = ctl->tau;
             const int l0 = b * a.batch;
@@ -907,7 +1089,15 @@ void search_kernel(const SearchArgs a) {
             if (ns > 0) refine_and_select(ns);
         }
         TRIM_TICK(3);
-        c0 += span;
+        if (replay_np < 0) advance = span;
+        }  // span path
+        if (replay_np > 0) {
+            __syncthreads();   // the possibles are in place
+            TRIM_TICK(13);
+            refine_and_replay(replay_np, c0);
+            TRIM_TICK(15);
+        }
+        c0 += advance;
     }
 
     // ---- epilogue ----
