@@ -38,7 +38,7 @@ struct Plan {
     size_t lds;
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
-    int span, wqcap, cruise, poss_cap, scap;
+    int span, wqcap, cruise, poss_cap, scap, bucket;
 };
 
 // Decide table phases, block size and LDS layout for a search launch.
@@ -70,11 +70,17 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
     const int span = nbatch * batch;
     if (span > 65535) return false;
-    // cruise stretches: up to 61440 candidates (16-bit queue entries) and 1024 batches
-    int cruise = 61440 < 1024 * (int64_t)batch ? 61440 : 1024 * batch;
+    // cruise stretches: up to 61440 candidates (16-bit queue entries).  Their possibles are
+    // counted per bucket of `bucket` candidates (a whole number of batches, at most 1024
+    // buckets); wide result sets (more than 64) count per batch and keep to 1024 batches.
+    const bool small_k = !range && result_slots(k) == 1;
+    int cruise = (small_k || 61440 < 1024 * (int64_t)batch) ? 61440 : 1024 * batch;
     cruise = cruise / batch * batch;
     if (range || cruise < 2 * span) cruise = 0;
-    const int ncnt = cruise / batch > nbatch ? cruise / batch : nbatch;
+    int bucket = batch;
+    if (small_k && cruise / batch > 1024) bucket = batch * (((cruise + 1023) / 1024 + batch - 1) / batch);
+    const int nbucket = cruise > 0 ? (cruise + bucket - 1) / bucket : 0;
+    const int ncnt = nbucket > nbatch ? nbucket : nbatch;
     for (int P = 1; P <= M / 4; ++P) {
         if (M % P) continue;
         const int Mp = M / P;
@@ -131,6 +137,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 pl->cruise = p > 0 ? cruise : 0;
                 pl->poss_cap = p;
                 pl->scap = scap;
+                pl->bucket = bucket;
                 return true;
             }
         }
@@ -210,7 +217,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
     a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
-    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap; a.scap = pl.scap;
+    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap; a.scap = pl.scap; a.bucket = pl.bucket;
     a.small_addr = ix->n < (int64_t(1) << 24) && ix->n * (int64_t)ix->M < (int64_t(1) << 32) &&
                    ix->M < (1 << 24);
 }

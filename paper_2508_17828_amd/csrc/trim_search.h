@@ -76,6 +76,7 @@ struct SearchArgs {
     int32_t small_addr;  // n < 2^24 and n*M < 2^32: 24-bit multiply and 32-bit offsets suffice
     int32_t poss_cap;  // capacity of the possibles list
     int32_t scap;      // entries of spos[] and of sd2[] (>= survivor capacity and >= poss_cap)
+    int32_t bucket;    // cruise: possibles are counted per bucket of this many candidates (a multiple of batch)
 };
 
 // One record of the optional scan head.
@@ -610,7 +611,7 @@ void search_kernel(const SearchArgs a) {
         if (cruise > 0 && !ramping && small_span >= a.span && c0 > c_begin + kseed &&
             tau0 < __builtin_inff() && c_end - c0 > a.span) {
             const int S = c0 + cruise < c_end ? cruise : c_end - c0;
-            const int nb = (S + a.batch - 1) / a.batch;
+            const int nb = (S + a.bucket - 1) / a.bucket;   // buckets (= batches unless they are very small)
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
             if (tid == 0) ctl->nposs = 0;
             __syncthreads();
@@ -674,7 +675,7 @@ void search_kernel(const SearchArgs a) {
                             if (g <= tau0) {
                                 const int at = atomicAdd(&ctl->nposs, 1);
                                 if (at < a.poss_cap) { poss_cl[at] = d_cl; poss_g[at] = g; }
-                                atomicAdd(&cnt0[d_cl / a.batch], 1);
+                                atomicAdd(&cnt0[d_cl / a.bucket], 1);
                             }
                         }
                     }
@@ -820,9 +821,24 @@ void search_kernel(const SearchArgs a) {
                     float *s_g = sd2 + a.scap;
                     for (int i = tid; i < np; i += T) {
                         const int cl = poss_cl[i];
-                        const int slot = atomicAdd(&cnt0[cl / a.batch], 1);
+                        const int slot = atomicAdd(&cnt0[cl / a.bucket], 1);
                         spos[slot] = cl;
                         s_g[slot] = poss_g[i];
+                    }
+                    if (a.bucket > a.batch) {
+                        // a bucket holds several batches: put its few entries in scan order
+                        __syncthreads();
+                        for (int t = tid; t < nb; t += T) {
+                            const int lo = t > 0 ? cnt0[t - 1] : 0, hi = cnt0[t];  // ends after the scatter
+                            for (int x = lo + 1; x < hi; ++x) {
+                                const int cx = spos[x];
+                                const float gx = s_g[x];
+                                int y = x - 1;
+                                while (y >= lo && spos[y] > cx) { spos[y + 1] = spos[y]; s_g[y + 1] = s_g[y]; --y; }
+                                spos[y + 1] = cx;
+                                s_g[y + 1] = gx;
+                            }
+                        }
                     }
                 }
             } else {
