@@ -78,6 +78,25 @@ def test_knn_full_batch_sampled_against_oracle(c2, oracle, gamma):
         np.testing.assert_array_equal(ids[qs], bi)
 
 
+@pytest.mark.parametrize("batch", [1, 16, 100])
+def test_knn_small_batches_sampled_against_oracle(c2, oracle, batch):
+    """Small batches down to batch = 1, the paper's vector-at-a-time rule, at the benchmark's
+    full size (stage B by replay, long barrier-free stretches with bucketed possibles)."""
+    T, w, bw, host = c2["trim"], c2["w"], c2["bw"], c2["host"]
+    gamma = 0.4
+    full = T.trim_search_knn(bw.index, bw.queries, w.k, gamma, batch, probes=c2["probes"], want_mask=True)
+    ids, d2 = full["ids"].cpu().numpy(), full["d2"].cpu().numpy()
+    assert np.all(np.diff(d2, axis=1) >= 0) and np.all(ids >= 0)
+    qs = np.sort(synth.sample_indices(81, batch, w.nq, 16))
+    hp = c2["probes"].cpu().numpy()[qs]
+    ref = oracle.search_knn(host, np.ascontiguousarray(c2["queries"][qs]), w.k, gamma, batch, hp, want_mask=True)
+    np.testing.assert_array_equal(ids[qs], ref["ids"])
+    np.testing.assert_array_equal(d2[qs], ref["d2"])
+    np.testing.assert_array_equal(full["n_exact"].cpu().numpy()[qs], ref["n_exact"])
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(full["mask"].cpu().numpy().view(np.uint32)[qs][:, :mw], ref["mask"])
+
+
 def test_range_full_batch_sampled_against_oracle(c2, oracle):
     T, w, bw, host = c2["trim"], c2["w"], c2["bw"], c2["host"]
     knn = T.trim_search_knn(bw.index, bw.queries, w.k, 0.0, w.batch, probes=c2["probes"])
