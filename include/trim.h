@@ -83,8 +83,12 @@ typedef struct trim_candidates {
                                     masks; a query with more candidates is cut at this bound */
 } trim_candidates;
 
-/* Optional per-query counters (device, each [nq] or NULL): candidates scanned, and
- * candidates whose exact distance was computed.  Pruning ratio = 1 - n_exact/n_scanned. */
+/* Optional per-query counters (device, each [nq] or NULL): candidates scanned, and survivors
+ * of the filter, i.e. the candidates whose exact distance the scan of Section 4.2 calls for.
+ * Pruning ratio = 1 - n_exact/n_scanned.  (kNN with k <= 64 computes the exact distance of a
+ * few more candidates than it counts: those that passed the threshold in force when their
+ * stretch of the scan began but not the lower one of their own batch.  They change neither
+ * the results nor the survivor mask.) */
 typedef struct trim_stats {
     int32_t *n_scanned;
     int32_t *n_exact;
