@@ -264,7 +264,8 @@ __device__ __forceinline__ void merge_batch(const float *sd2, const int32_t *sid
 // (relative to the stretch), bound, exact distance and id.  For each batch in turn the threshold
 // is frozen at the current k-th distance; the batch's entries whose bound passes it are its
 // survivors: they are counted, marked, and merged into R.  Returns the number of survivors.
-template <int E>
+// BULK (for small batches): survivors that do not beat the k-th distance are handled all at once.
+template <int E, bool BULK>
 __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *s_g, const float *s_d2,
                                               const int32_t *s_id, int np, int batch, int c0,
                                               uint32_t *mask_row, int64_t mask_words, float *rd2,
@@ -281,7 +282,7 @@ __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *
         int32_t id = 0;
         float g = __builtin_inff(), d2 = 0.0f;
         if (pending) { cl = s_cl[i]; g = s_g[i]; d2 = s_d2[i]; id = s_id[i]; b = cl / batch; }
-        for (;;) {
+        for (; !BULK;) {
             // thresholds only fall: an entry of a batch not yet begun whose bound exceeds the
             // current k-th distance can no longer survive
             pending = pending && (b == frozen_b || g <= R.t_d2);
@@ -300,6 +301,41 @@ __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *
             }
             R.insert_pending(sel, d2, id);
             pending = pending && !grp;
+        }
+        for (; BULK;) {
+            // An entry can still survive only if its bound passes the threshold of its batch: the
+            // frozen one if its batch has begun, else the current k-th distance (thresholds only
+            // fall, so failing it now is final).
+            pending = pending && g <= (b == frozen_b ? tau_f : R.t_d2);
+            // Only an entry that also beats the k-th distance changes anything.  Up to the first
+            // such entry (in batch order) every pending entry is a survivor of a batch whose
+            // threshold is the current k-th distance: counted and marked in one go.
+            const unsigned long long mi = __ballot(pending && hit_less(d2, id, R.t_d2, R.t_id));
+            int fb = 0x7fffffff;
+            if (mi != 0) fb = __builtin_amdgcn_readlane(b, __ffsll((long long)mi) - 1);
+            const bool plain = pending && b < fb;
+            total += __popcll(__ballot(plain));
+            if (plain && mask_row) {
+                const int c = c0 + cl;
+                const int64_t wi = c >> 5;
+                if (wi < mask_words) atomicOr(&mask_row[wi], 1u << (c & 31));
+            }
+            pending = pending && !plain;
+            // (a batch that goes on in the next chunk keeps its threshold: the frozen one if it
+            // was frozen here, else the k-th distance, unchanged since that batch began)
+            if (mi == 0) break;
+            // the batch of the first improving entry: frozen threshold, all its passing entries
+            // survive, those that beat the k-th distance are merged
+            if (fb != frozen_b) { frozen_b = fb; tau_f = R.t_d2; }
+            const bool sel = pending && b == fb;
+            total += __popcll(__ballot(sel));
+            if (sel && mask_row) {
+                const int c = c0 + cl;
+                const int64_t wi = c >> 5;
+                if (wi < mask_words) atomicOr(&mask_row[wi], 1u << (c & 31));
+            }
+            R.insert_pending(sel, d2, id);
+            pending = pending && !sel;
         }
     }
     R.store(rd2, rid);
@@ -534,9 +570,12 @@ void search_kernel(const SearchArgs a) {
         __syncthreads();
         TRIM_TICK(14);
         if (tid < kWave) {
-            const int n = replay_batches<E>(spos, s_g, sd2, s_id, np, a.batch, c0,
-                                            a.mask ? a.mask + (size_t)q * a.mask_words : nullptr,
-                                            a.mask_words, rd2, rid, ctl, a.k, lane);
+            uint32_t *mrow = a.mask ? a.mask + (size_t)q * a.mask_words : nullptr;
+            const int n = a.batch < kWave
+                ? replay_batches<E, true>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
+                                          rd2, rid, ctl, a.k, lane)
+                : replay_batches<E, false>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
+                                           rd2, rid, ctl, a.k, lane);
             if (lane == 0) ctl->nexact += n;
         }
     };
