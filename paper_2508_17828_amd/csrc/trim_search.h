@@ -112,6 +112,7 @@ __device__ __forceinline__ CodeRow code_row(const SearchArgs &a, int pos) {
     return CodeRow{a.codes + (size_t)pos * a.M, 16u};
 }
 
+constexpr int kSmallBatch = 512;  // below this: short first spans and the bulk form of the replay
 constexpr int kRing = 256;  // entries of a wave's ring queue in cruise mode
 
 // Load or build the table rows [j0, j0+nj) of query q into LDS.
@@ -571,7 +572,7 @@ void search_kernel(const SearchArgs a) {
         TRIM_TICK(14);
         if (tid < kWave) {
             uint32_t *mrow = a.mask ? a.mask + (size_t)q * a.mask_words : nullptr;
-            const int n = a.batch < kWave
+            const int n = a.batch < kSmallBatch
                 ? replay_batches<E, true>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
                                           rd2, rid, ctl, a.k, lane)
                 : replay_batches<E, false>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
@@ -628,7 +629,7 @@ void search_kernel(const SearchArgs a) {
     int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
     int ramp = MODE == kKnn ? a.first_batch : a.batch;  // next batch size while below a.batch
     // next span length while the spans of a small-batch search still grow (a multiple of batch)
-    int small_span = (MODE == kKnn && E == 1 && a.batch < 64) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
+    int small_span = (MODE == kKnn && E == 1 && a.batch < kSmallBatch) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
@@ -892,7 +893,7 @@ void search_kernel(const SearchArgs a) {
         // The first stretch after the seed is a single batch: its threshold (from the k seeds)
         // is loose, so nothing is abandoned early; one batch is enough to make tau tight.
         // While the batches still grow, each is taken alone.
-        // Small batches: the first spans are short too (64 candidates, then doubling), so that
+        // Small batches: the first spans are short too (64 candidates or one batch, then doubling), so that
         // tau is tight before a full span's possibles have to fit the replay.
         int span_len = ramping ? ramp : c0 == c_begin + kseed ? a.batch : a.span;
         if (ramping) ramp = 2 * ramp < a.batch ? 2 * ramp : a.batch;
