@@ -241,6 +241,7 @@ def main():
     # on this workload; null when the timed configuration is not the profiled one)
     traffic = None
     valu = None
+    lds = None
     try:
         rec = json.load(open(os.path.join(ROOT, "profiles", "search_kernel_c2_traffic.json")))
         if (rec["workload"] == w.name and rec["gamma"] == gamma and rec["batch"] == batch
@@ -252,11 +253,18 @@ def main():
             peak = 256 * 4 * 2.4e9 / 4
             valu = dict(wave_instructions=insts, peak_per_s=peak,
                         frac=round(insts / (scan_ms * 1e-3) / peak, 4))
+            # on-chip-memory view: LDS wave instructions of the launch (SQ_INSTS_LDS) against the
+            # rate at which the library's lookup aid (random 4-byte table lookups and nothing
+            # else, `python -m paper_2508_17828_amd.ceiling_probe`) issues them
+            lds = dict(wave_instructions=rec["lds_wave_instructions_per_launch"],
+                       ceiling_per_s=rec["lds_lookup_ceiling_wave_instructions_per_s"],
+                       frac=round(rec["lds_wave_instructions_per_launch"] / (scan_ms * 1e-3) /
+                                  rec["lds_lookup_ceiling_wave_instructions_per_s"], 4))
     except (OSError, ValueError, KeyError):
         pass
     roofline = dict(bound="hbm", kernel="search_kernel<knn>", achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=traffic, valu=valu, kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
+                    traffic=traffic, valu=valu, lds=lds, kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
                     scan_stream_gbs=round(scan_bytes / (scan_ms * 1e-3) / 1e9, 1),
                     candidates_per_s=round(chosen["n_scanned"] / (scan_ms * 1e-3), 1))
 

@@ -267,6 +267,29 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
 int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t nlist,
                      int32_t *order_out, void *stream);
 
+/*
+ * Measurement aids (no counterpart in the paper): the two machine ceilings the scan of
+ * Section 4.2 is priced against.  Both launch `blocks` workgroups of 512 threads
+ * (1 <= blocks <= TRIM_CEILING_MAX_BLOCKS) on `stream` and return without synchronising; the
+ * caller times them.
+ *
+ * trim_ceiling_stream_read reads buf[0 .. bytes rounded down to 16) once (device, 16-byte
+ * aligned, bytes >= 16) and writes one checksum word per workgroup to sink [blocks] (device):
+ * the xor of these words is the xor of all 32-bit words read.  bytes / time = the
+ * streaming-read rate of the memory the buffer lives in (HBM for a buffer much larger than
+ * the caches).
+ *
+ * trim_ceiling_lds_gather has every thread perform iters * 32 lookups T[j][byte] in a
+ * [32][256] binary32 table held in on-chip memory, with the instruction sequence of the
+ * scan's own table sums (one lookup and one addition per code byte), and writes each thread's
+ * sum to sink [blocks * 512] (device).  1 <= iters <= 2^20.
+ * blocks * 512 * iters * 32 / time = lookups per second with nothing else going on.
+ */
+#define TRIM_CEILING_MAX_BLOCKS 65536
+int trim_ceiling_stream_read(const void *buf, size_t bytes, int32_t blocks, uint32_t *sink,
+                             void *stream);
+int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, uint32_t seed, float *sink, void *stream);
+
 /* Text for a trim_status. */
 const char *trim_strerror(int status);
 /* The hipError_t (as int) behind the calling thread's most recent TRIM_HIP_ERROR, else 0. */

@@ -300,6 +300,26 @@ int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks,
     return TRIM_OK;
 }
 
+int trim_ceiling_stream_read(const void *buf, size_t bytes, int32_t blocks, uint32_t *sink,
+                             void *stream) {
+    if (!buf || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(buf) & 15u)) return TRIM_INVALID_ARG;
+    if (blocks < 1 || blocks > TRIM_CEILING_MAX_BLOCKS) return TRIM_INVALID_ARG;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(512), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint4 *>(buf), bytes / 16,
+                       sink);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, uint32_t seed, float *sink, void *stream) {
+    if (!sink || iters < 1 || iters > (1 << 20)) return TRIM_INVALID_ARG;
+    if (blocks < 1 || blocks > TRIM_CEILING_MAX_BLOCKS) return TRIM_INVALID_ARG;
+    hipLaunchKernelGGL(lds_gather_kernel, dim3(blocks), dim3(512), 32 * kC * 4,
+                       static_cast<hipStream_t>(stream), iters, seed, sink);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
 int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32_t M,
                         void *head_out, void *stream) {
     if (n < 0 || n >= (int64_t(1) << 31) || M <= 0) return TRIM_INVALID_ARG;

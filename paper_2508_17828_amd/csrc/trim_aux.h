@@ -13,6 +13,65 @@ __global__ void fill_u32_kernel(uint32_t *p, size_t count, uint32_t v) {
         p[i] = v;
 }
 
+// ---- ceilings of the machine for the two resources the scan leans on (measurement aids) ----
+// Streaming read: every 16-byte piece of the buffer is read once, four loads in flight per
+// thread; the xor of everything read goes to sink[block] so that the loads cannot be dropped.
+__global__ __launch_bounds__(512) void stream_read_kernel(const uint4 *__restrict__ p, size_t n16,
+                                                          uint32_t *__restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], e = p[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ e.x ^ e.y ^ e.z ^ e.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = p[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
+    __shared__ uint32_t part[8];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t r = 0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) r ^= part[w];
+        sink[blockIdx.x] = r;
+    }
+}
+
+// Table gathers: the inner step of the scan and nothing else.  Each lane owns 32 code bytes
+// (8 words) and sums, per iteration, the 32 entries T[j][byte j] of a [32][256] binary32 table
+// in LDS with the scan's own gather routine; the code words are stirred between iterations so
+// that the reads stay random.  gathers = grid * 512 * iters * 32.
+__global__ __launch_bounds__(512) void lds_gather_kernel(int iters, uint32_t seed,
+                                                         float *__restrict__ sink) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *tab = reinterpret_cast<float *>(smem);  // [32][256]
+    for (int i = threadIdx.x; i < 32 * kC; i += blockDim.x) tab[i] = (float)((i * 2654435761u) >> 20);
+    __syncthreads();
+    const uint32_t tab_base = lds_addr(tab);
+    uint32_t w[8];
+    uint32_t h = seed ^ ((blockIdx.x * 512u + threadIdx.x) * 0x9e3779b9u);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+        w[v] = h;
+    }
+    float s = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+        const uint32_t lo[4] = {w[0], w[1], w[2], w[3]};
+        const uint32_t hi[4] = {w[4], w[5], w[6], w[7]};
+        s = gather_add<4>(s, tab_base, lo, __builtin_inff());
+        s = gather_add<4>(s, tab_base + 16 * kC * 4, hi, __builtin_inff());
+        const uint32_t t = w[0];
+#pragma unroll
+        for (int v = 0; v < 7; ++v) w[v] = w[v + 1];
+        w[7] = (t << 7 | t >> 25) ^ (uint32_t)it;
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // ---- scan head: {code bytes 0..7, landmark distance} of every vector as one 12-byte record ----
 __global__ void pack_scan_head_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ dlx,
                                       int64_t n, int M, uint32_t *__restrict__ head) {

@@ -23,6 +23,7 @@ TRIM_MAX_NPROBE = 4096
 EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
+           "trim_ceiling_stream_read", "trim_ceiling_lds_gather",
            "trim_strerror", "trim_last_hip_error", "trim_version")
 
 
@@ -91,6 +92,8 @@ def lib() -> C.CDLL:
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                       C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.trim_ceiling_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
+        L.trim_ceiling_lds_gather.argtypes = [C.c_int32, C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p]
         L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_search_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -363,3 +366,16 @@ def trim_query_order(probes: torch.Tensor, nlist: int) -> torch.Tensor:
     _check(lib().trim_query_order(_ptr(probes, torch.int32, "probes"), nq, nprobe, nlist,
                                   _ptr(order, torch.int32, "order"), _stream()), "trim_query_order")
     return order
+
+
+def trim_ceiling_stream_read(buf: torch.Tensor, blocks: int, sink: torch.Tensor) -> None:
+    assert sink.numel() >= blocks
+    _check(lib().trim_ceiling_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), blocks,
+                                          _ptr(sink, torch.int32, "sink"), _stream()),
+           "trim_ceiling_stream_read")
+
+
+def trim_ceiling_lds_gather(blocks: int, iters: int, seed: int, sink: torch.Tensor) -> None:
+    assert sink.numel() >= blocks * 512
+    _check(lib().trim_ceiling_lds_gather(blocks, iters, seed, _ptr(sink, torch.float32, "sink"),
+                                         _stream()), "trim_ceiling_lds_gather")

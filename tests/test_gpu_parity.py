@@ -366,6 +366,30 @@ def test_knn_is_deterministic(T, oracle):
         assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy())
 
 
+def test_ceiling_aids_read_what_they_claim(T):
+    """The streaming-read aid touches every 16-byte piece exactly once (its checksum is the xor
+    of the buffer, ragged tail of under 16 bytes left out); the lookup aid is deterministic."""
+    import torch
+    rng = np.random.default_rng(7)
+    for words, blocks in ((4, 1), (4 * 768 * 512 * 4 + 4 * 37, 768), (1_000_003, 300)):
+        host = rng.integers(0, 2**32, size=words, dtype=np.uint32)
+        buf = torch.from_numpy(host.view(np.int32)).cuda()
+        sink = torch.zeros(blocks, dtype=torch.int32, device="cuda")
+        T.trim_ceiling_stream_read(buf, blocks, sink)
+        got = np.bitwise_xor.reduce(u32(sink))
+        assert got == np.bitwise_xor.reduce(host[: words // 4 * 4])
+    a = torch.zeros(64 * 512, dtype=torch.float32, device="cuda")
+    c = torch.zeros_like(a)
+    T.trim_ceiling_lds_gather(64, 3, 99, a)
+    T.trim_ceiling_lds_gather(64, 3, 99, c)
+    assert torch.equal(a, c) and bool(torch.isfinite(a).all()) and float(a.min()) >= 0.0
+    assert len(torch.unique(a)) > 1000            # lanes follow different code bytes
+    with pytest.raises(T.TrimError):
+        T.trim_ceiling_lds_gather(0, 3, 99, a)
+    with pytest.raises(T.TrimError):
+        T.trim_ceiling_stream_read(buf, 1 << 20, torch.zeros(1 << 20, dtype=torch.int32, device="cuda"))
+
+
 def test_argument_errors(T):
     import torch
     b = case("c1")
