@@ -279,16 +279,20 @@ int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t 
  * streaming-read rate of the memory the buffer lives in (HBM for a buffer much larger than
  * the caches).
  *
- * trim_ceiling_lds_gather has every thread perform iters * 32 lookups T[j][byte] in a
- * [32][256] binary32 table held in on-chip memory, with the instruction sequence of the
- * scan's own table sums (one lookup and one addition per code byte), and writes each thread's
- * sum to sink [blocks * 512] (device).  1 <= iters <= 2^20.
+ * trim_ceiling_lds_gather, entry_floats = 1: every thread performs iters * 32 lookups
+ * T[j][byte] in a [32][256] binary32 table held in on-chip memory, with the instruction
+ * sequence of the scan's own table sums (one lookup and one addition per code byte), and
+ * writes its sum to sink [blocks * 512] (device).  1 <= iters <= 2^20.
  * blocks * 512 * iters * 32 / time = lookups per second with nothing else going on.
+ * entry_floats = 2 or 4: the table has 8 rows of 256 entries of that many binary32 values
+ * (what a table shared by 2 or 4 queries would hold); every thread performs iters * 8 lookups
+ * of a whole entry and adds its values up.  Other values: TRIM_INVALID_ARG.
  */
 #define TRIM_CEILING_MAX_BLOCKS 65536
 int trim_ceiling_stream_read(const void *buf, size_t bytes, int32_t blocks, uint32_t *sink,
                              void *stream);
-int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, uint32_t seed, float *sink, void *stream);
+int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, int32_t entry_floats, uint32_t seed,
+                            float *sink, void *stream);
 
 /* Text for a trim_status. */
 const char *trim_strerror(int status);

@@ -39,10 +39,15 @@ def main():
     for blocks in (256, 512, 768, 1024, 2048):      # 1..4 workgroups per CU, then two rounds
         t = _time(lambda: trim.trim_ceiling_lds_gather(blocks, iters, 12345, fsink), reps)
         look[blocks] = round(blocks * 512 * iters * 32 / t / 1e9, 1)
+    wide = {}
+    for ef in (2, 4):                                   # entries of 2 and 4 values, 1024 workgroups
+        t = _time(lambda: trim.trim_ceiling_lds_gather(1024, iters, 12345, fsink, entry_floats=ef), reps)
+        wide[ef] = round(1024 * 512 * iters * 8 / t / 1e9, 1)
     print(json.dumps({
         "stream_read_GBps_by_blocks": read, "stream_read_GBps": max(read.values()),
         "lds_Glookups_per_s_by_blocks": look, "lds_Glookups_per_s": max(look.values()),
         "lds_wave_instructions_per_s": round(max(look.values()) * 1e9 / 64, -8),
+        "lds_Glookups_per_s_entries_of_2_and_4_values": wide,
     }))
 
 

@@ -311,11 +311,24 @@ int trim_ceiling_stream_read(const void *buf, size_t bytes, int32_t blocks, uint
     return TRIM_OK;
 }
 
-int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, uint32_t seed, float *sink, void *stream) {
+int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, int32_t entry_floats, uint32_t seed,
+                            float *sink, void *stream) {
     if (!sink || iters < 1 || iters > (1 << 20)) return TRIM_INVALID_ARG;
     if (blocks < 1 || blocks > TRIM_CEILING_MAX_BLOCKS) return TRIM_INVALID_ARG;
-    hipLaunchKernelGGL(lds_gather_kernel, dim3(blocks), dim3(512), 32 * kC * 4,
-                       static_cast<hipStream_t>(stream), iters, seed, sink);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (entry_floats) {
+        case 1:
+            hipLaunchKernelGGL(lds_gather_kernel, dim3(blocks), dim3(512), 32 * kC * 4, st, iters, seed, sink);
+            break;
+        case 2:
+            hipLaunchKernelGGL(lds_gather_wide_kernel<2>, dim3(blocks), dim3(512), 8 * kC * 8, st, iters, seed, sink);
+            break;
+        case 4:
+            hipLaunchKernelGGL(lds_gather_wide_kernel<4>, dim3(blocks), dim3(512), 8 * kC * 16, st, iters, seed, sink);
+            break;
+        default:
+            return TRIM_INVALID_ARG;
+    }
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }

@@ -72,6 +72,42 @@ __global__ __launch_bounds__(512) void lds_gather_kernel(int iters, uint32_t see
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The same with entries of W binary32 values (W = 2, 4: what a table shared by W queries would
+// hold): 8 rows of 256 entries, every thread performs iters * 8 lookups of one whole entry and
+// adds its W values up.
+template <int W>
+__global__ __launch_bounds__(512) void lds_gather_wide_kernel(int iters, uint32_t seed,
+                                                              float *__restrict__ sink) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *tab = reinterpret_cast<float *>(smem);  // [8][256][W]
+    for (int i = threadIdx.x; i < 8 * kC * W; i += blockDim.x) tab[i] = (float)(i & 1023);
+    __syncthreads();
+    uint32_t h = seed ^ ((blockIdx.x * 512u + threadIdx.x) * 0x9e3779b9u);
+    h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+    uint32_t w0 = h;
+    h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+    uint32_t w1 = h;
+    float s = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t c = ((j < 4 ? w0 : w1) >> (8 * (j & 3))) & 255u;
+            const float *e = tab + (j * kC + c) * W;
+            if (W == 2) {
+                const float2 v = *reinterpret_cast<const float2 *>(e);
+                s += v.x; s += v.y;
+            } else {
+                const float4 v = *reinterpret_cast<const float4 *>(e);
+                s += v.x; s += v.y; s += v.z; s += v.w;
+            }
+        }
+        const uint32_t t = w0;
+        w0 = w1;
+        w1 = (t << 7 | t >> 25) ^ (uint32_t)it;
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // ---- scan head: {code bytes 0..7, landmark distance} of every vector as one 12-byte record ----
 __global__ void pack_scan_head_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ dlx,
                                       int64_t n, int M, uint32_t *__restrict__ head) {

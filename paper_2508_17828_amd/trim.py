@@ -93,7 +93,7 @@ def lib() -> C.CDLL:
                                       C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.trim_ceiling_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
-        L.trim_ceiling_lds_gather.argtypes = [C.c_int32, C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.trim_ceiling_lds_gather.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p]
         L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_search_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -375,7 +375,9 @@ def trim_ceiling_stream_read(buf: torch.Tensor, blocks: int, sink: torch.Tensor)
            "trim_ceiling_stream_read")
 
 
-def trim_ceiling_lds_gather(blocks: int, iters: int, seed: int, sink: torch.Tensor) -> None:
+def trim_ceiling_lds_gather(blocks: int, iters: int, seed: int, sink: torch.Tensor,
+                            entry_floats: int = 1) -> None:
     assert sink.numel() >= blocks * 512
-    _check(lib().trim_ceiling_lds_gather(blocks, iters, seed, _ptr(sink, torch.float32, "sink"),
-                                         _stream()), "trim_ceiling_lds_gather")
+    _check(lib().trim_ceiling_lds_gather(blocks, iters, entry_floats, seed,
+                                         _ptr(sink, torch.float32, "sink"), _stream()),
+           "trim_ceiling_lds_gather")

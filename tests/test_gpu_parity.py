@@ -384,6 +384,12 @@ def test_ceiling_aids_read_what_they_claim(T):
     T.trim_ceiling_lds_gather(64, 3, 99, c)
     assert torch.equal(a, c) and bool(torch.isfinite(a).all()) and float(a.min()) >= 0.0
     assert len(torch.unique(a)) > 1000            # lanes follow different code bytes
+    for ef in (2, 4):
+        T.trim_ceiling_lds_gather(64, 3, 99, a, entry_floats=ef)
+        T.trim_ceiling_lds_gather(64, 3, 99, c, entry_floats=ef)
+        assert torch.equal(a, c) and bool(torch.isfinite(a).all())
+    with pytest.raises(T.TrimError):
+        T.trim_ceiling_lds_gather(64, 3, 99, a, entry_floats=3)
     with pytest.raises(T.TrimError):
         T.trim_ceiling_lds_gather(0, 3, 99, a)
     with pytest.raises(T.TrimError):
