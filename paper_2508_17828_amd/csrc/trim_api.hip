@@ -38,7 +38,7 @@ struct Plan {
     size_t lds;
     uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
-    int span, wqcap, cruise, poss_cap, scap, bucket;
+    int span, wqcap, cruise, poss_cap, scap, rcap, bucket;
 };
 
 // Decide table phases, block size and LDS layout for a search launch.
@@ -73,7 +73,8 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     // cruise stretches: up to 61440 candidates (16-bit queue entries).  Their possibles are
     // counted per bucket of `bucket` candidates (a whole number of batches, at most 1024
     // buckets); wide result sets (more than 64) count per batch and keep to 1024 batches.
-    const bool small_k = !range && result_slots(k) == 1;
+    // (the stretches that end in a replay: see use_replay in the kernel)
+    const bool small_k = !range && (result_slots(k) == 1 || batch < kSmallBatch);
     int cruise = (small_k || 61440 < 1024 * (int64_t)batch) ? 61440 : 1024 * batch;
     cruise = cruise / batch * batch;
     if (range || cruise < 2 * span) cruise = 0;
@@ -109,6 +110,10 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 const int scap = cap > p ? cap : p;
                 size_t wq_bytes = wq_min;
                 if (wq_bytes < (size_t)(scap + p) * 4) wq_bytes = (size_t)(scap + p) * 4;
+                // a span that ends in a replay keeps up to min(scap, span) bounds behind the
+                // scap exact distances
+                const int span_poss = scap < span ? scap : span;
+                if (small_k && wq_bytes < (size_t)(scap + span_poss) * 4) wq_bytes = (size_t)(scap + span_poss) * 4;
                 wq_bytes = up16(wq_bytes);
                 size_t plb = up16((size_t)span * 4);             // bounds of a span / the possibles list
                 if (plb < (size_t)p * 8) plb = (size_t)p * 8;
@@ -137,6 +142,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 pl->cruise = p > 0 ? cruise : 0;
                 pl->poss_cap = p;
                 pl->scap = scap;
+                pl->rcap = (int)(wq_bytes / 4) - scap;
                 pl->bucket = bucket;
                 return true;
             }
@@ -217,7 +223,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
     a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
-    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap; a.scap = pl.scap; a.bucket = pl.bucket;
+    a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap; a.scap = pl.scap; a.rcap = pl.rcap; a.bucket = pl.bucket;
     a.small_addr = ix->n < (int64_t(1) << 24) && ix->n * (int64_t)ix->M < (int64_t(1) << 32) &&
                    ix->M < (1 << 24);
 }

@@ -76,6 +76,7 @@ struct SearchArgs {
     int32_t small_addr;  // n < 2^24 and n*M < 2^32: 24-bit multiply and 32-bit offsets suffice
     int32_t poss_cap;  // capacity of the possibles list
     int32_t scap;      // entries of spos[] and of sd2[] (>= survivor capacity and >= poss_cap)
+    int32_t rcap;      // entries behind sd2[scap] (bounds of a replay; >= poss_cap)
     int32_t bucket;    // cruise: possibles are counted per bucket of this many candidates (a multiple of batch)
 };
 
@@ -572,11 +573,17 @@ void search_kernel(const SearchArgs a) {
         TRIM_TICK(14);
         if (tid < kWave) {
             uint32_t *mrow = a.mask ? a.mask + (size_t)q * a.mask_words : nullptr;
-            const int n = a.batch < kSmallBatch
-                ? replay_batches<E, true>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
-                                          rd2, rid, ctl, a.k, lane)
-                : replay_batches<E, false>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
-                                           rd2, rid, ctl, a.k, lane);
+            int n;
+            if constexpr (E > 1) {   // wide result sets come here with small batches only
+                n = replay_batches<E, true>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
+                                            rd2, rid, ctl, a.k, lane);
+            } else {
+                n = a.batch < kSmallBatch
+                    ? replay_batches<E, true>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
+                                              rd2, rid, ctl, a.k, lane)
+                    : replay_batches<E, false>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
+                                               rd2, rid, ctl, a.k, lane);
+            }
             if (lane == 0) ctl->nexact += n;
         }
     };
@@ -629,7 +636,11 @@ void search_kernel(const SearchArgs a) {
     int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
     int ramp = MODE == kKnn ? a.first_batch : a.batch;  // next batch size while below a.batch
     // next span length while the spans of a small-batch search still grow (a multiple of batch)
-    int small_span = (MODE == kKnn && E == 1 && a.batch < kSmallBatch) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
+    int small_span = (MODE == kKnn && a.batch < kSmallBatch) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
+    // Stage B by replay: result sets up to 64 always; wider ones only when the batches are small
+    // (with long batches they refine batch by batch, under the freshest threshold: their rows
+    // are what bounds them, and a replay would fetch some in vain).
+    const bool use_replay = MODE == kKnn && (E == 1 || a.batch < kSmallBatch);
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
@@ -830,8 +841,8 @@ void search_kernel(const SearchArgs a) {
                 // one wave then replays the batch rule over them without any barrier.  A possible
                 // that turns out not to survive its batch has had its distance computed in vain;
                 // thresholds fall slowly this deep into the scan, so these are few.
-                if (E > 1) {
-                    // wide result sets: batch by batch, each with its own refine and merge
+                if (!use_replay) {
+                    // wide result sets, long batches: batch by batch, each with its own refine and merge
                     for (int b = 0; b < nb; ++b) {
                         if (cnt0[b] == 0) continue;  // same value for every thread
                         const float tau = ctl->tau;
@@ -1104,11 +1115,11 @@ void search_kernel(const SearchArgs a) {
         // Several batches in the span and a result set of at most 64: replay (see above), unless
         // the possibles do not fit its arrays (a loose threshold: then batch by batch as below).
         int np_span = -1;
-        if (MODE == kKnn && E == 1 && nb > 1) {
+        if (use_replay && nb > 1) {
             counts_to_offsets(nb);
             __syncthreads();
             np_span = ctl->nposs;
-            if (np_span <= a.scap) {
+            if (np_span <= a.scap && np_span <= a.rcap) {
                 replay_np = np_span;
                 advance = span;
                 if (np_span > 0) {
@@ -1157,6 +1168,9 @@ void search_kernel(const SearchArgs a) {
     }
 
     // ---- epilogue ----
+    // (the last stretch may have ended in a replay by the first wave alone: every thread that
+    // writes results must see its R)
+    __syncthreads();
     if (MODE == kKnn) {
         for (int i = tid; i < a.k; i += T) {
             const int32_t id = rid[i];

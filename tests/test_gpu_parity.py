@@ -202,7 +202,8 @@ def test_knn_c1(T, oracle, gamma, batch):
 
 @pytest.mark.parametrize("name,k,batch", [("c2s", 10, 1024), ("c2s", 1, 64), ("c2s", 70, 333),
                                           ("c5s", 10, 1024), ("c3s", 100, 4096),
-                                          ("c3s", 100, 512), ("c4s", 10, 2048)])
+                                          ("c3s", 100, 512), ("c4s", 10, 2048),
+                                          ("c3s", 100, 16), ("c2s", 70, 1), ("c2s", 300, 5)])
 @pytest.mark.parametrize("gamma", [0.0, 0.5, 0.8])
 def test_knn_shapes(T, oracle, name, k, batch, gamma):
     got, ref = check_knn(T, oracle, case(name), k, gamma, batch)

@@ -47,6 +47,9 @@ def draw_long(seed):
     if seed >= 6:      # small batches down to the vector-at-a-time rule: replay, buckets, short spans
         k = int(r.choice([1, 10, 37, 64]))
         batch = int(r.choice([1, 2, 3, 16, 48, 100]))
+    if seed >= 14:     # the same with result sets wider than 64 (more than one entry per lane)
+        k = int(r.choice([65, 100, 128, 200, 300, 1024]))
+        batch = int(r.choice([1, 3, 16, 100, 300]))
     first = int(r.choice([0, 32, batch]))
     first = min(first, batch)
     gamma = float(r.choice([0.0, 0.4, 0.8]))
@@ -56,7 +59,7 @@ def draw_long(seed):
     return w, k, batch, first, gamma
 
 
-@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(14)])
+@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(22)])
 def test_random_configuration(oracle, seed):
     import torch
     from paper_2508_17828_amd import trim as T
