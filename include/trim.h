@@ -85,7 +85,7 @@ typedef struct trim_candidates {
 
 /* Optional per-query counters (device, each [nq] or NULL): candidates scanned, and survivors
  * of the filter, i.e. the candidates whose exact distance the scan of Section 4.2 calls for.
- * Pruning ratio = 1 - n_exact/n_scanned.  (kNN with k <= 64 or batch < 512 computes the exact distance of a
+ * Pruning ratio = 1 - n_exact/n_scanned.  (kNN computes the exact distance of a
  * few more candidates than it counts: those that passed the threshold in force when their
  * stretch of the scan began but not the lower one of their own batch.  They change neither
  * the results nor the survivor mask.) */

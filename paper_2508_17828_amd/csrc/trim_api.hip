@@ -70,16 +70,13 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
     const int span = nbatch * batch;
     if (span > 65535) return false;
-    // cruise stretches: up to 61440 candidates (16-bit queue entries).  Their possibles are
-    // counted per bucket of `bucket` candidates (a whole number of batches, at most 1024
-    // buckets); wide result sets (more than 64) count per batch and keep to 1024 batches.
-    // (the stretches that end in a replay: see use_replay in the kernel)
-    const bool small_k = !range && (result_slots(k) == 1 || batch < kSmallBatch);
-    int cruise = (small_k || 61440 < 1024 * (int64_t)batch) ? 61440 : 1024 * batch;
-    cruise = cruise / batch * batch;
+    // cruise stretches (kNN): up to 61440 candidates (16-bit queue entries).  Their possibles
+    // are counted per bucket of `bucket` candidates (a whole number of batches, at most 1024
+    // buckets).
+    int cruise = 61440 / batch * batch;
     if (range || cruise < 2 * span) cruise = 0;
     int bucket = batch;
-    if (small_k && cruise / batch > 1024) bucket = batch * (((cruise + 1023) / 1024 + batch - 1) / batch);
+    if (cruise / batch > 1024) bucket = batch * (((cruise + 1023) / 1024 + batch - 1) / batch);
     const int nbucket = cruise > 0 ? (cruise + bucket - 1) / bucket : 0;
     const int ncnt = nbucket > nbatch ? nbucket : nbatch;
     for (int P = 1; P <= M / 4; ++P) {
@@ -113,7 +110,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 // a span that ends in a replay keeps up to min(scap, span) bounds behind the
                 // scap exact distances
                 const int span_poss = scap < span ? scap : span;
-                if (small_k && wq_bytes < (size_t)(scap + span_poss) * 4) wq_bytes = (size_t)(scap + span_poss) * 4;
+                if (!range && wq_bytes < (size_t)(scap + span_poss) * 4) wq_bytes = (size_t)(scap + span_poss) * 4;
                 wq_bytes = up16(wq_bytes);
                 size_t plb = up16((size_t)span * 4);             // bounds of a span / the possibles list
                 if (plb < (size_t)p * 8) plb = (size_t)p * 8;

@@ -574,7 +574,7 @@ void search_kernel(const SearchArgs a) {
         if (tid < kWave) {
             uint32_t *mrow = a.mask ? a.mask + (size_t)q * a.mask_words : nullptr;
             int n;
-            if constexpr (E > 1) {   // wide result sets come here with small batches only
+            if constexpr (E > 1) {
                 n = replay_batches<E, true>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
                                             rd2, rid, ctl, a.k, lane);
             } else {
@@ -637,10 +637,6 @@ void search_kernel(const SearchArgs a) {
     int ramp = MODE == kKnn ? a.first_batch : a.batch;  // next batch size while below a.batch
     // next span length while the spans of a small-batch search still grow (a multiple of batch)
     int small_span = (MODE == kKnn && a.batch < kSmallBatch) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
-    // Stage B by replay: result sets up to 64 always; wider ones only when the batches are small
-    // (with long batches they refine batch by batch, under the freshest threshold: their rows
-    // are what bounds them, and a replay would fetch some in vain).
-    const bool use_replay = MODE == kKnn && (E == 1 || a.batch < kSmallBatch);
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
@@ -841,29 +837,6 @@ void search_kernel(const SearchArgs a) {
                 // one wave then replays the batch rule over them without any barrier.  A possible
                 // that turns out not to survive its batch has had its distance computed in vain;
                 // thresholds fall slowly this deep into the scan, so these are few.
-                if (!use_replay) {
-                    // wide result sets, long batches: batch by batch, each with its own refine and merge
-                    for (int b = 0; b < nb; ++b) {
-                        if (cnt0[b] == 0) continue;  // same value for every thread
-                        const float tau = ctl->tau;
-                        for (int i0 = 0; i0 < np; i0 += T) {
-                            const int i = i0 + tid;
-                            int cl = 0;
-                            bool live = false;
-                            if (i < np) {
-                                cl = poss_cl[i];
-                                live = cl / a.batch == b && poss_g[i] <= tau;
-                            }
-                            append(live, c0 + cl);
-                        }
-                        __syncthreads();
-                        const int ns = ctl->nsurv;
-                        __syncthreads();
-                        if (ns > 0) refine_and_select(ns);
-                    }
-                    c0 += S;
-                    continue;
-                }
                 replay_np = np;
                 advance = S;
                 if (np > 0) {
@@ -1115,7 +1088,7 @@ void search_kernel(const SearchArgs a) {
         // Several batches in the span and a result set of at most 64: replay (see above), unless
         // the possibles do not fit its arrays (a loose threshold: then batch by batch as below).
         int np_span = -1;
-        if (use_replay && nb > 1) {
+        if (MODE == kKnn && nb > 1) {
             counts_to_offsets(nb);
             __syncthreads();
             np_span = ctl->nposs;
