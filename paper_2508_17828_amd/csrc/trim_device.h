@@ -211,7 +211,9 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) {
 // tab_base is the LDS byte address of the table row of the first of these subspaces.
 // The reads of 8 subspaces are issued together, ahead of their additions, so that their LDS
 // latencies overlap; the additions stay in subspace order.
-template <int VEC>
+// MARK: a sum stopped half way is returned as +inf (for callers whose later tests use larger
+// thresholds than the half-way one: see the remaining-minimum thresholds of the cruise).
+template <int VEC, bool MARK = false>
 __device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const uint32_t (&w)[VEC],
                                             float thr) {
     constexpr int kRow = kC * 4;  // bytes per table row
@@ -235,7 +237,7 @@ __device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const ui
         for (int i = 0; i < 8; ++i)
             if (v0 + i / 4 < VEC) s = s + t[i];
         // early abandon every 8 subspaces (see abandon_threshold)
-        if (v0 + 2 < VEC && s > thr) return s;
+        if (v0 + 2 < VEC && s > thr) return MARK ? __builtin_inff() : s;
     }
     return s;
 }
@@ -295,11 +297,18 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[VEC], const uint8_t *__
 // sqrt -> subtract -> square loses < 4 ulp (2.4e-7 relative); the threshold is inflated by
 // 1e-5.  tau = +inf gives +inf (never abandons).
 //
-// Per threshold tau:   st = abandon_scale(tau) = c * max(sqrt(tau), 1e-15), c = 1.000005
-// Per candidate:       thr = (c*b + st)^2 = c^2 (b + max(sqrt(tau),1e-15))^2 >= 1.00001 (b + sqrt(tau))^2
+// Per threshold tau:   st = abandon_scale(tau) = c * max(sqrt(tau), 1e-15), c = 1.000025
+// Per candidate:       thr = (c*b + st)^2 = c^2 (b + max(sqrt(tau),1e-15))^2 >= 1.00005 (b + sqrt(tau))^2
 // (the floor keeps thr >= 1e-30, inside the normal range, so the margin argument holds for
 // arbitrarily small tau as well).
-constexpr float kAbandonC = 1.000005f;
+//
+// The cruise tests a running sum s_j (subspaces 0..j-1) against thr - rest_j, where rest_j is
+// the binary32 sum over the remaining subspaces of their smallest table entry: the finished
+// sum is at least s_j + (true rest) up to the rounding of at most M additions on either side,
+//   s_full >= (s_j + rest_j) (1 - 2 M u),  u = 2^-24,  2 M u <= 3.1e-5 for M <= 256,
+// and the subtraction thr - rest_j errs by at most u thr; the 5e-5 of the margin cover the
+// 1e-5 of the first argument, these 3.1e-5 and that u.
+constexpr float kAbandonC = 1.000025f;
 __device__ __forceinline__ float abandon_scale(float tau) {
     return kAbandonC * fmaxf(sqrt_rn(tau), 1e-15f);
 }

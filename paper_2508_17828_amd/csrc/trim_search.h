@@ -69,7 +69,7 @@ struct SearchArgs {
     int64_t rmask_words;
     int32_t *chunk_counts;   // [nq][nsplit]
     // LDS carve-up (byte offsets)
-    uint32_t off_q, off_segp, off_segd, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_q, off_segp, off_segd, off_rest, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int32_t wqcap;     // entries per wave in each of the two work-queue arrays
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
@@ -361,6 +361,7 @@ void search_kernel(const SearchArgs a) {
     float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
     int *segp = reinterpret_cast<int *>(smem + a.off_segp);   // [nseg+1] prefix of lengths
     int *segd = reinterpret_cast<int *>(smem + a.off_segd);   // [nseg] start - prefix
+    float *restv = reinterpret_cast<float *>(smem + a.off_rest);  // [M/4+1] remaining minima (cruise)
     int32_t *spos = reinterpret_cast<int32_t *>(smem + a.off_spos);  // survivor position -> id
     float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // exact d2 (shares the queue area)
     int32_t *sidx = reinterpret_cast<int32_t *>(smem + a.off_sidx);  // range: scan-order number
@@ -433,6 +434,32 @@ void search_kernel(const SearchArgs a) {
     }
     if (a.P == 1) fill_table(tab, a, q_lds, q, 0, a.M);
     __syncthreads();
+    // restv[i] = sum over the subspaces j >= 4i of the smallest entry of table row j: what the
+    // subspaces still to come add to a running sum at the very least (see abandon_threshold).
+    // Here: the sums of four rows' minima, one wave per group; turned into suffix sums below.
+    if (MODE == kKnn && a.P == 1) {
+        for (int i = tid >> 6; i < a.M / 4; i += T >> 6) {
+            float gsum = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float4 v = *reinterpret_cast<const float4 *>(tab + (size_t)(4 * i + r) * kC + 4 * lane);
+                float m = __builtin_fminf(__builtin_fminf(v.x, v.y), __builtin_fminf(v.z, v.w));
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) m = __builtin_fminf(m, __shfl_xor(m, off));
+                gsum = gsum + m;
+            }
+            if (lane == 0) restv[i] = gsum;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float acc = 0.0f;
+        restv[a.Mp / 4] = 0.0f;
+        for (int i = a.Mp / 4 - 1; i >= 0; --i) {
+            acc = (MODE == kKnn && a.P == 1) ? acc + restv[i] : 0.0f;
+            restv[i] = acc;
+        }
+    }   // (read after the next barrier: the seed's, or the one at the top of the main loop)
 
     const int total = ctl->total;
     int c_begin = 0, c_end = total;
@@ -693,17 +720,21 @@ void search_kernel(const SearchArgs a) {
                     if (lane < d_n) {
                         const float thr = abandon_threshold(d_b, sqrt_tau0);
                         const CodeRow cr = code_row<kTiledOk>(a, d_pos);
-                        float sum = gather_add<DV>(0.0f, kTabLds, d_w0, thr);
+                        // every test of a running sum is against the threshold less what the
+                        // subspaces still to come add at the least (restv; a half-way stop inside
+                        // a 16-subspace piece comes back as +inf)
+                        float sum = gather_add<DV, true>(0.0f, kTabLds, d_w0, thr - restv[DV == 4 ? 2 : 0]);
                         int j = 4 * DV;
-                        if (two_chunks && !(sum > thr)) {
-                            sum = gather_add<DV>(sum, kTabLds + 4 * DV * (kC * 4), d_w1, thr);
+                        if (two_chunks && !(sum > thr - restv[j >> 2])) {
+                            sum = gather_add<DV, true>(sum, kTabLds + 4 * DV * (kC * 4), d_w1,
+                                                       thr - restv[DV == 4 ? 6 : 0]);
                             j = 8 * DV;
                         }
-                        while (j < a.M && !(sum > thr)) {  // widest aligned load that fits
+                        while (j < a.M && !(sum > thr - restv[j >> 2])) {  // widest aligned load that fits
                             if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
                                 uint32_t w[4];
                                 load_codes<4>(w, cr.at(j));
-                                sum = gather_add<4>(sum, kTabLds + j * (kC * 4), w, thr);
+                                sum = gather_add<4, true>(sum, kTabLds + j * (kC * 4), w, thr - restv[(j >> 2) + 2]);
                                 j += 16;
                             } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= a.M) {
                                 uint32_t w[2];
@@ -717,7 +748,7 @@ void search_kernel(const SearchArgs a) {
                                 j += 4;
                             }
                         }
-                        if (!(sum > thr)) {
+                        if (!(sum > thr - restv[j >> 2])) {
                             const float g = plb_from_s(sum, d_b, a.two_gamma);
                             if (g <= tau0) {
                                 const int at = atomicAdd(&ctl->nposs, 1);
@@ -733,6 +764,9 @@ void search_kernel(const SearchArgs a) {
                 int s_seg = 0;
                 int s_end = __builtin_amdgcn_readfirstlane(segp[1]);
                 int s_delta = __builtin_amdgcn_readfirstlane(segd[0]);
+                // what subspaces H0.. add at the least, in a scalar register
+                const float rest_h0 = __builtin_bit_cast(
+                    float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, restv[H0 / 4])));
                 for (int blk = wave; blk < nblk; blk += nwaves) {
                     // this block's loads fly while the previous drain is finished; the next
                     // drain's loads fly while this block is bounded
@@ -807,7 +841,7 @@ void search_kernel(const SearchArgs a) {
                         }
                         const float sum = sums[u];
                         const int cl = cb + u * kWave + lane;
-                        const float thr = abandon_threshold(bq[u], sqrt_tau0);
+                        const float thr = abandon_threshold(bq[u], sqrt_tau0) - rest_h0;
                         // lanes beyond the stretch carry a NaN landmark distance (issue_loads):
                         // their threshold is NaN and the comparison is false
                         const bool alive = sum <= thr;
