@@ -38,6 +38,8 @@ def parse():
                     help="CPU time budget for timing the oracle (0 = skip)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-order", action="store_true", help="do not sort queries by first probed list")
+    ap.add_argument("--no-list-bounds", action="store_true",
+                    help="do not give the search the per-list summaries (no list-level pruning)")
     return ap.parse_args()
 
 
@@ -149,7 +151,7 @@ def main():
     batch = args.batch or w.batch
     first_batch = min(batch, w.first_batch if args.first_batch is None else args.first_batch)
     t0 = time.time()
-    bw = index_setup.build_workload(w)
+    bw = index_setup.build_workload(w, list_bounds=not args.no_list_bounds)
     ix, queries = bw.index, bw.queries
     torch.cuda.synchronize()
     setup_s = time.time() - t0
@@ -303,6 +305,7 @@ def main():
                    "gamma": gamma, "batch": batch, "first_batch": first_batch, "recall_at_k": chosen["recall"],
                    "recall_truth": f"exact kNN over all n for the first {nt} queries",
                    "pruning_ratio": chosen["pruning_ratio"],
+                   "list_level_pruning": ix.list_bounds is not None,
                    "timed": "probe selection + query ordering + fused table/scan/refine/select, inputs in HBM",
                    "setup_s": round(setup_s, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,

@@ -81,6 +81,11 @@ typedef struct trim_candidates {
     int64_t max_candidates;      /* host value: upper bound on one query's candidate count
                                     (e.g. the sum of the nprobe longest lists); used to size
                                     masks; a query with more candidates is cut at this bound */
+    const void *list_bounds;     /* device, trim_list_bounds_bytes(nlist, M) bytes, or NULL: see
+                                    trim_pack_list_bounds.  With it trim_search_knn passes over
+                                    lists, and stops table sums early, where the codes that
+                                    occur in a list show that nothing in it can survive;
+                                    results, masks and counters are the same with and without */
 } trim_candidates;
 
 /* Optional per-query counters (device, each [nq] or NULL): candidates scanned, and survivors
@@ -266,6 +271,23 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
  */
 int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t nlist,
                      int32_t *order_out, void *stream);
+
+/*
+ * Per-list summaries for list-level pruning in trim_search_knn (an exact shortcut, not part of
+ * the paper's method; it tightens the lower bound of Section 3 with what the index knows about
+ * a list).  For every inverted list and every subspace j the set of PQ codes that occur in
+ * the list is recorded (up to 64; a larger set is marked as "any code"), and the largest
+ * landmark distance of the list.  For a query with table T, every vector of the list has
+ * T[j][code_j] >= min over the recorded codes c of T[j][c]; the sum of these minima over
+ * the subspaces still to come bounds the rest of a running table sum from below, and their sum
+ * over all subspaces, if it exceeds (max landmark distance + sqrt(tau))^2, shows that Equation 3
+ * is above tau for the whole list at every gamma >= 0.
+ * list_offsets [nlist+1] device; the index needs codes and dlx.  out: device,
+ * trim_list_bounds_bytes(nlist, index->M) bytes, 16-byte aligned.
+ */
+size_t trim_list_bounds_bytes(int32_t nlist, int32_t M);
+int trim_pack_list_bounds(const trim_index_view *index, const int64_t *list_offsets, int32_t nlist,
+                          void *out, void *stream);
 
 /*
  * Measurement aids (no counterpart in the paper): the two machine ceilings the scan of

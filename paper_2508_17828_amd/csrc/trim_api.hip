@@ -36,7 +36,7 @@ struct Plan {
     int threads;
     int P, Mp, vec;
     size_t lds;
-    uint32_t off_q, off_segp, off_segd, off_rest, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_q, off_segp, off_segd, off_rest, off_rowmin, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int span, wqcap, cruise, poss_cap, scap, rcap, bucket;
 };
@@ -94,6 +94,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
             if (can_cruise && wq_min < (size_t)nwaves * kRing * 4) wq_min = (size_t)nwaves * kRing * 4;
             const size_t rest = tab + up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) +
                                 up16((size_t)nsegs * 4) + up16((size_t)(Mp / 4 + 1) * 4) +
+                                up16((size_t)Mp * 4) + up16((size_t)nsegs * 20) +
                                 (range ? up16((size_t)cap * 4) : 0) +
                                 up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
                                 up16((size_t)ncnt * 4);
@@ -125,6 +126,8 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
                 pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
                 pl->off_rest = (uint32_t)off; off += up16((size_t)(Mp / 4 + 1) * 4);
+                pl->off_rowmin = (uint32_t)off; off += up16((size_t)Mp * 4);
+                pl->off_seglb = (uint32_t)off; off += up16((size_t)nsegs * 20);
                 pl->off_spos = (uint32_t)off; off += up16((size_t)scap * 4);
                 pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
                 pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
@@ -195,6 +198,7 @@ int check_cand(const trim_candidates *c) {
     if (!c) return TRIM_OK;
     if (c->nlist <= 0 || c->nprobe <= 0 || c->nprobe > TRIM_MAX_NPROBE) return TRIM_INVALID_ARG;
     if (!c->list_offsets || !c->probes) return TRIM_INVALID_ARG;
+    if (c->list_bounds && !aligned16(c->list_bounds)) return TRIM_INVALID_ARG;
     return TRIM_OK;
 }
 
@@ -219,6 +223,8 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.n_exact = stats ? stats->n_exact : nullptr;
     a.mask = mask; a.mask_words = mask_words;
     a.off_q = pl.off_q; a.off_segp = pl.off_segp; a.off_segd = pl.off_segd; a.off_rest = pl.off_rest;
+    a.off_rowmin = pl.off_rowmin; a.off_seglb = pl.off_seglb;
+    a.list_bounds = cand ? static_cast<const uint8_t *>(cand->list_bounds) : nullptr;
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;
     a.off_plb = pl.off_plb; a.off_cnt = pl.off_cnt; a.span = pl.span;
@@ -301,6 +307,23 @@ int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks,
         hipLaunchKernelGGL(encode_kernel<8>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
     else
         hipLaunchKernelGGL(encode_kernel<0>, grid, block, lds, st, base, n, d, codebooks, M, dsub, codes_out, dlx_out);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+size_t trim_list_bounds_bytes(int32_t nlist, int32_t M) {
+    if (nlist <= 0 || M <= 0) return 0;
+    return (size_t)nlist * list_record_bytes(M);
+}
+
+int trim_pack_list_bounds(const trim_index_view *index, const int64_t *list_offsets, int32_t nlist,
+                          void *out, void *stream) {
+    const int rc = check_index(index);
+    if (rc != TRIM_OK) return rc;
+    if (nlist <= 0 || !list_offsets || !out || !aligned16(out)) return TRIM_INVALID_ARG;
+    hipLaunchKernelGGL(list_bounds_kernel, dim3((unsigned)nlist), dim3(256), (size_t)index->M * 32,
+                       static_cast<hipStream_t>(stream), index->codes, index->dlx, index->n, index->M,
+                       list_offsets, static_cast<uint8_t *>(out));
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }

@@ -108,6 +108,65 @@ __global__ __launch_bounds__(512) void lds_gather_wide_kernel(int iters, uint32_
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// ---- per-list summaries for list-level pruning (record layout: list_record_bytes) ----
+// One workgroup per inverted list: a presence bitmap of 256 bits per subspace is filled from
+// the list's codes, then one wave per subspace writes the set codes in ascending order.
+__global__ __launch_bounds__(256) void list_bounds_kernel(const uint8_t *__restrict__ codes,
+                                                          const float *__restrict__ dlx, int64_t n,
+                                                          int M, const int64_t *__restrict__ list_offsets,
+                                                          uint8_t *__restrict__ out) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint32_t *bits = reinterpret_cast<uint32_t *>(smem);  // [M][8]
+    __shared__ float red[256];
+    const int l = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    uint8_t *rec = out + (size_t)l * list_record_bytes(M);
+    for (int i = tid; i < M * 8; i += blockDim.x) bits[i] = 0;
+    __syncthreads();
+    int64_t lo = list_offsets[l], hi = list_offsets[l + 1];
+    lo = lo < 0 ? 0 : (lo > n ? n : lo);
+    hi = hi < lo ? lo : (hi > n ? n : hi);
+    float bmax = 0.0f;
+    for (int64_t x = lo + tid; x < hi; x += blockDim.x) {
+        for (int j = 0; j < M; ++j) {
+            const uint32_t c = codes[(size_t)x * M + j];
+            atomicOr(&bits[j * 8 + (c >> 5)], 1u << (c & 31));
+        }
+        bmax = fmaxf(bmax, dlx[x]);
+    }
+    red[tid] = bmax;
+    __syncthreads();
+    for (int h = blockDim.x >> 1; h > 0; h >>= 1) {
+        if (tid < h) red[tid] = fmaxf(red[tid], red[tid + h]);
+        __syncthreads();
+    }
+    if (tid == 0) *reinterpret_cast<float *>(rec + list_record_bmax_offset(M)) = red[0];
+    for (int j = tid >> 6; j < M; j += blockDim.x >> 6) {   // one wave per subspace
+        const uint32_t nib = (bits[j * 8 + (lane >> 3)] >> ((lane & 7) * 4)) & 15u;  // codes 4*lane..4*lane+3
+        const int cnt = __popc(nib);
+        int incl = cnt;                                  // inclusive prefix over the lanes
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        const int total = __shfl(incl, 63);
+        uint8_t *row = rec + (size_t)j * kSetCap;
+        if (total == 0 || total > kSetCap) {
+            row[lane] = 0;
+            if (lane == 0) rec[(size_t)M * kSetCap + j] = total == 0 ? 0 : (uint8_t)kSetAny;
+            continue;
+        }
+        const unsigned long long have = __ballot(nib != 0);
+        const int fl = __ffsll((long long)have) - 1;
+        const uint32_t fn = (uint32_t)__shfl((int)nib, fl);
+        const uint8_t first = (uint8_t)(4 * fl + (__ffs((int)fn) - 1));
+        if (lane >= total) row[lane] = first;            // padding
+        int at = incl - cnt;
+        for (int b = 0; b < 4; ++b)
+            if ((nib >> b) & 1u) row[at++] = (uint8_t)(4 * lane + b);
+        if (lane == 0) rec[(size_t)M * kSetCap + j] = (uint8_t)total;
+    }
+}
+
 // ---- scan head: {code bytes 0..7, landmark distance} of every vector as one 12-byte record ----
 __global__ void pack_scan_head_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ dlx,
                                       int64_t n, int M, uint32_t *__restrict__ head) {

@@ -288,6 +288,16 @@ __device__ __forceinline__ void load_codes(uint32_t (&w)[VEC], const uint8_t *__
     }
 }
 
+// Per-list summary record (list-level pruning): for each subspace j a row of kSetCap code bytes
+// (the distinct codes that occur in the list, ascending, padded with the first one), then one
+// count byte per subspace (0: empty list, kSetAny: more than kSetCap distinct codes, "any
+// code"), then, 4-byte aligned, the list's largest landmark distance; records are 16-byte
+// multiples.
+constexpr int kSetCap = 64;
+constexpr int kSetAny = 255;
+__host__ __device__ inline size_t list_record_bmax_offset(int M) { return ((size_t)M * (kSetCap + 1) + 3) & ~size_t(3); }
+__host__ __device__ inline size_t list_record_bytes(int M) { return (list_record_bmax_offset(M) + 4 + 15) & ~size_t(15); }
+
 // Early-abandon threshold on the running table sum (an exact shortcut, not part of the
 // paper's method).  Table entries are >= 0, so the binary32 running sum never decreases, and
 // for a = sqrt(s) >= b the computed bound of Equation 3 is >= (a - b)^2.  Hence, once

@@ -46,6 +46,7 @@ struct SearchArgs {
     // candidate structure (nseg == 0: all n positions)
     const int64_t *list_offsets;
     const int32_t *probes;
+    const uint8_t *list_bounds;  // per-list summaries (list_record_bytes(M) each) or null
     int32_t nlist, nseg;
     int32_t max_cand;  // per-query cut
     // table phases: the M subspaces are handled Mp at a time (P = M / Mp passes per batch)
@@ -69,7 +70,7 @@ struct SearchArgs {
     int64_t rmask_words;
     int32_t *chunk_counts;   // [nq][nsplit]
     // LDS carve-up (byte offsets)
-    uint32_t off_q, off_segp, off_segd, off_rest, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_q, off_segp, off_segd, off_rest, off_rowmin, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int32_t wqcap;     // entries per wave in each of the two work-queue arrays
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
@@ -362,6 +363,12 @@ void search_kernel(const SearchArgs a) {
     int *segp = reinterpret_cast<int *>(smem + a.off_segp);   // [nseg+1] prefix of lengths
     int *segd = reinterpret_cast<int *>(smem + a.off_segd);   // [nseg] start - prefix
     float *restv = reinterpret_cast<float *>(smem + a.off_rest);  // [M/4+1] remaining minima (cruise)
+    float *rowmin = reinterpret_cast<float *>(smem + a.off_rowmin);  // [M] smallest entry of each table row
+    float *seglb = reinterpret_cast<float *>(smem + a.off_seglb);    // [nseg] list-level lower bound of the table sum
+    float *segrest = seglb + (a.nseg > 0 ? a.nseg : 1);             // [nseg] the same over subspaces H0..
+    float *segbm = segrest + (a.nseg > 0 ? a.nseg : 1);             // [nseg] largest landmark distance of the list
+    int *segl = reinterpret_cast<int *>(segbm + (a.nseg > 0 ? a.nseg : 1));  // [nseg] list id (-1: none)
+    float *segstate = reinterpret_cast<float *>(segl + (a.nseg > 0 ? a.nseg : 1));  // [nseg] per stretch, see the cruise
     int32_t *spos = reinterpret_cast<int32_t *>(smem + a.off_spos);  // survivor position -> id
     float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // exact d2 (shares the queue area)
     int32_t *sidx = reinterpret_cast<int32_t *>(smem + a.off_sidx);  // range: scan-order number
@@ -414,6 +421,7 @@ void search_kernel(const SearchArgs a) {
         }
         segd[p] = (int)s;            // start for now
         segp[p + 1] = (int)(e - s);  // length for now
+        segl[p] = (a.nseg > 0 && e > s) ? a.probes[(size_t)q * a.nseg + p] : -1;
     }
     __syncthreads();
     if (tid == 0) {
@@ -447,6 +455,7 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) m = __builtin_fminf(m, __shfl_xor(m, off));
                 gsum = gsum + m;
+                if (lane == 0) rowmin[4 * i + r] = m;
             }
             if (lane == 0) restv[i] = gsum;
         }
@@ -460,6 +469,76 @@ void search_kernel(const SearchArgs a) {
             restv[i] = acc;
         }
     }   // (read after the next barrier: the seed's, or the one at the top of the main loop)
+    // List-level bounds (kNN over inverted lists whose summaries the caller supplies): for the
+    // list of segment p, seglb[p] = sum over all subspaces j of the smallest T[j][c] over the
+    // codes c that occur in the list, a lower bound of every table sum of the list; segrest[p]
+    // = the same over the subspaces from H0 on; segbm[p] = the list's largest landmark distance.
+    // One wave per segment; a lane takes 16 recorded codes of one subspace (4 lanes per
+    // subspace, 16 subspaces per step).
+    if (MODE == kKnn && a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr) {
+        constexpr int kH0 = VEC >= 2 ? 8 : 4;
+        const size_t rec_bytes = list_record_bytes(a.M);
+        // two segments per round and wave, 32 subspaces per step: all the loads of a step are
+        // issued before the first is used
+        for (int p0 = 2 * (tid >> 6); p0 < nseg; p0 += 2 * (T >> 6)) {
+            const uint8_t *rec[2];
+            float bm[2], lb[2] = {0.0f, 0.0f}, rest[2] = {0.0f, 0.0f};
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int l = p0 + t < nseg ? segl[p0 + t] : -1;     // same for the wave
+                rec[t] = (l >= 0 && l < a.nlist) ? a.list_bounds + (size_t)l * rec_bytes : nullptr;
+                bm[t] = rec[t] ? *reinterpret_cast<const float *>(rec[t] + list_record_bmax_offset(a.M))
+                               : __builtin_inff();
+            }
+            for (int j0 = 0; j0 < a.M; j0 += 32) {
+                uint4 cw[2][2];
+                int cnt[2][2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int j = j0 + 16 * g + (lane >> 2);
+                        cw[t][g] = make_uint4(0, 0, 0, 0);
+                        cnt[t][g] = 0;
+                        if (rec[t] && j < a.M) {
+                            cw[t][g] = *reinterpret_cast<const uint4 *>(rec[t] + (size_t)j * kSetCap + (lane & 3) * 16);
+                            cnt[t][g] = rec[t][(size_t)a.M * kSetCap + j];
+                        }
+                    }
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const int j = j0 + 16 * g + (lane >> 2);
+                        const bool on = rec[t] && j < a.M;
+                        const float *row = tab + (size_t)(on ? j : 0) * kC;
+                        const uint32_t w4[4] = {cw[t][g].x, cw[t][g].y, cw[t][g].z, cw[t][g].w};
+                        float m = __builtin_inff();
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+#pragma unroll
+                            for (int b = 0; b < 4; ++b)
+                                m = __builtin_fminf(m, row[(w4[v] >> (8 * b)) & 255u]);
+                        m = __builtin_fminf(m, __shfl_xor(m, 1));
+                        m = __builtin_fminf(m, __shfl_xor(m, 2));
+                        if (on && (cnt[t][g] == 0 || cnt[t][g] == kSetAny)) m = rowmin[j];
+                        if (on && (lane & 3) == 0) {
+                            lb[t] = lb[t] + m;
+                            if (j >= kH0) rest[t] = rest[t] + m;
+                        }
+                    }
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int off = 32; off >= 4; off >>= 1) {
+                    lb[t] = lb[t] + __shfl_xor(lb[t], off);
+                    rest[t] = rest[t] + __shfl_xor(rest[t], off);
+                }
+                if (lane == 0 && p0 + t < nseg) { seglb[p0 + t] = lb[t]; segrest[p0 + t] = rest[t]; segbm[p0 + t] = bm[t]; }
+            }
+        }
+    }
 
     const int total = ctl->total;
     int c_begin = 0, c_end = total;
@@ -688,6 +767,9 @@ void search_kernel(const SearchArgs a) {
             const int nb = (S + a.bucket - 1) / a.bucket;   // buckets (= batches unless they are very small)
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
             if (tid == 0) ctl->nposs = 0;
+            if (a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr)
+                for (int p = tid; p < nseg; p += T)
+                    segstate[p] = seglb[p] > abandon_threshold(segbm[p], sqrt_tau0) ? __builtin_inff() : segrest[p];
             __syncthreads();
             {
                 uint32_t *ring = reinterpret_cast<uint32_t *>(wq) + (size_t)wave * kRing;  // (segment << 16) | number
@@ -767,6 +849,10 @@ void search_kernel(const SearchArgs a) {
                 // what subspaces H0.. add at the least, in a scalar register
                 const float rest_h0 = __builtin_bit_cast(
                     float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, restv[H0 / 4])));
+                // segstate[p] (set at the start of the stretch): what subspaces H0.. add at the
+                // least for the list of segment p, or +inf if the whole list is passed over
+                const bool have_lb = a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr;
+                constexpr int kInfBits = 0x7f800000;
                 for (int blk = wave; blk < nblk; blk += nwaves) {
                     // this block's loads fly while the previous drain is finished; the next
                     // drain's loads fly while this block is bounded
@@ -776,6 +862,22 @@ void search_kernel(const SearchArgs a) {
                     const int cb = blk * U * kWave;
                     // same for the whole wave
                     const bool full = H0 == 8 && a.head && a.small_addr && cb + U * kWave <= S;
+                    // A block that lies inside one list takes that list's remaining minimum, or is
+                    // passed over with the list; any other block takes the global minimum.
+                    float blk_rest = rest_h0;
+                    if (full && have_lb) {
+                        const int cf = c0 + cb;
+                        while (cf >= s_end) {                    // cf < total: terminates
+                            ++s_seg;
+                            s_end = __builtin_amdgcn_readfirstlane(segp[s_seg + 1]);
+                            s_delta = __builtin_amdgcn_readfirstlane(segd[s_seg]);
+                        }
+                        if (cf + U * kWave <= s_end) {
+                            const int st_bits = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, segstate[s_seg]));
+                            if (st_bits == kInfBits) continue;   // same for the whole wave
+                            blk_rest = __builtin_bit_cast(float, st_bits);
+                        }
+                    }
                     if (full) {
                         // whole block in range, 32-bit byte offsets from uniform bases; the
                         // segment of 64 consecutive candidates is found with scalar arithmetic
@@ -841,7 +943,7 @@ void search_kernel(const SearchArgs a) {
                         }
                         const float sum = sums[u];
                         const int cl = cb + u * kWave + lane;
-                        const float thr = abandon_threshold(bq[u], sqrt_tau0) - rest_h0;
+                        const float thr = abandon_threshold(bq[u], sqrt_tau0) - blk_rest;
                         // lanes beyond the stretch carry a NaN landmark distance (issue_loads):
                         // their threshold is NaN and the comparison is false
                         const bool alive = sum <= thr;

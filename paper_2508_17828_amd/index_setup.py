@@ -20,7 +20,7 @@ class BuiltWorkload:
 
 
 def build_workload(w: synth.Workload, device: str = "cuda:0", pq_train: int = 65536,
-                   ivf_train_per_list: int = 64) -> BuiltWorkload:
+                   ivf_train_per_list: int = 64, list_bounds: bool = True) -> BuiltWorkload:
     """Generate the synthetic base set and queries, train centroids, store the base set in
     list order and encode it.  Returns device-resident tensors."""
     base_h = synth.base_vectors(w)
@@ -53,6 +53,8 @@ def build_workload(w: synth.Workload, device: str = "cuda:0", pq_train: int = 65
     tiled = trim.trim_pack_codes_tiled(codes) if codes.shape[1] >= 64 and codes.shape[1] % 16 == 0 else None
     index = trim.Index(base, codes, dlx, codebooks, ids=ids, list_offsets=list_offsets,
                        max_list_len=max_len, scan_head=head, codes_tiled=tiled)
+    if list_offsets is not None and list_bounds:
+        index.list_bounds = trim.trim_pack_list_bounds(index)
     return BuiltWorkload(w, index, queries, centroids)
 
 

@@ -23,6 +23,7 @@ TRIM_MAX_NPROBE = 4096
 EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
+           "trim_list_bounds_bytes", "trim_pack_list_bounds",
            "trim_ceiling_stream_read", "trim_ceiling_lds_gather",
            "trim_strerror", "trim_last_hip_error", "trim_version")
 
@@ -50,7 +51,7 @@ class _IndexView(C.Structure):
 
 class _Candidates(C.Structure):
     _fields_ = [("nlist", C.c_int32), ("nprobe", C.c_int32), ("list_offsets", C.c_void_p),
-                ("probes", C.c_void_p), ("max_candidates", C.c_int64)]
+                ("probes", C.c_void_p), ("max_candidates", C.c_int64), ("list_bounds", C.c_void_p)]
 
 
 class _Stats(C.Structure):
@@ -92,6 +93,9 @@ def lib() -> C.CDLL:
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
                                       C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.trim_list_bounds_bytes.restype = C.c_size_t
+        L.trim_list_bounds_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.trim_pack_list_bounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_ceiling_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_ceiling_lds_gather.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p]
         L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
@@ -142,6 +146,7 @@ class Index:
     max_list_len: int = 0                 # host copy of the longest list's length
     scan_head: Optional[torch.Tensor] = None      # [n][12] uint8, from trim_pack_scan_head
     codes_tiled: Optional[torch.Tensor] = None    # uint8, from trim_pack_codes_tiled
+    list_bounds: Optional[torch.Tensor] = None    # uint8, from trim_pack_list_bounds
 
     @property
     def n(self): return self.base.shape[0]
@@ -166,7 +171,8 @@ class Index:
         mc = max_candidates or min(self.n, nprobe * self.max_list_len) or self.n
         c = _Candidates(self.list_offsets.shape[0] - 1, nprobe,
                         _ptr(self.list_offsets, torch.int64, "list_offsets"),
-                        _ptr(probes, torch.int32, "probes"), mc)
+                        _ptr(probes, torch.int32, "probes"), mc,
+                        _ptr(self.list_bounds, torch.uint8, "list_bounds"))
         return c, mc
 
 
@@ -366,6 +372,20 @@ def trim_query_order(probes: torch.Tensor, nlist: int) -> torch.Tensor:
     _check(lib().trim_query_order(_ptr(probes, torch.int32, "probes"), nq, nprobe, nlist,
                                   _ptr(order, torch.int32, "order"), _stream()), "trim_query_order")
     return order
+
+
+def trim_pack_list_bounds(index: "Index") -> torch.Tensor:
+    """Per-list summaries (occurring codes per subspace, largest landmark distance) for the
+    list-level pruning of trim_search_knn."""
+    assert index.list_offsets is not None
+    nlist = index.list_offsets.shape[0] - 1
+    out = torch.empty((lib().trim_list_bounds_bytes(nlist, index.M),), dtype=torch.uint8,
+                      device=index.base.device)
+    view = index._view()
+    _check(lib().trim_pack_list_bounds(C.byref(view), _ptr(index.list_offsets, torch.int64, "list_offsets"),
+                                       nlist, _ptr(out, torch.uint8, "out"), _stream()),
+           "trim_pack_list_bounds")
+    return out
 
 
 def trim_ceiling_stream_read(buf: torch.Tensor, blocks: int, sink: torch.Tensor) -> None:

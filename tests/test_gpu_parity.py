@@ -33,6 +33,8 @@ def to_dev(T, b):
                  max_list_len=int(np.diff(ix.list_offsets).max()) if ix.list_offsets is not None else 0)
     if ix.codes.shape[1] % 8 == 0:
         gi.scan_head = T.trim_pack_scan_head(gi.codes, gi.dlx)
+    if ix.list_offsets is not None:
+        gi.list_bounds = T.trim_pack_list_bounds(gi)
     return gi, t(b.queries), t(b.probes)
 
 
@@ -315,6 +317,51 @@ def test_scan_head_is_a_copy_and_changes_no_result(T, oracle):
     with pytest.raises(T.TrimError):   # M = 12: the record's 8 code bytes need M % 8 == 0
         T.trim_pack_scan_head(torch.zeros((4, 12), dtype=torch.uint8, device="cuda"),
                               torch.zeros((4,), dtype=torch.float32, device="cuda"))
+
+
+@pytest.mark.parametrize("name", ["c2s", "c5s", "c4s"])
+def test_list_summaries_hold_and_change_no_result(T, oracle, name):
+    """The per-list records hold exactly the codes that occur in each list (ascending, padded with
+    the first; count 255 beyond 64 distinct codes) and the largest landmark distance; a search
+    gives the same masks, counters and results with and without them, equal to the oracle's."""
+    from paper_2508_17828_amd import trim as _t
+    b = case(name)
+    gi, q, probes = to_dev(T, b)
+    ix = b.index
+    M = ix.codes.shape[1]
+    nlist = len(ix.list_offsets) - 1
+    rec = gi.list_bounds.cpu().numpy().reshape(nlist, -1)
+    boff = (M * 65 + 3) // 4 * 4
+    assert rec.shape[1] == (boff + 4 + 15) // 16 * 16
+    lo = ix.list_offsets
+    for l in range(nlist):
+        rows = slice(int(lo[l]), int(lo[l + 1]))
+        bmax = rec[l, boff:boff + 4].copy().view(np.float32)[0]
+        if lo[l] == lo[l + 1]:
+            assert bmax == 0 and not rec[l, M * 64:M * 65].any()
+            continue
+        assert bmax == ix.dlx[rows].max()
+        for j in range(M):
+            want = np.unique(ix.codes[rows, j])
+            cnt = int(rec[l, M * 64 + j])
+            if len(want) > 64:
+                assert cnt == 255
+                continue
+            assert cnt == len(want)
+            got = rec[l, j * 64:(j + 1) * 64]
+            np.testing.assert_array_equal(got[:cnt], want)
+            assert (got[cnt:] == want[0]).all()
+    for k, gamma, batch in ((10, 0.3, 256), (100, 0.0, 16), (10, 0.8, 1024)):
+        with_b = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True)
+        saved, gi.list_bounds = gi.list_bounds, None
+        without = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True)
+        gi.list_bounds = saved
+        for key in ("ids", "d2", "n_exact", "n_scanned", "mask"):
+            assert np.array_equal(with_b[key].cpu().numpy(), without[key].cpu().numpy()), key
+        ref = oracle.search_knn(ix, b.queries, k, gamma, batch, b.probes, want_mask=True)
+        np.testing.assert_array_equal(with_b["ids"].cpu().numpy(), ref["ids"])
+        mw = ref["mask"].shape[1]
+        np.testing.assert_array_equal(u32(with_b["mask"])[:, :mw], ref["mask"])
 
 
 @pytest.mark.parametrize("name", ["c4s", "c2s"])

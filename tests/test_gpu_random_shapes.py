@@ -75,6 +75,8 @@ def test_random_configuration(oracle, seed):
         gi.scan_head = T.trim_pack_scan_head(gi.codes, gi.dlx)
     if w.M % 16 == 0 and seed % 2 == 0:
         gi.codes_tiled = T.trim_pack_codes_tiled(gi.codes)
+    if ix.list_offsets is not None and seed % 3 != 0:   # list-level pruning on in two draws of three
+        gi.list_bounds = T.trim_pack_list_bounds(gi)
     q, probes = t(b.queries), t(b.probes)
     what = f"seed {seed}: n={w.n} d={w.d} M={w.M} k={k} batch={batch} first={first} gamma={gamma} " \
            f"nlist={w.nlist} nprobe={w.nprobe} law={w.law}"
