@@ -36,7 +36,7 @@ struct Plan {
     int threads;
     int P, Mp, vec;
     size_t lds;
-    uint32_t off_q, off_segp, off_segd, off_rest, off_rowmin, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_q, off_segp, off_segd, off_rest, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int span, wqcap, cruise, poss_cap, scap, rcap, bucket;
 };
@@ -94,7 +94,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
             if (can_cruise && wq_min < (size_t)nwaves * kRing * 4) wq_min = (size_t)nwaves * kRing * 4;
             const size_t rest = tab + up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) +
                                 up16((size_t)nsegs * 4) + up16((size_t)(Mp / 4 + 1) * 4) +
-                                up16((size_t)Mp * 4) + up16((size_t)nsegs * 20) +
+                                up16((size_t)nsegs * 8) +
                                 (range ? up16((size_t)cap * 4) : 0) +
                                 up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
                                 up16((size_t)ncnt * 4);
@@ -126,8 +126,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
                 pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
                 pl->off_rest = (uint32_t)off; off += up16((size_t)(Mp / 4 + 1) * 4);
-                pl->off_rowmin = (uint32_t)off; off += up16((size_t)Mp * 4);
-                pl->off_seglb = (uint32_t)off; off += up16((size_t)nsegs * 20);
+                pl->off_seglb = (uint32_t)off; off += up16((size_t)nsegs * 8);
                 pl->off_spos = (uint32_t)off; off += up16((size_t)scap * 4);
                 pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
                 pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
@@ -223,7 +222,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.n_exact = stats ? stats->n_exact : nullptr;
     a.mask = mask; a.mask_words = mask_words;
     a.off_q = pl.off_q; a.off_segp = pl.off_segp; a.off_segd = pl.off_segd; a.off_rest = pl.off_rest;
-    a.off_rowmin = pl.off_rowmin; a.off_seglb = pl.off_seglb;
+    a.off_seglb = pl.off_seglb;
     a.list_bounds = cand ? static_cast<const uint8_t *>(cand->list_bounds) : nullptr;
     a.off_spos = pl.off_spos; a.off_sd2 = pl.off_sd2; a.off_sidx = pl.off_sidx;
     a.off_rd2 = pl.off_rd2; a.off_rid = pl.off_rid; a.off_ctl = pl.off_ctl;

@@ -70,7 +70,7 @@ struct SearchArgs {
     int64_t rmask_words;
     int32_t *chunk_counts;   // [nq][nsplit]
     // LDS carve-up (byte offsets)
-    uint32_t off_q, off_segp, off_segd, off_rest, off_rowmin, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
+    uint32_t off_q, off_segp, off_segd, off_rest, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int32_t wqcap;     // entries per wave in each of the two work-queue arrays
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
@@ -363,12 +363,8 @@ void search_kernel(const SearchArgs a) {
     int *segp = reinterpret_cast<int *>(smem + a.off_segp);   // [nseg+1] prefix of lengths
     int *segd = reinterpret_cast<int *>(smem + a.off_segd);   // [nseg] start - prefix
     float *restv = reinterpret_cast<float *>(smem + a.off_rest);  // [M/4+1] remaining minima (cruise)
-    float *rowmin = reinterpret_cast<float *>(smem + a.off_rowmin);  // [M] smallest entry of each table row
-    float *seglb = reinterpret_cast<float *>(smem + a.off_seglb);    // [nseg] list-level lower bound of the table sum
-    float *segrest = seglb + (a.nseg > 0 ? a.nseg : 1);             // [nseg] the same over subspaces H0..
-    float *segbm = segrest + (a.nseg > 0 ? a.nseg : 1);             // [nseg] largest landmark distance of the list
-    int *segl = reinterpret_cast<int *>(segbm + (a.nseg > 0 ? a.nseg : 1));  // [nseg] list id (-1: none)
-    float *segstate = reinterpret_cast<float *>(segl + (a.nseg > 0 ? a.nseg : 1));  // [nseg] per stretch, see the cruise
+    float *rowmin = reinterpret_cast<float *>(smem + a.off_plb);     // [M] smallest entry of each table row (prologue only)
+    float2 *seglist = reinterpret_cast<float2 *>(smem + a.off_seglb); // [nseg] list-level pruning {slack, rest}: see the prologue
     int32_t *spos = reinterpret_cast<int32_t *>(smem + a.off_spos);  // survivor position -> id
     float *sd2 = reinterpret_cast<float *>(smem + a.off_sd2);        // exact d2 (shares the queue area)
     int32_t *sidx = reinterpret_cast<int32_t *>(smem + a.off_sidx);  // range: scan-order number
@@ -406,10 +402,15 @@ void search_kernel(const SearchArgs a) {
     for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
     if (MODE == kKnn)
         for (int g = tid; g < kWave * E; g += T) { rd2[g] = __builtin_inff(); rid[g] = kEmptyId; }
+    // (list ids wait in the queue area, idle until the seed's barrier, for the list-level bounds)
+    int *segl = reinterpret_cast<int *>(smem + a.off_wq);
+    const bool segl_fits = nseg <= a.scap + a.rcap;
     for (int p = tid; p < nseg; p += T) {
         int64_t s = 0, e = a.n;
+        int32_t lp = -1;
         if (a.nseg > 0) {
             const int32_t l = a.probes[(size_t)q * a.nseg + p];
+            lp = l;
             if (l >= 0 && l < a.nlist) {
                 s = a.list_offsets[l];
                 e = a.list_offsets[l + 1];
@@ -421,7 +422,7 @@ void search_kernel(const SearchArgs a) {
         }
         segd[p] = (int)s;            // start for now
         segp[p + 1] = (int)(e - s);  // length for now
-        segl[p] = (a.nseg > 0 && e > s) ? a.probes[(size_t)q * a.nseg + p] : -1;
+        if (segl_fits) segl[p] = e > s ? lp : -1;
     }
     __syncthreads();
     if (tid == 0) {
@@ -470,11 +471,13 @@ void search_kernel(const SearchArgs a) {
         }
     }   // (read after the next barrier: the seed's, or the one at the top of the main loop)
     // List-level bounds (kNN over inverted lists whose summaries the caller supplies): for the
-    // list of segment p, seglb[p] = sum over all subspaces j of the smallest T[j][c] over the
-    // codes c that occur in the list, a lower bound of every table sum of the list; segrest[p]
-    // = the same over the subspaces from H0 on; segbm[p] = the list's largest landmark distance.
-    // One wave per segment; a lane takes 16 recorded codes of one subspace (4 lanes per
-    // subspace, 16 subspaces per step).
+    // list of segment p, lb = sum over all subspaces j of the smallest T[j][c] over the codes c
+    // that occur in the list, a lower bound of every table sum of the list; rest = the same
+    // over the subspaces from H0 on; bm = the list's largest landmark distance.  Every abandon
+    // threshold of the list is at most (c bm + st)^2 (abandon_threshold grows with the
+    // landmark distance), so while lb exceeds that, nothing in the list can survive.
+    // Two segments per wave and round; a lane takes 16 recorded codes of one subspace (4 lanes
+    // per subspace, 32 subspaces of either list per step, all loads of a step issued together).
     if (MODE == kKnn && a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr) {
         constexpr int kH0 = VEC >= 2 ? 8 : 4;
         const size_t rec_bytes = list_record_bytes(a.M);
@@ -485,7 +488,8 @@ void search_kernel(const SearchArgs a) {
             float bm[2], lb[2] = {0.0f, 0.0f}, rest[2] = {0.0f, 0.0f};
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const int l = p0 + t < nseg ? segl[p0 + t] : -1;     // same for the wave
+                const int l = p0 + t >= nseg ? -1                     // same for the wave
+                              : segl_fits ? segl[p0 + t] : a.probes[(size_t)q * a.nseg + p0 + t];
                 rec[t] = (l >= 0 && l < a.nlist) ? a.list_bounds + (size_t)l * rec_bytes : nullptr;
                 bm[t] = rec[t] ? *reinterpret_cast<const float *>(rec[t] + list_record_bmax_offset(a.M))
                                : __builtin_inff();
@@ -535,7 +539,11 @@ void search_kernel(const SearchArgs a) {
                     lb[t] = lb[t] + __shfl_xor(lb[t], off);
                     rest[t] = rest[t] + __shfl_xor(rest[t], off);
                 }
-                if (lane == 0 && p0 + t < nseg) { seglb[p0 + t] = lb[t]; segrest[p0 + t] = rest[t]; segbm[p0 + t] = bm[t]; }
+                // the list is passed over while lb > (c bm + st)^2, i.e. while
+                // sqrt(lb) - c bm > st: the left side is kept, rounded against passing over
+                float slack = sqrt_rn(lb[t]) * (1.0f - 1e-6f) - kAbandonC * bm[t] * (1.0f + 1e-6f);
+                if (!(slack == slack)) slack = -__builtin_inff();
+                if (lane == 0 && p0 + t < nseg) seglist[p0 + t] = make_float2(slack, rest[t]);
             }
         }
     }
@@ -767,9 +775,6 @@ void search_kernel(const SearchArgs a) {
             const int nb = (S + a.bucket - 1) / a.bucket;   // buckets (= batches unless they are very small)
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
             if (tid == 0) ctl->nposs = 0;
-            if (a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr)
-                for (int p = tid; p < nseg; p += T)
-                    segstate[p] = seglb[p] > abandon_threshold(segbm[p], sqrt_tau0) ? __builtin_inff() : segrest[p];
             __syncthreads();
             {
                 uint32_t *ring = reinterpret_cast<uint32_t *>(wq) + (size_t)wave * kRing;  // (segment << 16) | number
@@ -849,10 +854,10 @@ void search_kernel(const SearchArgs a) {
                 // what subspaces H0.. add at the least, in a scalar register
                 const float rest_h0 = __builtin_bit_cast(
                     float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, restv[H0 / 4])));
-                // segstate[p] (set at the start of the stretch): what subspaces H0.. add at the
-                // least for the list of segment p, or +inf if the whole list is passed over
+                // list-level pruning: a list is passed over while its slack > st (both compared as
+                // integers: st > 0, and a negative slack is a negative integer)
                 const bool have_lb = a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr;
-                constexpr int kInfBits = 0x7f800000;
+                const int st_bits = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sqrt_tau0));
                 for (int blk = wave; blk < nblk; blk += nwaves) {
                     // this block's loads fly while the previous drain is finished; the next
                     // drain's loads fly while this block is bounded
@@ -873,9 +878,11 @@ void search_kernel(const SearchArgs a) {
                             s_delta = __builtin_amdgcn_readfirstlane(segd[s_seg]);
                         }
                         if (cf + U * kWave <= s_end) {
-                            const int st_bits = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, segstate[s_seg]));
-                            if (st_bits == kInfBits) continue;   // same for the whole wave
-                            blk_rest = __builtin_bit_cast(float, st_bits);
+                            const float2 sr = seglist[s_seg];
+                            const int sl = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sr.x));
+                            const int rs = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sr.y));
+                            if (sl > st_bits) continue;          // same for the whole wave
+                            blk_rest = __builtin_bit_cast(float, rs);
                         }
                     }
                     if (full) {
