@@ -883,6 +883,12 @@ void search_kernel(const SearchArgs a) {
                             const int rs = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sr.y));
                             if (sl > st_bits) continue;          // same for the whole wave
                             blk_rest = __builtin_bit_cast(float, rs);
+                        } else if (s_seg + 1 < nseg) {
+                            // the block ends in the next list: passed over if both lists are
+                            const int e2 = __builtin_amdgcn_readfirstlane(segp[s_seg + 2]);
+                            const int sl1 = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seglist[s_seg].x));
+                            const int sl2 = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seglist[s_seg + 1].x));
+                            if (cf + U * kWave <= e2 && sl1 > st_bits && sl2 > st_bits) continue;
                         }
                     }
                     if (full) {
