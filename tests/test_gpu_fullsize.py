@@ -78,6 +78,21 @@ def test_knn_full_batch_sampled_against_oracle(c2, oracle, gamma):
         np.testing.assert_array_equal(ids[qs], bi)
 
 
+@pytest.mark.parametrize("gamma,batch,k", [(0.45, 1024, 10), (0.0, 1024, 10), (0.8, 1024, 10), (0.4, 16, 10),
+                                           (0.4, 1, 10), (0.3, 128, 10), (0.45, 1024, 100), (0.4, 16, 100)])
+def test_knn_every_query_against_oracle(c2, oracle, gamma, batch, k):
+    """All 10,000 queries at the benchmark's operating point: result ids, distances and both
+    counters of every query equal the oracle's (the oracle scans them on all host threads; the
+    per-candidate masks are compared on the sampled queries above)."""
+    T, w, bw, host = c2["trim"], c2["w"], c2["bw"], c2["host"]
+    full = T.trim_search_knn(bw.index, bw.queries, k, gamma, batch, probes=c2["probes"])
+    ref = oracle.search_knn(host, c2["queries"], k, gamma, batch, c2["probes"].cpu().numpy())
+    np.testing.assert_array_equal(full["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_array_equal(full["d2"].cpu().numpy().view(np.uint32), ref["d2"].view(np.uint32))
+    np.testing.assert_array_equal(full["n_exact"].cpu().numpy(), ref["n_exact"])
+    np.testing.assert_array_equal(full["n_scanned"].cpu().numpy(), ref["n_scanned"])
+
+
 @pytest.mark.parametrize("batch", [1, 16, 100])
 def test_knn_small_batches_sampled_against_oracle(c2, oracle, batch):
     """Small batches down to batch = 1, the paper's vector-at-a-time rule, at the benchmark's

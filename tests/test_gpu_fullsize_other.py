@@ -77,7 +77,7 @@ def test_c3_full_base(oracle):
     w, bw, host, queries, probes, trim = build("C3", oracle)
     check_encode_rows(oracle, host, 91)
     for gamma in w.gammas:
-        check_knn(oracle, w, bw, host, queries, probes, trim, gamma, 3, 92)
+        check_knn(oracle, w, bw, host, queries, probes, trim, gamma, 24, 92)
 
 
 def test_c4_full_base_range(oracle):
@@ -86,15 +86,15 @@ def test_c4_full_base_range(oracle):
     radius = radius_from_pairs(w, host, queries, w.range_percentile)
     total = 0
     for gamma in w.gammas:
-        total += check_range(oracle, w, bw, host, queries, probes, trim, radius, gamma, 6, 94)
+        total += check_range(oracle, w, bw, host, queries, probes, trim, radius, gamma, 24, 94)
     assert total > 0
-    check_knn(oracle, w, bw, host, queries, probes, trim, 0.0, 4, 95)
+    check_knn(oracle, w, bw, host, queries, probes, trim, 0.0, 24, 95)
 
 
 def test_c5_full_base(oracle):
     w, bw, host, queries, probes, trim = build("C5", oracle)
     check_encode_rows(oracle, host, 96)
     for gamma in (0.0, 0.5):
-        check_knn(oracle, w, bw, host, queries, probes, trim, gamma, 6, 97)
+        check_knn(oracle, w, bw, host, queries, probes, trim, gamma, NQ, 97)   # every query
     radius = radius_from_pairs(w, host, queries, w.range_percentile)
     check_range(oracle, w, bw, host, queries, probes, trim, radius, 0.5, 6, 98)
