@@ -268,6 +268,21 @@ def test_knn_empty_and_repeated_lists(T, oracle):
     assert np.all(got["ids"].cpu().numpy() == -1)
 
 
+def test_knn_long_probe_sequences(T, oracle):
+    """2,500 probed lists per query (more segments than the kernel keeps list ids for in
+    on-chip memory), short lists, with and without the list summaries."""
+    w = synth.scaled(synth.WORKLOADS["C2"], 150_000, 12, nlist=3000, nprobe=2500, kmeans_iters=2)
+    b = helpers.build(w, pq_train_max=8192, ivf_train_per_list=16)
+    for k, gamma, batch in ((10, 0.4, 1024), (10, 0.0, 16), (100, 0.5, 256)):
+        check_knn(T, oracle, b, k, gamma, batch)
+    gi, q, probes = to_dev(T, b)
+    gi.list_bounds = None
+    got = T.trim_search_knn(gi, q, 10, 0.4, 1024, probes=probes, want_mask=True)
+    ref = oracle.search_knn(b.index, b.queries, 10, 0.4, 1024, b.probes, want_mask=True)
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"])
+
+
 def test_query_order_changes_nothing_but_scheduling(T, oracle):
     b = case("c5s")
     gi, q, probes = to_dev(T, b)
