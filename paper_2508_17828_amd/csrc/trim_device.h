@@ -177,6 +177,49 @@ __device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
     for (int u = 0; u < 4; ++u) out[u] = half_reduce(acc[u]);
 }
 
+// Two long rows at once with ALL their loads in flight together (up to 8 steps of 128 values
+// per row and pass; longer rows take several passes).  For the few survivors of a short span,
+// where the latency of a row's dependent steps, not bandwidth, is what the refine step waits
+// for.  Same arithmetic per row as exact_d2_half.
+__device__ __forceinline__ void exact_d2_half_x2_deep(const float *__restrict__ r0,
+                                                      const float *__restrict__ r1,
+                                                      const float *__restrict__ q, int d, int lane32,
+                                                      float (&out)[2]) {
+    constexpr int kDeep = 8;
+    const float4 *rows[2] = {reinterpret_cast<const float4 *>(r0), reinterpret_cast<const float4 *>(r1)};
+    const float4 *q4 = reinterpret_cast<const float4 *>(q);
+    float acc[2] = {0.0f, 0.0f};
+    const int ng = d >> 2;
+    for (int g0 = lane32; g0 < ng; g0 += 32 * kDeep) {
+        float4 xv[2][kDeep];
+#pragma unroll
+        for (int t = 0; t < kDeep; ++t) {
+            const int g = g0 + 32 * t;
+            if (g < ng) {
+                xv[0][t] = rows[0][g];
+                xv[1][t] = rows[1][g];
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kDeep; ++t) {
+            const int g = g0 + 32 * t;
+            if (g < ng) {
+                const float4 qv = q4[g];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    float e;
+                    e = qv.x - xv[u][t].x; acc[u] = __builtin_fmaf(e, e, acc[u]);
+                    e = qv.y - xv[u][t].y; acc[u] = __builtin_fmaf(e, e, acc[u]);
+                    e = qv.z - xv[u][t].z; acc[u] = __builtin_fmaf(e, e, acc[u]);
+                    e = qv.w - xv[u][t].w; acc[u] = __builtin_fmaf(e, e, acc[u]);
+                }
+            }
+        }
+    }
+    out[0] = half_reduce(acc[0]);
+    out[1] = half_reduce(acc[1]);
+}
+
 // 4 * (byte B of w): the byte offset of a table entry inside its 1 KB row.
 template <int B>
 __device__ __forceinline__ uint32_t byte_times4(uint32_t w) {

@@ -599,6 +599,26 @@ void search_kernel(const SearchArgs a) {
     // per half wave.  pos_of(i) gives the storage position of entry i; put(i, d2, id or
     // position) stores the result (called by one lane of the half wave).
     auto refine_rows = [&](int ns, auto pos_of, auto put) {
+        // Few long rows (the survivors of a short span): two rows per half wave with all their
+        // loads in flight, instead of four rows step by step.  (Instances with the larger
+        // register budget only.)
+        if ((MODE != kKnn || E > 1) && a.d >= 512 && ns <= 8 * nhalf) {
+            for (int i = half; i < ns; i += 2 * nhalf) {
+                const int i1 = i + nhalf;
+                const bool ok1 = i1 < ns;               // uniform within the half wave
+                const int p0 = pos_of(i), p1 = pos_of(ok1 ? i1 : i);
+                const int32_t id0 = (MODE == kKnn && a.ids) ? a.ids[p0] : p0;
+                const int32_t id1 = (MODE == kKnn && a.ids) ? a.ids[p1] : p1;
+                float d2[2];
+                exact_d2_half_x2_deep(a.base + (size_t)p0 * a.d, a.base + (size_t)p1 * a.d, q_lds, a.d,
+                                      lane32, d2);
+                if (lane32 == 0) {
+                    put(i, d2[0], id0);
+                    if (ok1) put(i1, d2[1], id1);
+                }
+            }
+            return;
+        }
         for (int i = half; i < ns; i += 4 * nhalf) {
             int idx[4], pos[4];
             bool ok[4];
