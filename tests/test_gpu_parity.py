@@ -475,6 +475,24 @@ def test_argument_errors(T):
         T.trim_encode(gi.base, gi.codebooks[:, :, :7].contiguous())
     with pytest.raises(TypeError):
         T.trim_encode(gi.base.cpu(), gi.codebooks)
+    # list summaries: the record size is what the header says; a misaligned buffer, or one that is
+    # passed to a search misaligned, is refused
+    import ctypes as C
+    L = T.lib()
+    assert L.trim_list_bounds_bytes(7, 32) == 7 * 2096      # 32 x 64 codes + 32 counts + 4, to 16
+    assert L.trim_list_bounds_bytes(0, 32) == 0
+    b2 = case("c5s")
+    gi2, q2, probes2 = to_dev(T, b2)
+    buf = torch.zeros(gi2.list_bounds.numel() + 16, dtype=torch.uint8, device="cuda")
+    view = gi2._view()
+    nlist = gi2.list_offsets.shape[0] - 1
+    assert L.trim_pack_list_bounds(C.byref(view), C.c_void_p(gi2.list_offsets.data_ptr()), nlist,
+                                   C.c_void_p(buf.data_ptr() + 4), None) == -1
+    assert L.trim_pack_list_bounds(C.byref(view), C.c_void_p(gi2.list_offsets.data_ptr()), 0,
+                                   C.c_void_p(buf.data_ptr()), None) == -1
+    gi2.list_bounds = buf[4:4 + gi2.list_bounds.numel()]          # a view that starts 4 bytes in
+    with pytest.raises(T.TrimError):
+        T.trim_search_knn(gi2, q2, 10, 0.0, 64, probes=probes2)
 
 
 # ---- trim_search_range ---------------------------------------------------------------------------
