@@ -1035,8 +1035,12 @@ void search_kernel(const SearchArgs a) {
                     }
                 }
             } else {
-                // overflow: shorter stretches from now on (or none), and redo from c0 span by span
-                cruise = cruise / 2 >= 2 * a.span ? cruise / 2 / a.batch * a.batch : 0;
+                // overflow: redo from c0 span by span, and shorter stretches from now on (or
+                // none): np counts every possible of the stretch, so the length that would
+                // have half filled the list is known
+                const long long want = (long long)S * a.poss_cap / (2LL * np);
+                const int shorter = (int)(want < cruise / 2 ? want : cruise / 2) / a.batch * a.batch;
+                cruise = shorter >= 2 * a.span ? shorter : 0;
                 cur.init(segp, segd);
                 __syncthreads();
             }
