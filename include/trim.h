@@ -248,7 +248,8 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
                       void *stream);
 
 /* Bytes of workspace trim_search_range needs for nq queries with at most max_candidates
- * candidates each (index->n when there is no candidate structure). */
+ * candidates each (index->n when there is no candidate structure): about 4.2 bytes per
+ * (query, candidate) pair -- a result bit and a slot for the result's exact distance. */
 size_t trim_range_workspace_bytes(int64_t nq, int64_t max_candidates);
 
 /*

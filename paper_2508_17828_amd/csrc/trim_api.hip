@@ -259,7 +259,7 @@ struct RangeLayout {
     int nsplit;
     int chunk;
     int64_t rmask_words;
-    size_t off_counts, off_cbase, total;
+    size_t off_counts, off_cbase, off_d2, total;
 };
 
 RangeLayout range_layout(int64_t nq, int64_t max_cand) {
@@ -275,6 +275,10 @@ RangeLayout range_layout(int64_t nq, int64_t max_cand) {
     L.off_counts = off; off += (size_t)nq * L.nsplit * 4;
     off = (off + 255) & ~size_t(255);
     L.off_cbase = off; off += (size_t)nq * L.nsplit * 8;
+    off = (off + 255) & ~size_t(255);
+    // the exact distance of every result waits here, at its scan-order number, for the pass that
+    // writes the CSR arrays (one binary32 per candidate slot; only result slots are touched)
+    L.off_d2 = off; off += (size_t)nq * L.rmask_words * 32 * 4;
     L.total = (off + 255) & ~size_t(255);
     return L;
 }
@@ -585,6 +589,7 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
     uint32_t *rmask = reinterpret_cast<uint32_t *>(ws);
     int32_t *counts = reinterpret_cast<int32_t *>(ws + L.off_counts);
     int64_t *cbase = reinterpret_cast<int64_t *>(ws + L.off_cbase);
+    float *rd2 = reinterpret_cast<float *>(ws + L.off_d2);
 
     if ((rc = fill_u32(rmask, (size_t)nq * L.rmask_words, 0u, st))) return rc;
     if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
@@ -597,13 +602,14 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
     a.radius2 = radius * radius;
     a.chunk = L.chunk; a.nsplit = L.nsplit;
     a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;
+    a.result_d2 = rd2;
     if (a.max_cand > max_cand) a.max_cand = (int32_t)max_cand;
 
     RangeFillArgs f{};
     f.base = index->base; f.ids = index->ids; f.queries = queries;
     f.list_offsets = a.list_offsets; f.probes = a.probes; f.n = index->n; f.d = index->d;
     f.nlist = a.nlist; f.nseg = a.nseg; f.max_cand = a.max_cand; f.chunk = L.chunk;
-    f.nsplit = L.nsplit; f.result_mask = rmask; f.rmask_words = L.rmask_words;
+    f.nsplit = L.nsplit; f.result_mask = rmask; f.rmask_words = L.rmask_words; f.result_d2 = rd2;
     f.chunk_base = cbase; f.out_ids = out_ids; f.out_d2 = out_d2; f.capacity = capacity;
     const int nsegs = a.nseg > 0 ? a.nseg : 1;
     size_t off = 0;

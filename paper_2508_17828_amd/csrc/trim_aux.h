@@ -511,6 +511,7 @@ struct RangeFillArgs {
     int32_t d, nlist, nseg, max_cand, chunk, nsplit;
     const uint32_t *result_mask;
     int64_t rmask_words;
+    const float *result_d2;   // exact distance of each result, by scan-order number
     const int64_t *chunk_base;
     int32_t *out_ids;
     float *out_d2;
@@ -520,7 +521,6 @@ struct RangeFillArgs {
 
 __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
     int *segp = reinterpret_cast<int *>(smem + a.off_segp);
     int *segd = reinterpret_cast<int *>(smem + a.off_segd);
     int *list = reinterpret_cast<int *>(smem + a.off_list);  // [2048] scan-order numbers
@@ -532,7 +532,6 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
     const int split = blockIdx.y;
     const int nseg = a.nseg > 0 ? a.nseg : 1;
 
-    for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
     for (int p = tid; p < nseg; p += T) {
         int64_t s = 0, e = a.n;
         if (a.nseg > 0) {
@@ -593,7 +592,8 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
         }
         __syncthreads();
         const int cnt = s_cnt;
-        for (int i = tid >> 5; i < cnt; i += T >> 5) {
+        for (int i = tid; i < cnt; i += T) {
+            if (out + i >= a.capacity) break;
             const int c = list[i];
             // segment of c by binary search over the prefix table
             int lo = 0, hi = nseg - 1;
@@ -602,11 +602,8 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
                 if (c >= segp[mid + 1]) lo = mid + 1; else hi = mid;
             }
             const int pos = c + segd[lo];
-            const float d2 = exact_d2_half(a.base + (size_t)pos * a.d, q_lds, a.d, tid & 31);
-            if ((tid & 31) == 0 && out + i < a.capacity) {
-                a.out_ids[out + i] = a.ids ? a.ids[pos] : pos;
-                a.out_d2[out + i] = d2;
-            }
+            a.out_ids[out + i] = a.ids ? a.ids[pos] : pos;
+            a.out_d2[out + i] = a.result_d2[(size_t)q * a.rmask_words * 32 + c];   // as the search computed it
         }
         out += cnt;
         __syncthreads();

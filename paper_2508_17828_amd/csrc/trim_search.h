@@ -67,6 +67,7 @@ struct SearchArgs {
     int32_t chunk;           // candidates per workgroup, multiple of 64
     int32_t nsplit;
     uint32_t *result_mask;   // [nq][rmask_words]
+    float *result_d2;        // [nq][rmask_words * 32]: exact distance of each result, by scan-order number
     int64_t rmask_words;
     int32_t *chunk_counts;   // [nq][nsplit]
     // LDS carve-up (byte offsets)
@@ -655,6 +656,7 @@ void search_kernel(const SearchArgs a) {
                         } else if (d2 <= a.radius2) {
                             const int c = sidx[i];
                             atomicOr(&a.result_mask[(size_t)q * a.rmask_words + (c >> 5)], 1u << (c & 31));
+                            a.result_d2[(size_t)q * a.rmask_words * 32 + c] = d2;
                             atomicAdd(&ctl->nresult, 1);
                         }
                     });
