@@ -674,6 +674,61 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         }
     }
     __syncthreads();
+    // Short probe lists (nprobe <= 32, at least 128 lists): one wave per query.  Lane l takes the
+    // smallest of the keys l, l+64, ...; the nprobe-th smallest of these 64 minima (sorted across
+    // the lanes) is an upper bound of the nprobe-th smallest key, so only the keys not above it
+    // can be selected.  If at most 64 keys qualify they are sorted across the lanes and the
+    // first nprobe are the result; otherwise (rare) the whole workgroup takes the general path
+    // below.  Keys are distinct, so either path gives the same list.
+    __shared__ int general_path;
+    if (nprobe <= 32 && npow2 >= 128) {
+        if (tid == 0) general_path = 0;
+        __syncthreads();
+        const int wave = tid >> 6, lane = tid & 63;
+        auto sort64 = [&](unsigned long long &key) {
+#pragma unroll
+            for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+                for (int j = size >> 1; j > 0; j >>= 1) {
+                    const uint32_t olo = (uint32_t)__shfl_xor((int)(uint32_t)key, j);
+                    const uint32_t ohi = (uint32_t)__shfl_xor((int)(uint32_t)(key >> 32), j);
+                    const unsigned long long other = ((unsigned long long)ohi << 32) | olo;
+                    const bool keep_min = ((lane & j) == 0) == ((lane & size) == 0);
+                    if (keep_min ? other < key : other > key) key = other;
+                }
+            }
+        };
+        unsigned long long *kq = keys + ((size_t)(wave < nqt ? wave : 0) * npow2);
+        unsigned long long cut = 0;
+        int c = 0;
+        if (wave < nqt) {
+            unsigned long long cmin = ~0ull;
+            for (int i = lane; i < npow2; i += 64) cmin = kq[i] < cmin ? kq[i] : cmin;
+            sort64(cmin);
+            cut = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(cmin >> 32), nprobe - 1) << 32) |
+                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cmin, nprobe - 1);
+            for (int i0 = 0; i0 < npow2; i0 += 64) c += __popcll(__ballot(kq[i0 + lane] <= cut));
+            if (c > 64) atomicOr(&general_path, 1);
+        }
+        __syncthreads();   // nothing has been moved yet: the general path finds every key in place
+        if (!general_path) {
+            if (wave < nqt) {
+                // move the qualifying keys to the front (in place: none moves backwards)
+                int at0 = 0;
+                for (int i0 = 0; i0 < npow2; i0 += 64) {
+                    const unsigned long long key = kq[i0 + lane];
+                    const bool take = key <= cut;
+                    const unsigned long long m = __ballot(take);
+                    if (take) kq[at0 + __popcll(m & ((1ull << lane) - 1ull))] = key;
+                    at0 += __popcll(m);
+                }
+                unsigned long long key = lane < c ? kq[lane] : ~0ull;
+                sort64(key);
+                if (lane < nprobe) probes[(size_t)(q0 + wave) * nprobe + lane] = (int32_t)(key & 0xffffffffu);
+            }
+            return;
+        }
+    }
     // Selection of the nprobe smallest keys of each query with bitonic networks; all sizes are
     // powers of two, so the index arithmetic is shifts and masks (lg_* are base-2 logarithms).
     // (1) runs of R >= nprobe keys are sorted, ascending and descending in turn;
