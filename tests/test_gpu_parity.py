@@ -179,6 +179,27 @@ def test_ivf_probe(T, oracle, name):
 
 # ---- trim_search_knn ---------------------------------------------------------------------------
 
+def test_ivf_probe_keys_crowded_in_few_columns(T, oracle):
+    """The short-list selection looks at the smallest key of each of 64 interleaved columns
+    first.  Here the nearest centroids all sit in the same few columns (index mod 64), so far
+    more than 64 keys lie under its bound and the general selection has to take over; with the
+    centroid order reversed the bound is tight.  Both must give the oracle's lists."""
+    import torch
+    nlist, d = 1024, 8
+    i = np.arange(nlist)
+    rank = (i % 64) * 16 + i // 64                      # column c holds ranks 16c .. 16c+15
+    for r in (rank, nlist - 1 - i):
+        cen = np.zeros((nlist, d), dtype=np.float32)
+        cen[:, 0] = r.astype(np.float32)
+        cen[:, 3] = 0.25 * (i % 3)
+        q = np.zeros((9, d), dtype=np.float32)
+        q[:, 0] = -1.0 - np.arange(9, dtype=np.float32)
+        q[5:, 0] = nlist + 3.0                            # some queries from the far end
+        for nprobe in (1, 7, 32):
+            got = T.trim_ivf_probe(torch.from_numpy(q).cuda(), torch.from_numpy(cen).cuda(), nprobe)
+            np.testing.assert_array_equal(got.cpu().numpy(), oracle.ivf_probe(q, cen, nprobe))
+
+
 def check_knn(T, oracle, b, k, gamma, batch, prebuilt_lut=False, first_batch=0):
     gi, q, probes = to_dev(T, b)
     lut = T.trim_build_lut(q, gi.codebooks) if prebuilt_lut else None
