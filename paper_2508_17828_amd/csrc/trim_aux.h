@@ -674,27 +674,37 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         }
     }
     __syncthreads();
-    // Short probe lists (nprobe <= 32, at least 128 lists): one wave per query.  Lane l takes the
-    // smallest of the keys l, l+64, ...; the nprobe-th smallest of these 64 minima (sorted across
-    // the lanes) is an upper bound of the nprobe-th smallest key, so only the keys not above it
-    // can be selected.  If at most 64 keys qualify they are sorted across the lanes and the
-    // first nprobe are the result; otherwise (rare) the whole workgroup takes the general path
-    // below.  Keys are distinct, so either path gives the same list.
+    // Short probe lists (nprobe <= 64, at least 256 lists): one wave per query.  The keys are seen
+    // as 64 S interleaved columns (S = 1 for nprobe <= 32, else 2; lane l, slot s holds column
+    // 64 s + l); the nprobe-th smallest of the column minima (sorted across lanes and slots) is
+    // an upper bound of the nprobe-th smallest key, so only the keys not above it can be
+    // selected.  If at most 64 S keys qualify they are sorted the same way and the first nprobe
+    // are the result; otherwise (rare) the whole workgroup takes the general path below.  Keys
+    // are distinct, so either path gives the same list.
     __shared__ int general_path;
-    if (nprobe <= 32 && npow2 >= 128) {
+    if (nprobe <= 64 && npow2 >= 256) {
         if (tid == 0) general_path = 0;
         __syncthreads();
         const int wave = tid >> 6, lane = tid & 63;
-        auto sort64 = [&](unsigned long long &key) {
-#pragma unroll
-            for (int size = 2; size <= 64; size <<= 1) {
-#pragma unroll
+        const int S = nprobe <= 32 ? 1 : 2;
+        // ascending bitonic sort of the 64 S elements (element e = 64 slot + lane)
+        auto sort_across = [&](unsigned long long (&key)[2]) {
+            for (int size = 2; size <= 64 * S; size <<= 1) {
                 for (int j = size >> 1; j > 0; j >>= 1) {
-                    const uint32_t olo = (uint32_t)__shfl_xor((int)(uint32_t)key, j);
-                    const uint32_t ohi = (uint32_t)__shfl_xor((int)(uint32_t)(key >> 32), j);
-                    const unsigned long long other = ((unsigned long long)ohi << 32) | olo;
-                    const bool keep_min = ((lane & j) == 0) == ((lane & size) == 0);
-                    if (keep_min ? other < key : other > key) key = other;
+                    if (j >= 64) {            // partner in the other slot of the same lane (S == 2, size 128: ascending)
+                        if (key[1] < key[0]) { const unsigned long long t = key[0]; key[0] = key[1]; key[1] = t; }
+                        continue;
+                    }
+#pragma unroll
+                    for (int sl = 0; sl < 2; ++sl) {
+                        if (sl >= S) break;
+                        const uint32_t olo = (uint32_t)__shfl_xor((int)(uint32_t)key[sl], j);
+                        const uint32_t ohi = (uint32_t)__shfl_xor((int)(uint32_t)(key[sl] >> 32), j);
+                        const unsigned long long other = ((unsigned long long)ohi << 32) | olo;
+                        const int e = 64 * sl + lane;
+                        const bool keep_min = ((lane & j) == 0) == ((e & size) == 0);
+                        if (keep_min ? other < key[sl] : other > key[sl]) key[sl] = other;
+                    }
                 }
             }
         };
@@ -702,13 +712,18 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         unsigned long long cut = 0;
         int c = 0;
         if (wave < nqt) {
-            unsigned long long cmin = ~0ull;
-            for (int i = lane; i < npow2; i += 64) cmin = kq[i] < cmin ? kq[i] : cmin;
-            sort64(cmin);
-            cut = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(cmin >> 32), nprobe - 1) << 32) |
-                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cmin, nprobe - 1);
+            unsigned long long cmin[2] = {~0ull, ~0ull};
+            for (int i = lane; i < npow2; i += 64 * S) {
+                cmin[0] = kq[i] < cmin[0] ? kq[i] : cmin[0];
+                if (S == 2) cmin[1] = kq[i + 64] < cmin[1] ? kq[i + 64] : cmin[1];
+            }
+            sort_across(cmin);
+            const unsigned long long at = (nprobe - 1) >= 64 ? cmin[1] : cmin[0];   // same choice in every lane
+            const int src = (nprobe - 1) & 63;
+            cut = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(at >> 32), src) << 32) |
+                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)at, src);
             for (int i0 = 0; i0 < npow2; i0 += 64) c += __popcll(__ballot(kq[i0 + lane] <= cut));
-            if (c > 64) atomicOr(&general_path, 1);
+            if (c > 64 * S) atomicOr(&general_path, 1);
         }
         __syncthreads();   // nothing has been moved yet: the general path finds every key in place
         if (!general_path) {
@@ -722,9 +737,12 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
                     if (take) kq[at0 + __popcll(m & ((1ull << lane) - 1ull))] = key;
                     at0 += __popcll(m);
                 }
-                unsigned long long key = lane < c ? kq[lane] : ~0ull;
-                sort64(key);
-                if (lane < nprobe) probes[(size_t)(q0 + wave) * nprobe + lane] = (int32_t)(key & 0xffffffffu);
+                unsigned long long key[2];
+                key[0] = lane < c ? kq[lane] : ~0ull;
+                key[1] = (S == 2 && 64 + lane < c) ? kq[64 + lane] : ~0ull;
+                sort_across(key);
+                if (lane < nprobe) probes[(size_t)(q0 + wave) * nprobe + lane] = (int32_t)(key[0] & 0xffffffffu);
+                if (64 + lane < nprobe) probes[(size_t)(q0 + wave) * nprobe + 64 + lane] = (int32_t)(key[1] & 0xffffffffu);
             }
             return;
         }

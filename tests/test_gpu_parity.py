@@ -195,7 +195,7 @@ def test_ivf_probe_keys_crowded_in_few_columns(T, oracle):
         q = np.zeros((9, d), dtype=np.float32)
         q[:, 0] = -1.0 - np.arange(9, dtype=np.float32)
         q[5:, 0] = nlist + 3.0                            # some queries from the far end
-        for nprobe in (1, 7, 32):
+        for nprobe in (1, 7, 32, 33, 64, 65):
             got = T.trim_ivf_probe(torch.from_numpy(q).cuda(), torch.from_numpy(cen).cuda(), nprobe)
             np.testing.assert_array_equal(got.cpu().numpy(), oracle.ivf_probe(q, cen, nprobe))
 
