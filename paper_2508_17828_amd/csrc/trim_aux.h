@@ -717,7 +717,19 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
                 cmin[0] = kq[i] < cmin[0] ? kq[i] : cmin[0];
                 if (S == 2) cmin[1] = kq[i + 64] < cmin[1] ? kq[i + 64] : cmin[1];
             }
-            sort_across(cmin);
+            if (nprobe == 1) {   // the nearest list alone (assignment of a base set): a minimum, no sort
+                unsigned long long m = cmin[0];
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint32_t olo = (uint32_t)__shfl_xor((int)(uint32_t)m, off);
+                    const uint32_t ohi = (uint32_t)__shfl_xor((int)(uint32_t)(m >> 32), off);
+                    const unsigned long long other = ((unsigned long long)ohi << 32) | olo;
+                    m = other < m ? other : m;
+                }
+                cmin[0] = m;       // every lane holds it: the bound below is the key itself
+            } else {
+                sort_across(cmin);
+            }
             const unsigned long long at = (nprobe - 1) >= 64 ? cmin[1] : cmin[0];   // same choice in every lane
             const int src = (nprobe - 1) & 63;
             cut = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(at >> 32), src) << 32) |
@@ -740,7 +752,7 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
                 unsigned long long key[2];
                 key[0] = lane < c ? kq[lane] : ~0ull;
                 key[1] = (S == 2 && 64 + lane < c) ? kq[64 + lane] : ~0ull;
-                sort_across(key);
+                if (nprobe > 1) sort_across(key);   // (one probe: c == 1, the key sits in lane 0)
                 if (lane < nprobe) probes[(size_t)(q0 + wave) * nprobe + lane] = (int32_t)(key[0] & 0xffffffffu);
                 if (64 + lane < nprobe) probes[(size_t)(q0 + wave) * nprobe + 64 + lane] = (int32_t)(key[1] & 0xffffffffu);
             }
