@@ -67,6 +67,16 @@ def test_host_side_validation(L):
     assert L.trim_encode(None, 5, 128, None, 6, None, None, None) == -2
     assert L.trim_build_lut(None, 3, 128, None, 32, None, 0, None) == -1
     assert L.trim_ivf_probe(None, 3, 128, None, 16, 32, None, None) == -1   # nprobe > nlist
+    # sizes of caller-owned buffers (pure host functions)
+    assert L.trim_list_bounds_bytes(7, 32) == 7 * 2096     # 32 x 64 codes + 32 counts + 4, to 16
+    assert L.trim_list_bounds_bytes(0, 32) == 0 and L.trim_list_bounds_bytes(5, 0) == 0
+    small, large = L.trim_range_workspace_bytes(10, 1000), L.trim_range_workspace_bytes(10, 100_000)
+    assert small % 256 == 0 and large > small >= 10 * 1000 * 4   # a distance slot per candidate
+    assert L.trim_codes_tiled_bytes(100, 192) >= 100 * 192
+    # the list-summary and ceiling entry points refuse null buffers on the host
+    assert L.trim_pack_list_bounds(None, None, 4, None, None) == -1
+    assert L.trim_ceiling_lds_gather(0, 1, 1, 0, None, None) == -1
+    assert L.trim_ceiling_stream_read(None, 1024, 8, None, None) == -1
 
 
 def test_product_does_not_import_the_oracle():
