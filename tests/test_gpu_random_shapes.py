@@ -59,12 +59,31 @@ def draw_long(seed):
     return w, k, batch, first, gamma
 
 
-@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(22)])
+def draw_ivf_long(seed):
+    """Inverted lists with long candidate sequences: barrier-free stretches over many lists,
+    list summaries, probe selection by the library."""
+    r = np.random.default_rng([777, seed])
+    M = int(r.choice([16, 32, 64]))
+    dsub = int(r.choice([4, 8]))
+    n = int(r.integers(60_000, 200_000))
+    nlist = int(r.choice([16, 40, 100, 256]))
+    nprobe = int(r.integers(2, min(nlist, 70) + 1))
+    k = int(r.choice([1, 10, 64, 100]))
+    batch = int(r.choice([1, 16, 256, 1024]))
+    gamma = float(r.choice([0.0, 0.3, 0.6]))
+    law = str(r.choice(["clip255", "aniso01"]))
+    w = synth.scaled(synth.WORKLOADS[LAWS[law]], n, 6, d=M * dsub, M=M, nlist=nlist, nprobe=nprobe, k=k,
+                     ncomp=int(r.choice([8, 32, 128])), seed=5000 + seed, kmeans_iters=3)
+    return w, k, batch, 0, gamma
+
+
+@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(22)] + [2000 + s for s in range(10)])
 def test_random_configuration(oracle, seed):
     import torch
     from paper_2508_17828_amd import trim as T
     T.lib()
-    w, k, batch, first, gamma = draw(seed) if seed < 1000 else draw_long(seed - 1000)
+    w, k, batch, first, gamma = (draw(seed) if seed < 1000 else draw_long(seed - 1000) if seed < 2000
+                                 else draw_ivf_long(seed - 2000))
     b = helpers.build(w, pq_train_max=4096, ivf_train_per_list=32)
     ix = b.index
     t = lambda a: None if a is None else torch.from_numpy(a).cuda()
@@ -75,7 +94,7 @@ def test_random_configuration(oracle, seed):
         gi.scan_head = T.trim_pack_scan_head(gi.codes, gi.dlx)
     if w.M % 16 == 0 and seed % 2 == 0:
         gi.codes_tiled = T.trim_pack_codes_tiled(gi.codes)
-    if ix.list_offsets is not None and seed % 3 != 0:   # list-level pruning on in two draws of three
+    if ix.list_offsets is not None and (seed % 3 != 0 or seed >= 2000):   # list-level pruning on in two draws of three
         gi.list_bounds = T.trim_pack_list_bounds(gi)
     q, probes = t(b.queries), t(b.probes)
     what = f"seed {seed}: n={w.n} d={w.d} M={w.M} k={k} batch={batch} first={first} gamma={gamma} " \
