@@ -51,6 +51,7 @@ struct Plan {
 // fitted to the smallest footprint tier (most workgroups per CU) that holds it.
 constexpr int kSpanKnn = 1024;
 constexpr int kSpanRange = 4096;
+constexpr int kSpanLong = 4096;   // kNN span target when the table leaves one workgroup per CU anyway
 constexpr int kMaxBatchesPerSpan = 1024;
 constexpr int kPossMin = 512;    // smallest possibles list worth cruising with
 constexpr int kPossMax = 2048;
@@ -62,14 +63,12 @@ struct Tier { int threads; size_t lds; bool needs_6_waves; };
 constexpr Tier kTiers[] = {{256, 40960, false}, {512, 53760, true}, {512, 81920, false},
                            {1024, kLdsBytes, false}};
 
-bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
-    if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
-    const int nsegs = nseg > 0 ? nseg : 1;
-    int nbatch = (range ? kSpanRange : kSpanKnn) / batch;
-    if (nbatch < 1) nbatch = 1;
-    if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
-    const int span = nbatch * batch;
-    if (span > 65535) return false;
+// One attempt: table phases P, a footprint tier, a span; need_poss: only layouts with a possibles
+// list (a cruise) count.
+bool fit_plan(int d, int M, int nsegs, int cap, int batch, int k, bool range, int P, const Tier &tier,
+              int span, bool need_poss, Plan *pl) {
+    const int Mp = M / P;
+    const int nbatch = span / batch;
     // cruise stretches (kNN): up to 61440 candidates (16-bit queue entries).  Their possibles
     // are counted per bucket of `bucket` candidates (a whole number of batches, at most 1024
     // buckets).
@@ -79,74 +78,105 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     if (cruise / batch > 1024) bucket = batch * (((cruise + 1023) / 1024 + batch - 1) / batch);
     const int nbucket = cruise > 0 ? (cruise + bucket - 1) / bucket : 0;
     const int ncnt = nbucket > nbatch ? nbucket : nbatch;
+    const size_t tab = (size_t)Mp * kC * 4;
+    const bool can_cruise = cruise > 0 && P == 1;  // table phases need block-wide barriers
+    if (need_poss && !can_cruise) return false;
+    const int nwaves = tier.threads / 64;
+    // a wave's share of a span is rounded up to 64; two queue arrays of 16-bit entries
+    const int wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
+    size_t wq_min = (size_t)2 * nwaves * wqcap * 2;
+    if (can_cruise && wq_min < (size_t)nwaves * kRing * 4) wq_min = (size_t)nwaves * kRing * 4;
+    const size_t rest = tab + up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) +
+                        up16((size_t)nsegs * 4) + up16((size_t)(Mp / 4 + 1) * 4) +
+                        up16((size_t)nsegs * 8) +
+                        (range ? up16((size_t)cap * 4) : 0) +
+                        up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
+                        up16((size_t)ncnt * 4);
+    // The possibles list of a cruise stretch takes what is left, largest first.  Its
+    // capacity p also sizes the arrays of the stretch's replay: spos[] holds p entries,
+    // and the queue area holds p exact distances and p bounds (queues are only live
+    // while bounds are computed, distances and bounds only afterwards).
+    static const int kPossTry[] = {kPossMax, 1536, 1024, 768, kPossMin, 0};
+    for (int p : kPossTry) {
+        if (p > 0 && !can_cruise) continue;
+        if (p == 0 && need_poss) continue;
+        const int scap = cap > p ? cap : p;
+        size_t wq_bytes = wq_min;
+        if (wq_bytes < (size_t)(scap + p) * 4) wq_bytes = (size_t)(scap + p) * 4;
+        // a span that ends in a replay keeps up to min(scap, span) bounds behind the
+        // scap exact distances
+        const int span_poss = scap < span ? scap : span;
+        if (!range && wq_bytes < (size_t)(scap + span_poss) * 4) wq_bytes = (size_t)(scap + span_poss) * 4;
+        wq_bytes = up16(wq_bytes);
+        size_t plb = up16((size_t)span * 4);             // bounds of a span / the possibles list
+        if (plb < (size_t)p * 8) plb = (size_t)p * 8;
+        const size_t total = rest + up16((size_t)scap * 4) + plb + wq_bytes;
+        if (total > tier.lds) continue;
+        pl->P = P;
+        pl->Mp = Mp;
+        pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
+        size_t off = tab;
+        pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
+        pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
+        pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
+        pl->off_rest = (uint32_t)off; off += up16((size_t)(Mp / 4 + 1) * 4);
+        pl->off_seglb = (uint32_t)off; off += up16((size_t)nsegs * 8);
+        pl->off_spos = (uint32_t)off; off += up16((size_t)scap * 4);
+        pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
+        pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+        pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
+        pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
+        pl->off_plb = (uint32_t)off;  off += plb;
+        pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
+        pl->off_wq = (uint32_t)off;   off += wq_bytes;
+        pl->off_sd2 = pl->off_wq;
+        pl->span = span;
+        pl->lds = off;
+        pl->threads = tier.threads;
+        pl->wqcap = wqcap;
+        pl->cruise = p > 0 ? cruise : 0;
+        pl->poss_cap = p;
+        pl->scap = scap;
+        pl->rcap = (int)(wq_bytes / 4) - scap;
+        pl->bucket = bucket;
+        return true;
+    }
+    return false;
+}
+
+bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
+    if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
+    const int nsegs = nseg > 0 ? nseg : 1;
+    int nbatch = (range ? kSpanRange : kSpanKnn) / batch;
+    if (nbatch < 1) nbatch = 1;
+    if (nbatch > kMaxBatchesPerSpan) nbatch = kMaxBatchesPerSpan;
+    const int span = nbatch * batch;
+    if (span > 65535) return false;
+    constexpr int nt = (int)(sizeof(kTiers) / sizeof(kTiers[0]));
     for (int P = 1; P <= M / 4; ++P) {
-        if (M % P) continue;
-        const int Mp = M / P;
-        if (Mp % 4) continue;
-        const size_t tab = (size_t)Mp * kC * 4;
-        const bool can_cruise = cruise > 0 && P == 1;  // table phases need block-wide barriers
-        for (const Tier &tier : kTiers) {
+        if (M % P || (M / P) % 4) continue;
+        for (int t = 0; t < nt; ++t) {
+            const Tier &tier = kTiers[t];
             if (tier.needs_6_waves && (range || result_slots(k) != 1)) continue;
-            const int nwaves = tier.threads / 64;
-            // a wave's share of a span is rounded up to 64; two queue arrays of 16-bit entries
-            const int wqcap = ((span + nwaves - 1) / nwaves + 63) / 64 * 64;
-            size_t wq_min = (size_t)2 * nwaves * wqcap * 2;
-            if (can_cruise && wq_min < (size_t)nwaves * kRing * 4) wq_min = (size_t)nwaves * kRing * 4;
-            const size_t rest = tab + up16((size_t)d * 4) + up16((size_t)(nsegs + 1) * 4) +
-                                up16((size_t)nsegs * 4) + up16((size_t)(Mp / 4 + 1) * 4) +
-                                up16((size_t)nsegs * 8) +
-                                (range ? up16((size_t)cap * 4) : 0) +
-                                up16((size_t)kWave * result_slots(k) * 4) * 2 + up16(sizeof(Ctl)) +
-                                up16((size_t)ncnt * 4);
-            // The possibles list of a cruise stretch takes what is left, largest first.  Its
-            // capacity p also sizes the arrays of the stretch's replay: spos[] holds p entries,
-            // and the queue area holds p exact distances and p bounds (queues are only live
-            // while bounds are computed, distances and bounds only afterwards).
-            static const int kPossTry[] = {kPossMax, 1536, 1024, 768, kPossMin, 0};
-            for (int p : kPossTry) {
-                if (p > 0 && !can_cruise) continue;
-                if (p == 0 && can_cruise && tier.lds < kLdsBytes) continue;  // try the next tier first
-                const int scap = cap > p ? cap : p;
-                size_t wq_bytes = wq_min;
-                if (wq_bytes < (size_t)(scap + p) * 4) wq_bytes = (size_t)(scap + p) * 4;
-                // a span that ends in a replay keeps up to min(scap, span) bounds behind the
-                // scap exact distances
-                const int span_poss = scap < span ? scap : span;
-                if (!range && wq_bytes < (size_t)(scap + span_poss) * 4) wq_bytes = (size_t)(scap + span_poss) * 4;
-                wq_bytes = up16(wq_bytes);
-                size_t plb = up16((size_t)span * 4);             // bounds of a span / the possibles list
-                if (plb < (size_t)p * 8) plb = (size_t)p * 8;
-                const size_t total = rest + up16((size_t)scap * 4) + plb + wq_bytes;
-                if (total > tier.lds) continue;
-                pl->P = P;
-                pl->Mp = Mp;
-                pl->vec = (M % 16 == 0 && Mp % 16 == 0) ? 4 : (M % 8 == 0 && Mp % 8 == 0) ? 2 : 1;
-                size_t off = tab;
-                pl->off_q = (uint32_t)off;    off += up16((size_t)d * 4);
-                pl->off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
-                pl->off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
-                pl->off_rest = (uint32_t)off; off += up16((size_t)(Mp / 4 + 1) * 4);
-                pl->off_seglb = (uint32_t)off; off += up16((size_t)nsegs * 8);
-                pl->off_spos = (uint32_t)off; off += up16((size_t)scap * 4);
-                pl->off_sidx = (uint32_t)off; if (range) off += up16((size_t)cap * 4);
-                pl->off_rd2 = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
-                pl->off_rid = (uint32_t)off;  off += up16((size_t)kWave * result_slots(k) * 4);
-                pl->off_ctl = (uint32_t)off;  off += up16(sizeof(Ctl));
-                pl->off_plb = (uint32_t)off;  off += plb;
-                pl->off_cnt = (uint32_t)off;  off += up16((size_t)ncnt * 4);
-                pl->off_wq = (uint32_t)off;   off += wq_bytes;
-                pl->off_sd2 = pl->off_wq;
-                pl->span = span;
-                pl->lds = off;
-                pl->threads = tier.threads;
-                pl->wqcap = wqcap;
-                pl->cruise = p > 0 ? cruise : 0;
-                pl->poss_cap = p;
-                pl->scap = scap;
-                pl->rcap = (int)(wq_bytes / 4) - scap;
-                pl->bucket = bucket;
-                return true;
+            if (t + 1 < nt) {
+                // below the last tier a layout must leave room for a cruise when one is possible
+                // at all (else the next tier is tried first)
+                const bool cruise_possible = !range && P == 1 && 61440 / batch * batch >= 2 * span;
+                if (fit_plan(d, M, nsegs, cap, batch, k, range, P, tier, span, cruise_possible, pl)) return true;
+                continue;
             }
+            // One workgroup per CU whatever the span: kNN takes the longest span that fits (fewer
+            // barriers and more survivors per refine step on the span-by-span path), first among the
+            // layouts that keep a possibles list, then among those without.
+            if (!range) {
+                for (int pass = 0; pass < 2; ++pass)
+                    for (int target = kSpanLong; target > span; target -= 1024) {
+                        const int longer = target / batch * batch;
+                        if (longer <= span || longer / batch > kMaxBatchesPerSpan) continue;
+                        if (fit_plan(d, M, nsegs, cap, batch, k, range, P, tier, longer, pass == 0, pl)) return true;
+                    }
+            }
+            if (fit_plan(d, M, nsegs, cap, batch, k, range, P, tier, span, false, pl)) return true;
         }
     }
     return false;

@@ -51,7 +51,7 @@ WORKLOADS = {
                    nprobe=32, k=10, gammas=(0.0, 0.5, 0.8), batch=1024, seed=2),
     # 1M x 960 GIST-like shape, brute-force scan with pruning, k=100.
     "C3": Workload("C3", 1_000_000, 1_000, 960, 120, 512, "aniso01", k=100,
-                   gammas=(0.0, 0.7), batch=2048, seed=3),
+                   gammas=(0.0, 0.7), batch=512, seed=3),
     # 1M x 1536 unit-norm embeddings, IVF 1024 / nprobe 64, range search.
     "C4": Workload("C4", 1_000_000, 10_000, 1536, 192, 256, "unit", nlist=1024,
                    nprobe=64, mode="range", gammas=(0.0, 0.7), range_percentile=0.1,
