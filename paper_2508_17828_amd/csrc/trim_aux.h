@@ -831,33 +831,51 @@ __global__ __launch_bounds__(1024) void query_order_kernel(const int32_t *__rest
                                                            int32_t *__restrict__ order) {
     extern __shared__ __align__(16) unsigned char smem[];
     int *hist = reinterpret_cast<int *>(smem);  // [nbucket], then running cursors
-    __shared__ int part[1024];
+    __shared__ int part[16];
     const int tid = threadIdx.x, T = blockDim.x;
     for (int b = tid; b < nbucket; b += T) hist[b] = 0;
+    // the first kKeep queries of a thread stay in registers for both passes, their loads in flight together
+    constexpr int kKeep = 16;
+    uint32_t mine[kKeep];
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        const int64_t q = tid + (int64_t)i * T;
+        mine[i] = q < nq ? (uint32_t)probes[(size_t)q * nprobe] % (uint32_t)nbucket : 0xffffffffu;
+    }
     __syncthreads();
-    for (int64_t q = tid; q < nq; q += T) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i)
+        if (mine[i] != 0xffffffffu) atomicAdd(&hist[mine[i]], 1);
+    for (int64_t q = tid + (int64_t)kKeep * T; q < nq; q += T) {
         const uint32_t l = (uint32_t)probes[(size_t)q * nprobe];
         atomicAdd(&hist[l % (uint32_t)nbucket], 1);
     }
     __syncthreads();
-    // exclusive prefix over the buckets: each thread owns a contiguous run
+    // exclusive prefix over the buckets: each thread owns a contiguous run; the runs' sums are
+    // scanned inside each wave, then across the (at most 16) waves
     const int per = (nbucket + T - 1) / T;
     const int lo = tid * per < nbucket ? tid * per : nbucket;
     const int hi = lo + per < nbucket ? lo + per : nbucket;
     int sum = 0;
     for (int b = lo; b < hi; ++b) sum += hist[b];
-    part[tid] = sum;
-    __syncthreads();
-    for (int off = 1; off < T; off <<= 1) {
-        const int v = tid >= off ? part[tid - off] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
+    const int lane = tid & 63, wave = tid >> 6;
+    int incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
     }
-    int run = part[tid] - sum;
+    if (lane == 63) part[wave] = incl;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += part[w];
+    int run = before + incl - sum;
     for (int b = lo; b < hi; ++b) { const int c = hist[b]; hist[b] = run; run += c; }
     __syncthreads();
-    for (int64_t q = tid; q < nq; q += T) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i)
+        if (mine[i] != 0xffffffffu) order[atomicAdd(&hist[mine[i]], 1)] = (int32_t)(tid + i * T);
+    for (int64_t q = tid + (int64_t)kKeep * T; q < nq; q += T) {
         const uint32_t l = (uint32_t)probes[(size_t)q * nprobe];
         order[atomicAdd(&hist[l % (uint32_t)nbucket], 1)] = (int32_t)q;
     }
