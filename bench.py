@@ -6,7 +6,7 @@ coarse-probe selection, distance tables (built inside the scan kernel), lower-bo
 with pruning, exact refinement of survivors and top-k selection.  Inputs (index, queries)
 are resident in HBM before the timed region; results stay on the device.
 
-Prints ONE JSON line (see the design doc for the definition of every field).
+Prints ONE JSON line.
 """
 import argparse
 import json
@@ -136,7 +136,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
-              "(the path has no collective; see DESIGN.md, 'How it would shard')", file=sys.stderr)
+              "(the path has no collective: queries would simply be dealt out to the GPUs)", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
