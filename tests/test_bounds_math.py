@@ -68,3 +68,25 @@ def test_passing_over_a_list_is_implied_by_its_slack():
             b = np.float32(bmax * np.float32(rng.random()))
             r = np.float32(np.float64(b) * np.float64(c) + np.float64(st))      # one rounding: an fma
             assert lb > np.float32(r * r)
+
+
+def test_abandon_threshold_implies_the_bound_exceeds_tau(oracle):
+    """Once a table sum s exceeds (c b + c max(sqrt(tau), 1e-15))^2 as the kernel computes it, the
+    oracle's Equation 3 at that s (and at any larger s, any gamma >= 0) is above tau: abandoning
+    there prunes nobody the full evaluation would keep."""
+    rng = np.random.default_rng(14)
+    c = np.float32(1.000025)
+    checked = 0
+    for _ in range(4000):
+        b = np.float32(rng.random() * 10 ** rng.uniform(-3, 3))
+        tau = np.float32(rng.random() * 10 ** rng.uniform(-6, 6))
+        st = np.float32(c * max(np.float32(np.sqrt(tau)), np.float32(1e-15)))
+        r = np.float32(np.float64(b) * np.float64(c) + np.float64(st))
+        thr = np.float32(r * r)
+        for gamma in (0.0, 0.3, 1.0):
+            for mult in (1.0 + 1e-7, 1.0001, 1.5, 40.0):
+                s = np.nextafter(np.float32(thr * np.float32(mult)), np.float32(np.inf))
+                if s > thr:
+                    assert oracle.plb_from_s(s, b, gamma) > tau
+                    checked += 1
+    assert checked > 40000
