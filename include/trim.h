@@ -4,7 +4,8 @@
  * C ABI.  Every pointer marked "device" is HIP device memory on the current device, owned
  * by the caller for the whole call and until the work enqueued on `stream` has finished.
  * Pointers marked "host" are ordinary host memory read during the call only.  The library
- * keeps no state between calls, allocates no device memory and never synchronises: all
+ * keeps no state between calls (but see trim_search_range_static), allocates no device memory
+ * and never synchronises: all
  * work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream).
  *
  * Every function returns 0 on success or a negative trim_status; nothing is enqueued when
@@ -246,6 +247,29 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
                       int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                       int64_t mask_words, void *workspace, size_t workspace_bytes,
                       void *stream);
+
+/*
+ * trim_search_range for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same search with the same
+ * results, but the workspace is a fixed area of TRIM_STATIC_SCRATCH_BYTES bytes of device memory
+ * that belongs to the library (one copy per GPU, held from the library's first use on that GPU
+ * until the process ends).  The call allocates nothing and frees nothing.  It returns
+ * TRIM_WORKSPACE, with nothing enqueued, when trim_range_workspace_bytes(nq, max candidates)
+ * exceeds TRIM_STATIC_SCRATCH_BYTES (about 4.2 bytes per (query, candidate) pair: 32 MiB hold
+ * roughly 7.9 million pairs per call; split the query set to stay below).
+ * Every call on a GPU uses that GPU's one area: two calls whose work overlaps in time on the same
+ * GPU (different streams, or different host threads) race and give undefined results; calls
+ * ordered on one stream are safe.  The area keeps the previous call's contents; the call itself
+ * clears what it needs cleared.
+ */
+#define TRIM_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int trim_search_range_static(const trim_index_view *index, const float *queries, int64_t nq,
+                             const float *lut, const trim_candidates *cand, float radius, float gamma,
+                             int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                             int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
+                             int64_t mask_words, void *stream);
+/* TRIM_STATIC_SCRATCH_BYTES of the loaded library. */
+size_t trim_static_scratch_bytes(void);
 
 /* Bytes of workspace trim_search_range needs for nq queries with at most max_candidates
  * candidates each (index->n when there is no candidate structure): about 4.2 bytes per

@@ -6,9 +6,14 @@
 
 #include <cmath>
 #include <cstdio>
+#include <mutex>
 
 #include "trim_aux.h"
 #include "trim_search.h"
+
+// Scratch area of trim_search_range_static (see below): device memory inside the library's code
+// object; every GPU the library runs on holds its own copy at its own address.
+static __device__ __align__(256) unsigned char scratch[TRIM_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -313,6 +318,114 @@ RangeLayout range_layout(int64_t nq, int64_t max_cand) {
     return L;
 }
 
+// The scratch area lives from the first use of the library on a GPU until the process ends.
+// In host code the array's name is only a handle: its device address is asked for once per
+// device (hipGetSymbolAddress with that device current) and kept here; host code passes that
+// address, never the name, to kernels.
+constexpr size_t kScratchBytes = TRIM_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_for_current_device(void **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return TRIM_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return TRIM_HIP_ERROR;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TRIM_OK;
+}
+
+// The range search behind both entry points: `workspace` is the caller's buffer or this
+// device's copy of the static scratch area.
+int range_search(const trim_index_view *index, const float *queries, int64_t nq,
+                 const float *lut, const trim_candidates *cand, float radius, float gamma,
+                 int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                 int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
+                 int64_t mask_words, void *workspace, size_t workspace_bytes, void *stream) {
+    int rc = check_index(index);
+    if (rc) return rc;
+    if ((rc = check_cand(cand))) return rc;
+    if (nq < 0 || nq > TRIM_MAX_QUERIES || capacity < 0) return TRIM_INVALID_ARG;
+    if (!(gamma >= 0.0f) || std::isinf(gamma) || !(radius >= 0.0f)) return TRIM_INVALID_ARG;
+    if (!out_offsets) return TRIM_INVALID_ARG;
+    if (capacity > 0 && (!out_ids || !out_d2)) return TRIM_INVALID_ARG;
+    if (lut && !aligned16(lut)) return TRIM_INVALID_ARG;
+    if (!lut && !index->codebooks) return TRIM_INVALID_ARG;
+    if (survivor_mask && mask_words <= 0) return TRIM_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (nq == 0) {
+        if ((rc = fill_u32(reinterpret_cast<uint32_t *>(out_offsets), 2, 0u, st))) return rc;
+        if (required && (rc = fill_u32(reinterpret_cast<uint32_t *>(required), 2, 0u, st))) return rc;
+        return TRIM_OK;
+    }
+    if (!queries) return TRIM_INVALID_ARG;
+    int64_t max_cand = cand ? cand->max_candidates : index->n;
+    if (cand && max_cand <= 0) return TRIM_INVALID_ARG;  // needed to size the masks
+    const RangeLayout L = range_layout(nq, max_cand);
+    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return TRIM_WORKSPACE;
+    Plan pl;
+    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, kRangeRound, kRangeRound, 1, true, &pl))
+        return TRIM_UNSUPPORTED_SHAPE;
+
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    uint32_t *rmask = reinterpret_cast<uint32_t *>(ws);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.off_counts);
+    int64_t *cbase = reinterpret_cast<int64_t *>(ws + L.off_cbase);
+    float *rd2 = reinterpret_cast<float *>(ws + L.off_d2);
+
+    if ((rc = fill_u32(rmask, (size_t)nq * L.rmask_words, 0u, st))) return rc;
+    if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
+    if (stats && stats->n_exact && (rc = fill_u32(reinterpret_cast<uint32_t *>(stats->n_exact), (size_t)nq, 0u, st)))
+        return rc;
+
+    SearchArgs a{};
+    fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
+    a.k = 1; a.batch = kRangeRound; a.first_batch = kRangeRound;
+    a.radius2 = radius * radius;
+    a.chunk = L.chunk; a.nsplit = L.nsplit;
+    a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;
+    a.result_d2 = rd2;
+    if (a.max_cand > max_cand) a.max_cand = (int32_t)max_cand;
+
+    RangeFillArgs f{};
+    f.base = index->base; f.ids = index->ids; f.queries = queries;
+    f.list_offsets = a.list_offsets; f.probes = a.probes; f.n = index->n; f.d = index->d;
+    f.nlist = a.nlist; f.nseg = a.nseg; f.max_cand = a.max_cand; f.chunk = L.chunk;
+    f.nsplit = L.nsplit; f.result_mask = rmask; f.rmask_words = L.rmask_words; f.result_d2 = rd2;
+    f.chunk_base = cbase; f.out_ids = out_ids; f.out_d2 = out_d2; f.capacity = capacity;
+    const int nsegs = a.nseg > 0 ? a.nseg : 1;
+    size_t off = 0;
+    f.off_q = (uint32_t)off;    off += up16((size_t)index->d * 4);
+    f.off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
+    f.off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
+    f.off_list = (uint32_t)off; off += 2048 * 4;
+    const size_t fill_lds = off;
+
+    a.nq = nq;
+    const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
+    if (slots * pl.threads >= (int64_t(1) << 32)) return TRIM_INVALID_ARG;  // threads per launch
+    if ((rc = launch_search<kRange>(a, pl, dim3((unsigned)slots, (unsigned)L.nsplit), st))) return rc;
+    hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(1024), 0, st, counts, nq, L.nsplit, cbase,
+                       out_offsets, required);
+    HIP_TRY(hipGetLastError());
+    if (capacity > 0) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(range_fill_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)fill_lds));
+        hipLaunchKernelGGL(range_fill_kernel, dim3((unsigned)nq, (unsigned)L.nsplit), dim3(256), fill_lds,
+                           st, f);
+        HIP_TRY(hipGetLastError());
+    }
+    return TRIM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -589,82 +702,30 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
                       int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
                       int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                       int64_t mask_words, void *workspace, size_t workspace_bytes, void *stream) {
-    int rc = check_index(index);
-    if (rc) return rc;
-    if ((rc = check_cand(cand))) return rc;
-    if (nq < 0 || nq > TRIM_MAX_QUERIES || capacity < 0) return TRIM_INVALID_ARG;
-    if (!(gamma >= 0.0f) || std::isinf(gamma) || !(radius >= 0.0f)) return TRIM_INVALID_ARG;
-    if (!out_offsets) return TRIM_INVALID_ARG;
-    if (capacity > 0 && (!out_ids || !out_d2)) return TRIM_INVALID_ARG;
-    if (lut && !aligned16(lut)) return TRIM_INVALID_ARG;
-    if (!lut && !index->codebooks) return TRIM_INVALID_ARG;
-    if (survivor_mask && mask_words <= 0) return TRIM_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (nq == 0) {
-        if ((rc = fill_u32(reinterpret_cast<uint32_t *>(out_offsets), 2, 0u, st))) return rc;
-        if (required && (rc = fill_u32(reinterpret_cast<uint32_t *>(required), 2, 0u, st))) return rc;
-        return TRIM_OK;
-    }
-    if (!queries) return TRIM_INVALID_ARG;
-    int64_t max_cand = cand ? cand->max_candidates : index->n;
-    if (cand && max_cand <= 0) return TRIM_INVALID_ARG;  // needed to size the masks
-    const RangeLayout L = range_layout(nq, max_cand);
-    if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
-        return TRIM_WORKSPACE;
-    Plan pl;
-    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, kRangeRound, kRangeRound, 1, true, &pl))
-        return TRIM_UNSUPPORTED_SHAPE;
-
-    unsigned char *ws = static_cast<unsigned char *>(workspace);
-    uint32_t *rmask = reinterpret_cast<uint32_t *>(ws);
-    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.off_counts);
-    int64_t *cbase = reinterpret_cast<int64_t *>(ws + L.off_cbase);
-    float *rd2 = reinterpret_cast<float *>(ws + L.off_d2);
-
-    if ((rc = fill_u32(rmask, (size_t)nq * L.rmask_words, 0u, st))) return rc;
-    if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
-    if (stats && stats->n_exact && (rc = fill_u32(reinterpret_cast<uint32_t *>(stats->n_exact), (size_t)nq, 0u, st)))
-        return rc;
-
-    SearchArgs a{};
-    fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
-    a.k = 1; a.batch = kRangeRound; a.first_batch = kRangeRound;
-    a.radius2 = radius * radius;
-    a.chunk = L.chunk; a.nsplit = L.nsplit;
-    a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;
-    a.result_d2 = rd2;
-    if (a.max_cand > max_cand) a.max_cand = (int32_t)max_cand;
-
-    RangeFillArgs f{};
-    f.base = index->base; f.ids = index->ids; f.queries = queries;
-    f.list_offsets = a.list_offsets; f.probes = a.probes; f.n = index->n; f.d = index->d;
-    f.nlist = a.nlist; f.nseg = a.nseg; f.max_cand = a.max_cand; f.chunk = L.chunk;
-    f.nsplit = L.nsplit; f.result_mask = rmask; f.rmask_words = L.rmask_words; f.result_d2 = rd2;
-    f.chunk_base = cbase; f.out_ids = out_ids; f.out_d2 = out_d2; f.capacity = capacity;
-    const int nsegs = a.nseg > 0 ? a.nseg : 1;
-    size_t off = 0;
-    f.off_q = (uint32_t)off;    off += up16((size_t)index->d * 4);
-    f.off_segp = (uint32_t)off; off += up16((size_t)(nsegs + 1) * 4);
-    f.off_segd = (uint32_t)off; off += up16((size_t)nsegs * 4);
-    f.off_list = (uint32_t)off; off += 2048 * 4;
-    const size_t fill_lds = off;
-
-    a.nq = nq;
-    const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
-    if (slots * pl.threads >= (int64_t(1) << 32)) return TRIM_INVALID_ARG;  // threads per launch
-    if ((rc = launch_search<kRange>(a, pl, dim3((unsigned)slots, (unsigned)L.nsplit), st))) return rc;
-    hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(1024), 0, st, counts, nq, L.nsplit, cbase,
-                       out_offsets, required);
-    HIP_TRY(hipGetLastError());
-    if (capacity > 0) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(range_fill_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)fill_lds));
-        hipLaunchKernelGGL(range_fill_kernel, dim3((unsigned)nq, (unsigned)L.nsplit), dim3(256), fill_lds,
-                           st, f);
-        HIP_TRY(hipGetLastError());
-    }
-    return TRIM_OK;
+    return range_search(index, queries, nq, lut, cand, radius, gamma, out_offsets, out_ids, out_d2,
+                        capacity, required, stats, survivor_mask, mask_words, workspace,
+                        workspace_bytes, stream);
 }
+
+int trim_search_range_static(const trim_index_view *index, const float *queries, int64_t nq,
+                             const float *lut, const trim_candidates *cand, float radius, float gamma,
+                             int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                             int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
+                             int64_t mask_words, void *stream) {
+    // refuse what does not fit before anything else: no device call has been made yet
+    if (nq > 0 && index) {
+        const int64_t max_cand = cand ? cand->max_candidates : index->n;
+        if (max_cand >= 0 && nq <= TRIM_MAX_QUERIES && range_layout(nq, max_cand).total > kScratchBytes)
+            return TRIM_WORKSPACE;
+    }
+    void *ws = nullptr;
+    const int rc = scratch_for_current_device(&ws);
+    if (rc) return rc;
+    return range_search(index, queries, nq, lut, cand, radius, gamma, out_offsets, out_ids, out_d2,
+                        capacity, required, stats, survivor_mask, mask_words, ws, kScratchBytes, stream);
+}
+
+size_t trim_static_scratch_bytes(void) { return kScratchBytes; }
 
 int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *centroids,
                    int32_t nlist, int32_t nprobe, int32_t *probes_out, void *stream) {
@@ -720,7 +781,7 @@ const char *trim_strerror(int status) {
         case TRIM_OK: return "ok";
         case TRIM_INVALID_ARG: return "invalid argument";
         case TRIM_UNSUPPORTED_SHAPE: return "unsupported shape (d, M) for this build";
-        case TRIM_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TRIM_WORKSPACE: return "workspace missing, misaligned or too small (trim_search_range_static: the search needs more than TRIM_STATIC_SCRATCH_BYTES)";
         case TRIM_HIP_ERROR: return "HIP call failed (see trim_last_hip_error)";
         default: return "unknown status";
     }

@@ -22,7 +22,7 @@ TRIM_MAX_NPROBE = 4096
 
 EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
-           "trim_search_range", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
+           "trim_search_range", "trim_search_range_static", "trim_static_scratch_bytes", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_list_bounds_bytes", "trim_pack_list_bounds",
            "trim_ceiling_stream_read", "trim_ceiling_lds_gather",
            "trim_strerror", "trim_last_hip_error", "trim_version")
@@ -103,6 +103,8 @@ def lib() -> C.CDLL:
                                         C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+        L.trim_search_range_static.argtypes = L.trim_search_range.argtypes[:15] + [C.c_void_p]
+        L.trim_static_scratch_bytes.restype = C.c_size_t
         L.trim_ivf_probe.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                      C.c_int32, C.c_void_p, C.c_void_p]
         _lib = L
@@ -308,16 +310,17 @@ def trim_range_workspace_bytes(nq: int, max_candidates: int) -> int:
 def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma: float,
                       probes: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
                       capacity: int = 0, want_stats: bool = True, want_mask: bool = False,
-                      workspace: Optional[torch.Tensor] = None):
+                      workspace: Optional[torch.Tensor] = None, static_scratch: bool = False):
     """CSR results in scan order: dict(offsets [nq+1] int64, ids, d2, n_scanned, n_exact, mask).
 
     Synchronises once to read the result count; raises TrimCapacityError if a caller-given
-    capacity is too small (capacity 0 = size the buffers from a first counting call)."""
+    capacity is too small (capacity 0 = size the buffers from a first counting call).
+    static_scratch: call trim_search_range_static (the library's own scratch area, no workspace)."""
     nq = queries.shape[0]
     dev = queries.device
     cand, mc = index._cand(probes)
     need = trim_range_workspace_bytes(nq, mc)
-    if workspace is None:
+    if workspace is None and not static_scratch:
         workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
     offsets = torch.empty((nq + 1,), dtype=torch.int64, device=dev)
     required = torch.zeros((1,), dtype=torch.int64, device=dev)
@@ -335,6 +338,15 @@ def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma:
     view = index._view()
 
     def call(cap, oi, od):
+        if static_scratch:
+            _check(lib().trim_search_range_static(
+                C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
+                _ptr(lut, torch.float32, "lut"), C.byref(cand) if cand is not None else None,
+                radius, gamma, _ptr(offsets, torch.int64, "offsets"), _ptr(oi, torch.int32, "out_ids"),
+                _ptr(od, torch.float32, "out_d2"), cap, _ptr(required, torch.int64, "required"),
+                C.byref(stats) if stats is not None else None, _ptr(mask, torch.int32, "mask"), mw,
+                _stream()), "trim_search_range_static")
+            return
         _check(lib().trim_search_range(
             C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
             _ptr(lut, torch.float32, "lut"), C.byref(cand) if cand is not None else None,
