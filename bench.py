@@ -2,15 +2,22 @@
 """Benchmark of the TRIM filter-then-refine scan on one MI355X.
 
 A step = one pass of the whole hot path over the full query batch of the workload:
-coarse-probe selection, distance tables (built inside the scan kernel), lower-bound scan
-with pruning, exact refinement of survivors and top-k selection.  Inputs (index, queries)
-are resident in HBM before the timed region; results stay on the device.
+coarse-probe selection, query ordering, distance tables (built inside the scan kernel), lower-
+bound scan with pruning, exact refinement of survivors and top-k selection (range workloads:
+radius filter and CSR output).  Inputs (index, queries) are resident in HBM before the timed
+region; results stay on the device.
 
-Prints ONE JSON line.
+Every number in the printed line is produced in this run: kernel times by HIP events on the
+launch stream, what the kernel touched by its own work counters (one untimed launch), the two
+machine ceilings it is priced against (streaming read, table lookups out of LDS) by the
+library's measurement aids, recall / average precision against ground truth from the CPU oracle,
+and the oracle's own speed on the host cores.  Prints ONE JSON line.
 """
 import argparse
+import ctypes
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -19,6 +26,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# LDS peak derived from the chip's unit counts: 256 CUs x 128 bytes per clock x 2.4 GHz; a table
+# lookup moves 4 bytes.
+LDS_PEAK_GLOOKUPS = 256 * 128 * 2.4 / 4
 
 
 def parse():
@@ -26,109 +36,272 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", help="C1..C5 (default C2, the headline config)")
+    ap.add_argument("--workload", default="C2", help="C1..C5, T384, W768 (default C2, the headline config)")
     ap.add_argument("--gamma", type=float, default=None,
                     help="relaxation to time (default: largest swept gamma with recall@k >= 0.95)")
     ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--first-batch", type=int, default=None,
-                    help="size of the first batch; later ones double up to --batch (0: all alike)")
-    ap.add_argument("--truth-queries", type=int, default=1000,
-                    help="queries used for the exact ground truth behind recall@k")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0,
-                    help="CPU time budget for timing the oracle (0 = skip)")
+    ap.add_argument("--truth-queries", type=int, default=0,
+                    help="queries behind recall / average precision (0: sized so that the oracle's "
+                         "exact search over all n takes about ten seconds)")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0,
+                    help="CPU time budget for timing the oracle on all threads (0 = skip); the "
+                         "single-thread figure gets half of it on top")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-order", action="store_true", help="do not sort queries by first probed list")
     ap.add_argument("--no-list-bounds", action="store_true",
-                    help="do not give the search the per-list summaries (no list-level pruning)")
+                    help="time the search without the per-list summaries only (no list-level pruning)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the machine-ceiling measurements")
     return ap.parse_args()
 
 
-def bench_range(args, w, bw, probes_for, setup_s):
-    """Range-search workloads (Section 2.1, range search): a step = probe selection + the fused
-    table / scan / refine / radius filter + the CSR fill, for the whole query set."""
+def _event_ms(fn, reps):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def machine_ceilings(trim):
+    """Streaming-read rate of HBM and table-lookup rate of LDS, by the library's aids, now."""
+    import torch
+    size = 2 << 30
+    buf = torch.empty(size // 4, dtype=torch.int32, device="cuda").random_()
+    sink = torch.empty(8192, dtype=torch.int32, device="cuda")
+    read = max(size / (_event_ms(lambda: trim.trim_ceiling_stream_read(buf, blocks, sink), 5) * 1e-3) / 1e9
+               for blocks in (1024, 2048, 4096))
+    del buf
+    iters = 1024
+    fsink = torch.empty(1024 * 512, dtype=torch.float32, device="cuda")
+    look = max(blocks * 512 * iters * 32 / (_event_ms(
+        lambda: trim.trim_ceiling_lds_gather(blocks, iters, 12345, fsink), 5) * 1e-3) / 1e9
+        for blocks in (768, 1024))
+    return dict(stream_read_GBps=round(read, 1), lds_random_lookup_Glookups=round(look, 1))
+
+
+def host_index(trim_oracle, ix, centroids):
+    h = lambda t: None if t is None else t.cpu().numpy()
+    return trim_oracle.Index(h(ix.base), h(ix.codes), h(ix.dlx), h(ix.codebooks), ids=h(ix.ids),
+                             list_offsets=h(ix.list_offsets), centroids=h(centroids))
+
+
+def set_threads(n):
+    """Threads of the oracle's OpenMP loops (the runtime's own call; the oracle is not touched)."""
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+
+
+def time_oracle(fn_chunk, nq, budget_s, chunk):
+    """Run fn_chunk(lo, hi) -> bool (same as the GPU's?) over the query set in order, wrapping
+    around, until the time budget is used.  Returns (queries done, seconds, all equal)."""
+    done, used, same = 0, 0.0, True
+    while used < budget_s:
+        lo = done % nq
+        hi = min(nq, lo + chunk)
+        t1 = time.perf_counter()
+        ok = fn_chunk(lo, hi)
+        used += time.perf_counter() - t1
+        same = same and ok
+        done += hi - lo
+    return done, used, same
+
+
+def truth_count(args, w):
+    if args.truth_queries > 0:
+        return min(args.truth_queries, w.nq)
+    # the oracle's exact search costs about n*d multiply-adds per query in float64
+    return int(max(50, min(1000, w.nq, 1.0e11 / (w.n * w.d))))
+
+
+def work_totals(trim, work):
+    tot = work.to(dtype=__import__("torch").int64).sum(0).tolist()
+    return {name: int(tot[i]) for i, name in enumerate(trim.WORK_NAMES)}
+
+
+def touched_bytes(w, nq, k_or_results, wt, use_lut):
+    """Bytes the launch requested from memory, by the kernel's own counters: codes / scan heads /
+    landmark distances / list summaries, raw rows (+ id) of every exact distance, the query, the
+    PQ centroids (or the prebuilt table) behind each query's distance table, the results."""
+    table_src = nq * (w.M * 1024 if use_lut else w.d * 256 * 4)
+    return dict(codes=wt["code_bytes"], rows=wt["rows"] * (4 * w.d + 4), queries=nq * 4 * w.d,
+                table_source=table_src, results=k_or_results * 8,
+                total=wt["code_bytes"] + wt["rows"] * (4 * w.d + 4) + nq * 4 * w.d + table_src + k_or_results * 8)
+
+
+def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel):
+    """The dominant kernel against the resource that binds it.  Long codes streamed once per
+    query are bound by HBM; short codes shared by many queries through the caches are bound by
+    the rate of table lookups out of LDS."""
+    sec = scan_ms * 1e-3
+    alg = alg_bytes / sec / 1e9
+    tch = touched["total"] / sec / 1e9
+    looks = wt["lookups"] / sec / 1e9
+    hbm = dict(algorithmic_bytes=alg_bytes, algorithmic_GBps=round(alg, 1),
+               algorithmic_frac_of_peak=round(alg / HBM_PEAK_GBS, 4),
+               touched_bytes=touched, touched_GBps=round(tch, 1),
+               touched_frac_of_peak=round(tch / HBM_PEAK_GBS, 4), peak_GBps=HBM_PEAK_GBS,
+               stream_read_ceiling_GBps=ceil.get("stream_read_GBps"),
+               note="algorithmic = (M+4) B per scanned candidate + (4d+4) B per exact distance + query "
+                    "and results, no reuse assumed; touched = what the kernel requested (its work "
+                    "counters), part of it served by the caches; bytes beyond L2 are in profiles/")
+    lds = dict(lookups=wt["lookups"], Glookups_per_s=round(looks, 1), peak_Glookups=LDS_PEAK_GLOOKUPS,
+               frac_of_peak=round(looks / LDS_PEAK_GLOOKUPS, 4),
+               random_lookup_ceiling_Glookups=ceil.get("lds_random_lookup_Glookups"),
+               frac_of_random_lookup_ceiling=(round(looks / ceil["lds_random_lookup_Glookups"], 4)
+                                              if ceil.get("lds_random_lookup_Glookups") else None),
+               note="peak = 256 CUs x 128 B/clk x 2.4 GHz / 4 B; the ceiling is the scan's own lookup-and-"
+                    "add sequence on random byte codes with nothing else going on (bank conflicts), "
+                    "measured in this run")
+    f_hbm = min(alg, tch) / HBM_PEAK_GBS     # never credit more than what was requested
+    f_lds = looks / (ceil.get("lds_random_lookup_Glookups") or LDS_PEAK_GLOOKUPS)
+    if alg <= HBM_PEAK_GBS and f_hbm >= f_lds:
+        head = dict(bound="hbm", achieved=round(alg, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(alg / HBM_PEAK_GBS, 4))
+    else:
+        head = dict(bound="lds", achieved=round(looks, 1), peak=LDS_PEAK_GLOOKUPS, unit="Glookup/s",
+                    frac=round(looks / LDS_PEAK_GLOOKUPS, 4))
+    head.update(traffic=None, kernel=kernel, kernel_ms=round(scan_ms, 4), hbm=hbm, lds=lds, work=wt,
+                candidates_per_s=dict(
+                    counted=round((wt["first_pass"] + wt["skipped"]) / sec, 1),
+                    read=round(wt["first_pass"] / sec, 1),
+                    note="counted = every candidate of Section 4.2's scan; read = those whose code was "
+                         "looked at (the rest were passed over with their whole list)"))
+    return head
+
+
+def timed_steps(args, step_fn):
+    """W warm-up steps, then K timed steps bracketed by synchronisation; per-step events at the
+    step's start, before the search launch and at its end."""
+    import torch
+    for _ in range(args.warmup):
+        step_fn(None)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step_fn(ev[s])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    steps = [e[0].elapsed_time(e[2]) for e in ev]
+    scans = [e[1].elapsed_time(e[2]) for e in ev]
+    return dict(ms_per_step=max(wall_ms, sum(steps) / len(steps)), step_median=statistics.median(steps),
+                scan_mean=sum(scans) / len(scans), scan_median=statistics.median(scans))
+
+
+def bench_range(args, w, bw, probes_for, setup_s, ceil):
+    """Range-search workloads (Section 2.1, range search): a step = probe selection + tables +
+    the fused scan / refine / radius filter + offsets + the CSR fill, for the whole query set."""
     import numpy as np
     import torch
+    from oracle import trim_oracle
     from paper_2508_17828_amd import synth, trim
     ix, queries, nq = bw.index, bw.queries, w.nq
+    oix = host_index(trim_oracle, ix, bw.centroids)
+    qh = queries.cpu().numpy()
     # one global radius: the stated percentile of seeded (query, base) pair distances
     qi, bi = synth.pair_sample(w, 256, 10_000)
-    qs = queries[torch.from_numpy(qi).cuda()].double()
-    xs = ix.base[torch.from_numpy(np.sort(bi)).cuda()].double()
+    qs = qh[qi].astype(np.float64)
+    xs = oix.base[np.sort(bi)].astype(np.float64)
     d2 = (qs * qs).sum(1)[:, None] - 2 * qs @ xs.T + (xs * xs).sum(1)[None, :]
-    radius = float(torch.quantile(d2.clamp_min(0).flatten()[:16_000_000].float(),
-                                  w.range_percentile / 100).sqrt().item())
-    # ground truth on a query subset: the strict scan (gamma = 0 loses nothing) over ALL n
-    nt = min(args.truth_queries, nq, 200)
-    truth = trim.trim_search_range(ix, queries[:nt].contiguous(), radius, 0.0) if nt else None
+    radius = float(np.sqrt(max(np.percentile(d2, w.range_percentile), 0.0)))
+    # ground truth on a query subset: Section 2.1's definition over ALL n by the oracle's exact distance
+    nt = truth_count(args, w)
+    r2 = np.float32(radius) * np.float32(radius)
+    pos_all = np.arange(w.n, dtype=np.int64)
+    id_of = oix.ids if oix.ids is not None else np.arange(w.n, dtype=np.int32)
+    truth = [id_of[trim_oracle.exact_pairs(oix.base, qh, np.full(w.n, q, np.int64), pos_all) <= r2]
+             for q in range(nt)]
     rows = []
     gammas = [args.gamma] if args.gamma is not None else sorted(set(w.gammas))
     for g in gammas:
-        pr = probes_for(queries)
-        r = trim.trim_search_range(ix, queries, radius, g, probes=pr)
-        ap = None
-        if nt:   # average precision of Section 2.1: |R intersect R'| / |R'| over the queries with R' nonempty
-            to, ti = truth["offsets"].cpu().numpy(), truth["ids"].cpu().numpy()
-            go, gi = r["offsets"].cpu().numpy(), r["ids"].cpu().numpy()
-            vals = [len(np.intersect1d(ti[to[q]:to[q + 1]], gi[go[q]:go[q + 1]])) / (to[q + 1] - to[q])
-                    for q in range(nt) if to[q + 1] > to[q]]
-            ap = round(float(np.mean(vals)), 4) if vals else None
+        r = trim.trim_search_range(ix, queries, radius, g, probes=probes_for(queries))
+        go, gi = r["offsets"].cpu().numpy(), r["ids"].cpu().numpy()
+        # average precision of Section 2.1: |R'| / |R| over the queries with R nonempty (R' is a subset of R)
+        vals = [len(np.intersect1d(truth[q], gi[go[q]:go[q + 1]])) / len(truth[q])
+                for q in range(nt) if len(truth[q])]
         scanned, exact = int(r["n_scanned"].sum().item()), int(r["n_exact"].sum().item())
-        rows.append(dict(gamma=g, average_precision=ap, results=r["required"],
-                         pruning_ratio=round(1 - exact / max(1, scanned), 5), n_scanned=scanned,
-                         n_exact=exact))
+        rows.append(dict(gamma=g, average_precision=round(float(np.mean(vals)), 4) if vals else None,
+                         results=r["required"], pruning_ratio=round(1 - exact / max(1, scanned), 5),
+                         n_scanned=scanned, n_exact=exact))
     ok = [x for x in rows if x["average_precision"] is not None and x["average_precision"] >= 0.95]
     chosen = max(ok, key=lambda x: x["gamma"]) if ok else rows[0]
     gamma = chosen["gamma"]
     cap = max(1, chosen["results"])
-    cand, mc = ix._cand(probes_for(queries))
+    _, mc = ix._cand(probes_for(queries))
     ws = torch.empty((trim.trim_range_workspace_bytes(nq, mc),), dtype=torch.uint8, device="cuda")
-    for _ in range(args.warmup):
-        trim.trim_search_range(ix, queries, radius, gamma, probes=probes_for(queries), capacity=cap,
-                               want_stats=False, workspace=ws)
-    torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    t_start = time.perf_counter()
     # A table that does not fit the LDS in one piece (M > 128) is refilled for every span of
     # candidates: then the tables are built once per step by trim_build_lut and copied from there.
     use_lut = w.M * 1024 > 128 * 1024
     lut_buf = torch.empty((nq, w.M, 256), dtype=torch.float32, device="cuda") if use_lut else None
-    for s in range(args.steps):
-        ev[s][0].record()
+    last = {}
+
+    def step(ev):
+        if ev: ev[0].record()
         pr = probes_for(queries)
-        ev[s][1].record()
         lut = trim.trim_build_lut(queries, ix.codebooks, out=lut_buf) if use_lut else None
-        trim.trim_search_range(ix, queries, radius, gamma, probes=pr, capacity=cap, want_stats=False,
-                               workspace=ws, lut=lut)
-        ev[s][2].record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_start) * 1e3 / args.steps
-    step_ms = sum(e[0].elapsed_time(e[2]) for e in ev) / args.steps
-    scan_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
-    ms_per_step = max(wall_ms, step_ms)
+        if ev: ev[1].record()
+        last["r"] = trim.trim_search_range(ix, queries, radius, gamma, probes=pr, capacity=cap,
+                                           want_stats=False, workspace=ws, lut=lut)
+        if ev: ev[2].record()
+
+    t = timed_steps(args, step)
+    got = last["r"]
+    # what the launch touched (one untimed launch with the work counters)
+    lut = trim.trim_build_lut(queries, ix.codebooks, out=lut_buf) if use_lut else None
+    acc = trim.trim_search_range(ix, queries, radius, gamma, probes=probes_for(queries), capacity=cap,
+                                 workspace=ws, lut=lut, want_work=True)
+    wt = work_totals(trim, acc["work"])
+    touched = touched_bytes(w, nq, chosen["results"], wt, use_lut)
     alg_bytes = (chosen["n_scanned"] * (w.M + 4) + chosen["n_exact"] * (4 * w.d + 4) + nq * 4 * w.d +
                  chosen["results"] * 8 + (nq + 1) * 8)
-    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+    roof = roofline_object(w, nq, t["scan_mean"], alg_bytes, wt, touched, ceil,
+                           "search_kernel<range> + range_offsets_kernel + range_fill_kernel")
+
+    # ---- CPU baseline: the oracle on a bounded sample, results compared with the GPU's ----
+    cpu = None
+    if args.cpu_seconds > 0:
+        go, gi = got["offsets"].cpu().numpy(), got["ids"].cpu().numpy()
+        ch = oix.centroids
+
+        def chunk(lo, hi):
+            qs_ = np.ascontiguousarray(qh[lo:hi])
+            ph = trim_oracle.ivf_probe(qs_, ch, w.nprobe) if w.nlist else None
+            ro = trim_oracle.search_range(oix, qs_, radius, gamma, ph)
+            return bool(np.array_equal(ro["ids"], gi[go[lo]:go[hi]]) and
+                        np.array_equal(ro["offsets"], go[lo:hi + 1] - go[lo]))
+
+        nthr = trim_oracle.num_threads()
+        done, used, same = time_oracle(chunk, nq, args.cpu_seconds, min(nq, 4 * nthr))
+        set_threads(1)
+        done1, used1, same1 = time_oracle(chunk, nq, args.cpu_seconds / 2, 2)
+        set_threads(nthr)
+        cpu = dict(value=round(done / used, 2), unit="queries/s", cores=nthr, kind="oracle",
+                   sample=f"{done} queries (the query set in order) in {used:.1f} s: probe selection + range "
+                          f"scan, same index, radius and gamma; result ids equal to the GPU's: {same}",
+                   single_thread=dict(value=round(done1 / used1, 2), unit="queries/s", cores=1,
+                                      sample=f"{done1} queries in {used1:.1f} s; ids equal: {same1}"))
     return {
         "metric": "queries/sec at average precision>=0.95 (1 MI355X); pruning ratio; scan HBM GB/s",
-        "value": round(nq / (ms_per_step * 1e-3), 1), "unit": "queries/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "value": round(nq / (t["ms_per_step"] * 1e-3), 1), "unit": "queries/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(t["ms_per_step"], 4),
+        "ms_per_step_median": round(t["step_median"], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n} base x {nq} queries, d={w.d}, PQ M={w.M}x256, "
                                f"IVF nlist={w.nlist} nprobe={w.nprobe}, range search, radius at the "
                                f"{w.range_percentile} th percentile of sampled pair distances",
                    "gamma": gamma, "radius": round(radius, 6), "average_precision": chosen["average_precision"],
-                   "truth": f"strict range search over all n for the first {nt} queries",
+                   "truth": f"all vectors within the radius by the CPU oracle's exact distance over all n, "
+                            f"first {nt} queries",
                    "pruning_ratio": chosen["pruning_ratio"], "results": chosen["results"],
-                   "timed": "probe selection + fused table/scan/refine/filter + offsets + CSR fill "
+                   "timed": "probe selection + tables + fused scan/refine/filter + offsets + CSR fill "
                             "(one host read of the result count per step), inputs in HBM",
                    "setup_s": round(setup_s, 1)},
-        "roofline": dict(bound="hbm", kernel="search_kernel<range> + range_fill_kernel",
-                         achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                         frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
-                         kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
-                         candidates_per_s=round(chosen["n_scanned"] / (scan_ms * 1e-3), 1)),
-        "cpu_baseline": None, "sweep": rows,
+        "roofline": roof, "cpu_baseline": cpu, "ceilings": ceil, "sweep": rows,
     }
 
 
@@ -149,170 +322,137 @@ def main():
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
     batch = args.batch or w.batch
-    first_batch = min(batch, w.first_batch if args.first_batch is None else args.first_batch)
     t0 = time.time()
-    bw = index_setup.build_workload(w, list_bounds=not args.no_list_bounds)
+    bw = index_setup.build_workload(w)
     ix, queries = bw.index, bw.queries
     torch.cuda.synchronize()
     setup_s = time.time() - t0
     nq, k = w.nq, w.k
+    ceil = {} if args.no_ceilings else machine_ceilings(trim)
 
     def probes_for(q):
         return trim.trim_ivf_probe(q, bw.centroids, w.nprobe) if w.nlist else None
 
     if w.mode == "range":
-        print(json.dumps(bench_range(args, w, bw, probes_for, setup_s)))
+        print(json.dumps(bench_range(args, w, bw, probes_for, setup_s, ceil)))
         return
 
-    # ---- ground truth on a query subset: exact kNN over ALL n by the strict scan (gamma = 0
-    # never prunes a true neighbour), no candidate structure ----
-    nt = min(args.truth_queries, nq)
-    truth = None
-    if nt > 0:
-        truth = trim.trim_search_knn(ix, queries[:nt].contiguous(), k, 0.0, 4096,
-                                     want_stats=False)["ids"]
+    from oracle import trim_oracle
+    oix = host_index(trim_oracle, ix, bw.centroids)
+    qh = queries.cpu().numpy()
+
+    # ---- ground truth on a query subset: exact kNN over ALL n in float64 by the CPU oracle ----
+    nt = truth_count(args, w)
+    t1 = time.time()
+    truth_ids, _ = trim_oracle.brute_knn_f64(oix.base, np.ascontiguousarray(qh[:nt]), k, ids=oix.ids)
+    truth = torch.from_numpy(truth_ids).cuda()
+    truth_s = time.time() - t1
+
+    import dataclasses
+    ix_plain = dataclasses.replace(ix, list_bounds=None)     # the same index without list summaries
 
     def order_for(pr):
         return trim.trim_query_order(pr, w.nlist) if pr is not None and not args.no_order else None
 
-    def run_once(gamma, want_stats=True):
+    def run_once(index, gamma, **kw):
         pr = probes_for(queries)
-        return trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, first_batch=first_batch, want_stats=want_stats,
-                                    query_order=order_for(pr))
+        return trim.trim_search_knn(index, queries, k, gamma, batch, probes=pr, query_order=order_for(pr), **kw)
 
-    # ---- sweep of the relaxation parameter (untimed quality numbers, short timing) ----
+    # ---- sweep of the relaxation parameter (quality numbers; short timing) ----
     sweep = []
     gammas = sorted(set(list(w.gammas) + ([] if args.no_sweep else [0.2, 0.3, 0.4, 0.45, 0.6, 0.7])))
     if args.gamma is not None:
         gammas = [args.gamma]
+    main_ix = ix_plain if args.no_list_bounds else ix
     for g in gammas:
-        r = run_once(g)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        reps = 0 if args.gamma is not None else 3
-        for _ in range(reps):
-            run_once(g, want_stats=False)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / max(1, reps)
-        scanned = int(r["n_scanned"].sum().item())
-        exact = int(r["n_exact"].sum().item())
-        rec = round(index_setup.recall_at_k(r["ids"][:nt], truth), 4) if nt > 0 else None
-        sweep.append(dict(gamma=g, recall=rec,
+        r = run_once(main_ix, g)
+        ms = _event_ms(lambda: run_once(main_ix, g, want_stats=False), 3) if args.gamma is None else None
+        scanned, exact = int(r["n_scanned"].sum().item()), int(r["n_exact"].sum().item())
+        sweep.append(dict(gamma=g, recall=round(index_setup.recall_at_k(r["ids"][:nt], truth), 4),
                           pruning_ratio=round(1.0 - exact / max(1, scanned), 5),
-                          qps=round(nq / (ms * 1e-3), 1) if reps else None, n_scanned=scanned,
-                          n_exact=exact))
-    ok = [s for s in sweep if s["recall"] is not None and s["recall"] >= 0.95]
+                          qps=round(nq / (ms * 1e-3), 1) if ms else None, n_scanned=scanned, n_exact=exact))
+    ok = [s for s in sweep if s["recall"] >= 0.95]
     chosen = max(ok, key=lambda s: s["gamma"]) if ok else min(sweep, key=lambda s: s["gamma"])
     gamma = chosen["gamma"]
 
     # ---- timed region: K steps, events around each step and around the scan kernel ----
     out = (torch.empty((nq, k), dtype=torch.int32, device="cuda"),
            torch.empty((nq, k), dtype=torch.float32, device="cuda"))
-    for _ in range(args.warmup):
-        pr = probes_for(queries)
-        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, first_batch=first_batch, want_stats=False, out=out,
-                             query_order=order_for(pr))
-    torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    t_start = time.perf_counter()
-    for s in range(args.steps):
-        ev[s][0].record()
-        pr = probes_for(queries)
-        order = order_for(pr)
-        ev[s][1].record()
-        trim.trim_search_knn(ix, queries, k, gamma, batch, probes=pr, first_batch=first_batch, want_stats=False, out=out,
-                             query_order=order)
-        ev[s][2].record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_start) * 1e3 / args.steps
-    step_ms = sum(e[0].elapsed_time(e[2]) for e in ev) / args.steps
-    scan_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
-    ms_per_step = max(wall_ms, step_ms)
-    qps = nq / (ms_per_step * 1e-3)
 
-    # ---- roofline of the dominant kernel (the fused scan): algorithmic bytes per launch ----
-    # codes + landmark distance per scanned candidate, raw row + id per exact distance,
-    # the query itself and the k results; the table never leaves LDS.
-    alg_bytes = (chosen["n_scanned"] * (w.M + 4) + chosen["n_exact"] * (4 * w.d + 4) +
-                 nq * (4 * w.d + 8 * k))
-    scan_bytes = chosen["n_scanned"] * (w.M + 4)
-    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
-    # HBM bytes per launch as measured with rocprofv3 counters (recorded profile of this kernel
-    # on this workload; null when the timed configuration is not the profiled one)
-    traffic = None
-    valu = None
-    lds = None
-    try:
-        rec = json.load(open(os.path.join(ROOT, "profiles", "search_kernel_c2_traffic.json")))
-        if (rec["workload"] == w.name and rec["gamma"] == gamma and rec["batch"] == batch
-                and rec.get("first_batch", 0) == first_batch):
-            traffic = rec["traffic_bytes_per_launch"]
-            # vector-ALU view of the same launch: wave instructions (SQ_INSTS_VALU of the recorded
-            # profile) against 256 CUs x 4 SIMDs x one wave instruction per 4 cycles at 2.4 GHz
-            insts = rec["valu_wave_instructions_per_launch"]
-            peak = 256 * 4 * 2.4e9 / 4
-            valu = dict(wave_instructions=insts, peak_per_s=peak,
-                        frac=round(insts / (scan_ms * 1e-3) / peak, 4))
-            # on-chip-memory view: LDS wave instructions of the launch (SQ_INSTS_LDS) against the
-            # rate at which the library's lookup aid (random 4-byte table lookups and nothing
-            # else, `python -m paper_2508_17828_amd.ceiling_probe`) issues them
-            lds = dict(wave_instructions=rec["lds_wave_instructions_per_launch"],
-                       ceiling_per_s=rec["lds_lookup_ceiling_wave_instructions_per_s"],
-                       frac=round(rec["lds_wave_instructions_per_launch"] / (scan_ms * 1e-3) /
-                                  rec["lds_lookup_ceiling_wave_instructions_per_s"], 4))
-    except (OSError, ValueError, KeyError):
-        pass
-    roofline = dict(bound="hbm", kernel="search_kernel<knn>", achieved=round(achieved, 1),
-                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=traffic, valu=valu, lds=lds, kernel_ms=round(scan_ms, 4), algorithmic_bytes=alg_bytes,
-                    scan_stream_gbs=round(scan_bytes / (scan_ms * 1e-3) / 1e9, 1),
-                    candidates_per_s=round(chosen["n_scanned"] / (scan_ms * 1e-3), 1),
-                    note="achieved = algorithmic bytes / kernel time; it can exceed the HBM peak because "
-                         "queries share lists through the caches, the first pass reads a 12-byte record "
-                         "per candidate and excluded lists are not read: `traffic` is what was measured "
-                         "beyond L2, `lds` and `valu` price the kernel against what limits it")
+    def make_step(index):
+        def step(ev):
+            if ev: ev[0].record()
+            pr = probes_for(queries)
+            order = order_for(pr)
+            if ev: ev[1].record()
+            trim.trim_search_knn(index, queries, k, gamma, batch, probes=pr, want_stats=False, out=out,
+                                 query_order=order)
+            if ev: ev[2].record()
+        return step
+
+    t = timed_steps(args, make_step(main_ix))
+    got = out[0].cpu().numpy()
+    other = None
+    if ix.list_bounds is not None and not args.no_list_bounds:
+        # the same steps without the per-list summaries (no list-level pruning)
+        t2 = timed_steps(args, make_step(ix_plain))
+        other = dict(value=round(nq / (t2["ms_per_step"] * 1e-3), 1), ms_per_step=round(t2["ms_per_step"], 4),
+                     kernel_ms=round(t2["scan_mean"], 4),
+                     ids_equal=bool(np.array_equal(out[0].cpu().numpy(), got)))
+    qps = nq / (t["ms_per_step"] * 1e-3)
+
+    # ---- what the launch touched: one untimed launch with the kernel's work counters ----
+    acc = run_once(main_ix, gamma, want_work=True)
+    wt = work_totals(trim, acc["work"])
+    assert np.array_equal(acc["ids"].cpu().numpy(), got)
+    touched = touched_bytes(w, nq, nq * k, wt, False)
+    # the task's byte model: codes + landmark distance per scanned candidate, raw row + id per
+    # exact distance, the query itself and the k results; the table never leaves LDS
+    alg_bytes = (chosen["n_scanned"] * (w.M + 4) + chosen["n_exact"] * (4 * w.d + 4) + nq * (4 * w.d + 8 * k))
+    roof = roofline_object(w, nq, t["scan_mean"], alg_bytes, wt, touched, ceil, "search_kernel<knn>")
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     cpu = None
     if args.cpu_seconds > 0:
-        from oracle import trim_oracle
-        h = lambda t: None if t is None else t.cpu().numpy()
-        oix = trim_oracle.Index(h(ix.base), h(ix.codes), h(ix.dlx), h(ix.codebooks), ids=h(ix.ids),
-                                list_offsets=h(ix.list_offsets))
-        qh, ch = h(queries), h(bw.centroids)
-        done, cpu_s, same, chunk = 0, 0.0, True, min(nq, 1000)
-        got = out[0].cpu().numpy()
-        while cpu_s < args.cpu_seconds:
-            lo = done % nq
-            hi_ = min(nq, lo + chunk)
-            qs = np.ascontiguousarray(qh[lo:hi_])
-            t1 = time.perf_counter()
+        ch = oix.centroids
+
+        def chunk(lo, hi):
+            qs = np.ascontiguousarray(qh[lo:hi])
             ph = trim_oracle.ivf_probe(qs, ch, w.nprobe) if w.nlist else None
-            ro = trim_oracle.search_knn(oix, qs, k, gamma, batch, ph, first_batch=first_batch or None)
-            cpu_s += time.perf_counter() - t1
-            same = same and bool(np.array_equal(ro["ids"], got[lo:hi_]))
-            done += hi_ - lo
-        cpu = dict(value=round(done / cpu_s, 1), unit="queries/s", cores=trim_oracle.num_threads(),
-                   kind="oracle", sample=f"{done} queries (the query set in order, wrapping around) in "
-                   f"{cpu_s:.1f} s: probe selection + scan, same index, gamma and batch; "
-                   f"ids equal to the GPU's: {same}")
+            ro = trim_oracle.search_knn(oix, qs, k, gamma, batch, ph)
+            return bool(np.array_equal(ro["ids"], got[lo:hi]))
+
+        nthr = trim_oracle.num_threads()
+        per_q = max(1, int(chosen["n_scanned"] / nq))
+        big = max(nthr, min(nq, 1000, int(4e7 / per_q)))
+        done, used, same = time_oracle(chunk, nq, args.cpu_seconds, big)
+        set_threads(1)
+        done1, used1, same1 = time_oracle(chunk, nq, args.cpu_seconds / 2, max(1, big // 32))
+        set_threads(nthr)
+        cpu = dict(value=round(done / used, 1), unit="queries/s", cores=nthr, kind="oracle",
+                   sample=f"{done} queries (the query set in order, wrapping around) in {used:.1f} s: probe "
+                          f"selection + scan, same index, gamma and batch; ids equal to the GPU's: {same}",
+                   single_thread=dict(value=round(done1 / used1, 1), unit="queries/s", cores=1,
+                                      sample=f"{done1} queries in {used1:.1f} s (one thread, the paper's "
+                                             f"query protocol); ids equal: {same1}"))
 
     line = {
         "metric": "queries/sec at recall@10>=0.95 (1 MI355X); pruning ratio; scan HBM GB/s",
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(t["ms_per_step"], 4),
+        "ms_per_step_median": round(t["step_median"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n} base x {nq} queries, d={w.d}, PQ M={w.M}x256, "
                                f"IVF nlist={w.nlist} nprobe={w.nprobe}, kNN k={k}",
-                   "gamma": gamma, "batch": batch, "first_batch": first_batch, "recall_at_k": chosen["recall"],
-                   "recall_truth": f"exact kNN over all n for the first {nt} queries",
+                   "gamma": gamma, "batch": batch, "recall_at_k": chosen["recall"],
+                   "recall_truth": f"exact kNN over all n in float64 by the CPU oracle, first {nt} queries "
+                                   f"({truth_s:.1f} s)",
                    "pruning_ratio": chosen["pruning_ratio"],
-                   "list_level_pruning": ix.list_bounds is not None,
+                   "list_level_pruning": main_ix.list_bounds is not None,
+                   "without_list_level_pruning": other,
                    "timed": "probe selection + query ordering + fused table/scan/refine/select, inputs in HBM",
                    "setup_s": round(setup_s, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+        "roofline": roof, "cpu_baseline": cpu, "ceilings": ceil, "sweep": sweep,
     }
     print(json.dumps(line))
 

@@ -46,7 +46,8 @@ typedef enum trim_status {
     TRIM_INVALID_ARG = -1,       /* null pointer, negative size, gamma < 0 or NaN, ... */
     TRIM_UNSUPPORTED_SHAPE = -2, /* see trim_shape_supported */
     TRIM_WORKSPACE = -3,         /* workspace missing or smaller than trim_range_workspace_bytes */
-    TRIM_HIP_ERROR = -4          /* a HIP call failed; see trim_last_hip_error */
+    TRIM_HIP_ERROR = -4,         /* a HIP call failed; see trim_last_hip_error */
+    TRIM_INTERNAL = -5           /* the library itself is unusable (a build defect found at launch) */
 } trim_status;
 
 /* Limits of this build. */
@@ -98,7 +99,28 @@ typedef struct trim_candidates {
 typedef struct trim_stats {
     int32_t *n_scanned;
     int32_t *n_exact;
+    uint32_t *work;   /* device [nq][TRIM_WORK_COUNTERS] or NULL: see below */
 } trim_stats;
+
+/* Optional accounting of what a search actually touched, per query (measurement aid; a launch
+ * that keeps it is a little slower).  n_scanned counts every candidate of the query as Section
+ * 4.2's scan defines it; these counters say how the kernel disposed of them:
+ *   [TRIM_WORK_FIRST_PASS] candidates whose first code bytes and landmark distance were read
+ *   [TRIM_WORK_SKIPPED]    candidates passed over with their whole inverted list, never read
+ *                          (list-level pruning; first_pass + skipped + the k seeds = n_scanned)
+ *   [TRIM_WORK_CODE_BYTES] bytes of codes, scan-head records, landmark distances and list
+ *                          summaries requested from memory
+ *   [TRIM_WORK_LOOKUPS]    distance-table lookups issued
+ *   [TRIM_WORK_ROWS]       raw vectors read for an exact distance (>= n_exact: see above)
+ *   [TRIM_WORK_FULL_CODE]  candidates whose code was read beyond the first pass
+ * The remaining entries are reserved (written as 0). */
+#define TRIM_WORK_COUNTERS 8
+#define TRIM_WORK_FIRST_PASS 0
+#define TRIM_WORK_SKIPPED 1
+#define TRIM_WORK_CODE_BYTES 2
+#define TRIM_WORK_LOOKUPS 3
+#define TRIM_WORK_ROWS 4
+#define TRIM_WORK_FULL_CODE 5
 
 /* 1 if (d, M) can be searched by this build, else 0.  Needs d % 4 == 0, d % M == 0,
  * M % 4 == 0, d/M <= 64, and room in the 160 KB of LDS for the kernel's working set. */
@@ -201,19 +223,17 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
  * exact distances; the remaining candidates are taken in batches; inside a batch the
  * threshold tau (k-th squared distance in R; +inf while |R| < k) is frozen; a candidate
  * survives iff g <= tau (Equation 3); survivors get exact distances and are merged into R.
- * The first batch holds `first_batch` candidates, every later one twice as many as the one
- * before, up to `batch`; first_batch = 0 or = batch makes all batches `batch` long.
- * batch = 1 is the paper's vector-at-a-time rule; short early batches stay close to it
- * while R is still poor and tau falls fast, which spares most of the exact distances a
- * long first batch would spend.
+ * Every batch holds `batch` candidates; batch = 1 is the paper's vector-at-a-time rule.
  *
  * queries [nq][d] device.  lut: device [nq][M][256] or NULL (tables are then built inside
  * the kernel from index->codebooks).  cand: host struct or NULL.  nq <= TRIM_MAX_QUERIES,
  * 1 <= k <= TRIM_MAX_K,
- * 1 <= batch <= TRIM_MAX_BATCH, 0 <= first_batch <= batch, gamma >= 0.
+ * 1 <= batch <= TRIM_MAX_BATCH, gamma >= 0.
  * query_order: device [nq] or NULL; a permutation of 0..nq-1 giving the order in which
  * queries are handed to the GPU (see trim_query_order).  It changes scheduling only: every
- * query's results are written at its own row and do not depend on the order.
+ * query's results are written at its own row and do not depend on the order.  A query that
+ * the array does not name is not searched and its output rows are left untouched; entries
+ * outside [0, nq) are skipped.
  * out_ids [nq][k], out_d2 [nq][k] device: ascending by (d2, id); rows with fewer than k
  * candidates are padded with id -1, d2 +inf.
  * stats: host struct or NULL.  survivor_mask: device or NULL; if given it must hold
@@ -223,7 +243,7 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
  */
 int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
                     const float *lut, const trim_candidates *cand, int32_t k, float gamma,
-                    int32_t batch, int32_t first_batch, const int32_t *query_order,
+                    int32_t batch, const int32_t *query_order,
                     int32_t *out_ids, float *out_d2,
                     const trim_stats *stats, uint32_t *survivor_mask, int64_t mask_words,
                     void *stream);

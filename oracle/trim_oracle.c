@@ -182,11 +182,9 @@ static void result_insert(hit_t *R, int *size, int k, hit_t h) {
  * Per query: R (size k) is filled with the first k candidates, all with exact distances;
  * afterwards candidates are taken in batches; inside a batch the threshold tau (the k-th
  * squared distance in R, +inf while R is short) is frozen; a candidate survives iff
- * g <= tau; survivors get exact distances and are merged into R.  The first batch holds
- * `first_batch` candidates and every later one twice as many as the one before it, up to
- * `batch` (first_batch = batch: all batches alike).  batch = first_batch = 1 is the
- * paper's vector-at-a-time rule; short early batches stay close to it while R is still
- * poor and tau moves fast.  Everything is in squared distances.
+ * g <= tau; survivors get exact distances and are merged into R.  Every batch holds `batch`
+ * candidates (the last one what is left); batch = 1 is the paper's vector-at-a-time rule.
+ * Everything is in squared distances.
  *
  * lut may be NULL (the table is then built here).  ids may be NULL (id = position).
  * list_offsets NULL => every query scans positions 0..n-1.
@@ -198,7 +196,7 @@ void trim_oracle_search_knn(const float *base, const uint8_t *codes, const float
                             const int32_t *ids, const float *codebooks, int64_t n, int d,
                             int M, const float *queries, int64_t nq, const float *lut,
                             int nprobe, const int64_t *list_offsets, const int32_t *probes,
-                            int k, float gamma, int batch, int first_batch, int32_t *out_ids,
+                            int k, float gamma, int batch, int32_t *out_ids,
                             float *out_d2, int32_t *n_scanned, int32_t *n_exact, uint32_t *mask,
                             int64_t mask_words) {
 #pragma omp parallel for schedule(dynamic, 1)
@@ -230,11 +228,9 @@ void trim_oracle_search_knn(const float *base, const uint8_t *codes, const float
             if (mq) mq[idx / 32] |= 1u << (idx % 32);
         }
         hit_t *surv = malloc(sizeof(hit_t) * (size_t)(batch > 0 ? batch : 1));
-        int64_t len = first_batch; /* size of the batch about to be taken */
         while (idx < cs.total) {
             float tau = size >= k ? R[k - 1].d2 : INFINITY;
-            int64_t end = idx + len < cs.total ? idx + len : cs.total;
-            len = 2 * len < batch ? 2 * len : batch;
+            int64_t end = idx + batch < cs.total ? idx + batch : cs.total;
             int ns = 0;
             for (; idx < end; ++idx) {
                 int64_t pos = cs.pos[idx];

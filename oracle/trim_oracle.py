@@ -116,11 +116,8 @@ def max_candidates(ix: Index, probes) -> int:
     return int(lens[probes].sum(axis=1).max()) if probes.size else 0
 
 
-def search_knn(ix: Index, queries, k, gamma, batch, probes=None, lut=None, want_mask=False,
-               first_batch=None):
-    """first_batch: size of the first batch; later ones double up to `batch` (None: = batch)."""
-    first_batch = batch if first_batch is None else first_batch
-    assert 1 <= first_batch <= batch
+def search_knn(ix: Index, queries, k, gamma, batch, probes=None, lut=None, want_mask=False):
+    assert batch >= 1
     nq = queries.shape[0]
     out_ids = np.empty((nq, k), dtype=np.int32)
     out_d2 = np.empty((nq, k), dtype=np.float32)
@@ -133,7 +130,7 @@ def search_knn(ix: Index, queries, k, gamma, batch, probes=None, lut=None, want_
         _p(ix.base, f32), _p(ix.codes, u8), _p(ix.dlx, f32), _p(ix.ids, i32),
         _p(ix.codebooks, f32), C.c_int64(ix.n), C.c_int(ix.d), C.c_int(ix.M),
         _p(queries, f32), C.c_int64(nq), _p(lut, f32), npb, lo, pr, C.c_int(k),
-        C.c_float(gamma), C.c_int(batch), C.c_int(first_batch), _p(out_ids, i32), _p(out_d2, f32),
+        C.c_float(gamma), C.c_int(batch), _p(out_ids, i32), _p(out_d2, f32),
         _p(n_scanned, i32), _p(n_exact, i32), _p(mask, u32), C.c_int64(mw))
     return dict(ids=out_ids, d2=out_d2, n_scanned=n_scanned, n_exact=n_exact, mask=mask)
 

@@ -1,11 +1,13 @@
 """Compile libtrim.so (HIP, gfx950 only) in-tree with hipcc."""
 import os
+import re
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libtrim.so")
+RESOURCES = os.path.join(HERE, "libtrim.resources.txt")
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
@@ -14,15 +16,76 @@ FLAGS = [
     # no packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
+    # per-kernel registers, spills and static LDS, checked below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+_FIELDS = (("VGPRs", "vgpr"), ("AGPRs", "agpr"), (r"ScratchSize \[bytes/lane\]", "scratch"),
+           (r"Occupancy \[waves/SIMD\]", "waves"), ("SGPRs Spill", "sgpr_spill"),
+           ("VGPRs Spill", "vgpr_spill"), (r"LDS Size \[bytes/block\]", "static_lds"))
+
+
+def kernel_resources(remarks: str):
+    """Parse the compiler's kernel-resource-usage remarks: {mangled name: {field: int}}."""
+    out = {}
+    for block in re.split(r"remark: Function Name: ", remarks)[1:]:
+        name = block.split()[0]
+        out[name] = {key: int(re.search(pat + r": (\d+)", block).group(1)) for pat, key in _FIELDS}
+    return out
+
+
+def _without_remarks(stderr: str):
+    """The compiler's output less the resource remarks (with their source excerpts and include
+    trails) and the host pass's note about the packed-fp32 feature."""
+    out, pending, in_remark = [], [], False
+    for line in stderr.splitlines():
+        if "packed-fp32-ops" in line:
+            continue
+        if line.startswith("In file included from"):
+            pending.append(line)
+            in_remark = False
+            continue
+        if re.match(r"^\S.*:\d+:\d+: ", line):           # a diagnostic's first line
+            in_remark = "remark:" in line
+            if not in_remark:
+                out += pending
+            pending = []
+        if not in_remark:
+            out.append(line)
+    return out
+
+
+def check_resources(res) -> None:
+    """The search kernels address their distance table from LDS address 0: none may carry
+    static LDS in front of its dynamic area."""
+    bad = [n for n, r in res.items() if "search_kernel" in n and r["static_lds"] != 0]
+    if bad:
+        raise RuntimeError("search kernels with static LDS (their table would not start at LDS "
+                           "address 0): " + ", ".join(bad))
 
 
 def build(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra) + ["-o", OUT, os.path.join(CSRC, "trim_api.hip")]
+    tmp = OUT + ".tmp"
+    cmd = [hipcc] + FLAGS + list(extra) + ["-o", tmp, os.path.join(CSRC, "trim_api.hip")]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    p = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    rest = _without_remarks(p.stderr)
+    if rest:
+        print("\n".join(rest), file=sys.stderr, flush=True)
+    if p.returncode != 0:
+        raise subprocess.CalledProcessError(p.returncode, cmd)
+    res = kernel_resources(p.stderr)
+    try:
+        check_resources(res)
+    except RuntimeError:
+        os.remove(tmp)
+        raise
+    os.replace(tmp, OUT)
+    with open(RESOURCES, "w") as f:
+        for name in sorted(res):
+            f.write(name + " " + " ".join(f"{k}={v}" for k, v in res[name].items()) + "\n")
     return OUT
 
 

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <mutex>
@@ -20,6 +21,11 @@ namespace {
 using namespace trim;
 
 thread_local int g_last_hip_error = 0;
+
+static_assert(kWorkCounters == TRIM_WORK_COUNTERS && kWorkFirstPass == TRIM_WORK_FIRST_PASS &&
+              kWorkSkipped == TRIM_WORK_SKIPPED && kWorkCodeBytes == TRIM_WORK_CODE_BYTES &&
+              kWorkLookups == TRIM_WORK_LOOKUPS && kWorkRows == TRIM_WORK_ROWS &&
+              kWorkFullCode == TRIM_WORK_FULL_CODE, "header and kernel disagree on the work counters");
 
 constexpr size_t kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
 
@@ -187,14 +193,25 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
     return false;
 }
 
-template <int MODE, int E>
-int launch_search_e(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
+template <int MODE, int E, bool ACCT>
+int launch_search_a(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
     void (*fn)(const SearchArgs) = nullptr;
     switch (pl.vec) {
-        case 4: fn = search_kernel<MODE, 4, E>; break;
-        case 2: fn = search_kernel<MODE, 2, E>; break;
-        default: fn = search_kernel<MODE, 1, E>; break;
+        case 4: fn = search_kernel<MODE, 4, E, ACCT>; break;
+        case 2: fn = search_kernel<MODE, 2, E, ACCT>; break;
+        default: fn = search_kernel<MODE, 1, E, ACCT>; break;
     }
+    // The kernel addresses its distance table with immediate offsets from LDS address 0, so it
+    // must own the workgroup's LDS from the first byte: an instance that was built with static
+    // LDS in front of the dynamic area is refused here instead of being launched.
+    static std::atomic<int> lds_checked[3];   // per instance (MODE, E, ACCT) and code-load width
+    std::atomic<int> &seen = lds_checked[pl.vec == 4 ? 2 : pl.vec == 2 ? 1 : 0];
+    if (seen.load(std::memory_order_acquire) == 0) {
+        hipFuncAttributes fa;
+        HIP_TRY(hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(fn)));
+        seen.store(fa.sharedSizeBytes == 0 ? 1 : -1, std::memory_order_release);
+    }
+    if (seen.load(std::memory_order_acquire) < 0) return TRIM_INTERNAL;
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds));
     hipLaunchKernelGGL(fn, grid, dim3(pl.threads), pl.lds, st, a);
@@ -202,15 +219,24 @@ int launch_search_e(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t 
     return TRIM_OK;
 }
 
+template <int MODE, int E>
+int launch_search_e(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
+    return a.work ? launch_search_a<MODE, E, true>(a, pl, grid, st)
+                  : launch_search_a<MODE, E, false>(a, pl, grid, st);
+}
+
 // k decides how many result entries a lane of the merging wave holds (result_slots).
 template <int MODE>
 int launch_search(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
-    if (MODE == kRange) return launch_search_e<MODE, 1>(a, pl, grid, st);
-    switch (result_slots(a.k)) {
-        case 1: return launch_search_e<MODE, 1>(a, pl, grid, st);
-        case 2: return launch_search_e<MODE, 2>(a, pl, grid, st);
-        case 4: return launch_search_e<MODE, 4>(a, pl, grid, st);
-        default: return launch_search_e<MODE, 16>(a, pl, grid, st);
+    if constexpr (MODE == kRange) {
+        return launch_search_e<MODE, 1>(a, pl, grid, st);
+    } else {
+        switch (result_slots(a.k)) {
+            case 1: return launch_search_e<MODE, 1>(a, pl, grid, st);
+            case 2: return launch_search_e<MODE, 2>(a, pl, grid, st);
+            case 4: return launch_search_e<MODE, 4>(a, pl, grid, st);
+            default: return launch_search_e<MODE, 16>(a, pl, grid, st);
+        }
     }
 }
 
@@ -255,6 +281,7 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.two_gamma = 2.0f * gamma;
     a.n_scanned = stats ? stats->n_scanned : nullptr;
     a.n_exact = stats ? stats->n_exact : nullptr;
+    a.work = stats ? stats->work : nullptr;
     a.mask = mask; a.mask_words = mask_words;
     a.off_q = pl.off_q; a.off_segp = pl.off_segp; a.off_segd = pl.off_segd; a.off_rest = pl.off_rest;
     a.off_seglb = pl.off_seglb;
@@ -385,10 +412,11 @@ int range_search(const trim_index_view *index, const float *queries, int64_t nq,
     if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
     if (stats && stats->n_exact && (rc = fill_u32(reinterpret_cast<uint32_t *>(stats->n_exact), (size_t)nq, 0u, st)))
         return rc;
+    if (stats && stats->work && (rc = fill_u32(stats->work, (size_t)nq * kWorkCounters, 0u, st))) return rc;
 
     SearchArgs a{};
     fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
-    a.k = 1; a.batch = kRangeRound; a.first_batch = kRangeRound;
+    a.k = 1; a.batch = kRangeRound;
     a.radius2 = radius * radius;
     a.chunk = L.chunk; a.nsplit = L.nsplit;
     a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;
@@ -657,7 +685,7 @@ int trim_build_lut(const float *queries, int64_t nq, int32_t d, const float *cod
 
 int trim_search_knn(const trim_index_view *index, const float *queries, int64_t nq,
                     const float *lut, const trim_candidates *cand, int32_t k, float gamma,
-                    int32_t batch, int32_t first_batch, const int32_t *query_order,
+                    int32_t batch, const int32_t *query_order,
                     int32_t *out_ids, float *out_d2,
                     const trim_stats *stats, uint32_t *survivor_mask, int64_t mask_words,
                     void *stream) {
@@ -666,7 +694,6 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     if ((rc = check_cand(cand))) return rc;
     if (nq < 0 || nq > TRIM_MAX_QUERIES || k < 1 || k > TRIM_MAX_K || batch < 1 || batch > TRIM_MAX_BATCH)
         return TRIM_INVALID_ARG;
-    if (first_batch < 0 || first_batch > batch) return TRIM_INVALID_ARG;
     if (!(gamma >= 0.0f) || std::isinf(gamma)) return TRIM_INVALID_ARG;
     if (nq == 0) return TRIM_OK;
     if (!queries || !out_ids || !out_d2) return TRIM_INVALID_ARG;
@@ -682,7 +709,6 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     SearchArgs a{};
     fill_common(a, index, queries, lut, cand, gamma, stats, survivor_mask, mask_words, pl);
     a.k = k; a.batch = batch; a.radius2 = 0.0f;
-    a.first_batch = first_batch > 0 ? first_batch : batch;
     a.out_ids = out_ids; a.out_d2 = out_d2;
     a.chunk = 0; a.nsplit = 1;
     a.nq = nq; a.order = query_order;
@@ -783,6 +809,7 @@ const char *trim_strerror(int status) {
         case TRIM_UNSUPPORTED_SHAPE: return "unsupported shape (d, M) for this build";
         case TRIM_WORKSPACE: return "workspace missing, misaligned or too small (trim_search_range_static: the search needs more than TRIM_STATIC_SCRATCH_BYTES)";
         case TRIM_HIP_ERROR: return "HIP call failed (see trim_last_hip_error)";
+        case TRIM_INTERNAL: return "the library was built wrongly (a search kernel carries static LDS)";
         default: return "unknown status";
     }
 }
@@ -790,18 +817,5 @@ const char *trim_strerror(int status) {
 int trim_last_hip_error(void) { return g_last_hip_error; }
 
 const char *trim_version(void) { return "0.1"; }
-
-#ifdef TRIM_PHASE_TIMING
-// Profiling builds only: read (and optionally clear) the per-phase cycle totals.
-int trim_debug_phase_ticks(unsigned long long *out16, int reset) {
-    HIP_TRY(hipDeviceSynchronize());
-    HIP_TRY(hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_phase_ticks), 16 * sizeof(unsigned long long)));
-    if (reset) {
-        unsigned long long z[16] = {};
-        HIP_TRY(hipMemcpyToSymbol(HIP_SYMBOL(g_phase_ticks), z, sizeof(z)));
-    }
-    return TRIM_OK;
-}
-#endif
 
 }  // extern "C"

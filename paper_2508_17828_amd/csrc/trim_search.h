@@ -7,23 +7,13 @@
 
 #include "trim_device.h"
 
-// Optional per-phase cycle accounting (profiling builds only: -DTRIM_PHASE_TIMING).
-#ifdef TRIM_PHASE_TIMING
-__device__ unsigned long long g_phase_ticks[16];
-#define TRIM_TICK_INIT() unsigned long long _acc[16] = {}; unsigned long long _last = clock64();
-#define TRIM_TICK(i) do { if (threadIdx.x == 0) { unsigned long long _n = clock64(); _acc[i] += _n - _last; _last = _n; } } while (0)
-#define TRIM_TICK_FLUSH() do { if (threadIdx.x == 0) { for (int _i = 0; _i < 16; ++_i) atomicAdd(&g_phase_ticks[_i], _acc[_i]); } } while (0)
-#else
-#define TRIM_TICK_INIT()
-#define TRIM_TICK(i)
-#define TRIM_TICK_FLUSH()
-#endif
-
 namespace trim {
 
 enum Mode { kKnn = 0, kRange = 1 };
 // The distance table sits at the very start of the workgroup's LDS (the search kernel has no
-// static LDS), which lets table gathers use an immediate row offset.  Checked at kernel entry.
+// static LDS), which lets table gathers use an immediate row offset.  The launch wrapper checks
+// the kernel's static LDS size (it must be 0) before the first launch of an instance, and the
+// build refuses a library in which it is not.
 constexpr uint32_t kTabLds = 0;
 constexpr int kXcds = 8;  // accelerator dies of an MI355X, each with its own L2
 
@@ -53,7 +43,6 @@ struct SearchArgs {
     int32_t P, Mp;
     // search parameters
     int32_t k, batch;  // range: batch = span = survivor-list capacity per round
-    int32_t first_batch;  // kNN: batches double from this size up to batch (= batch: no ramp)
     int32_t span;      // candidates bounded between two barriers (a multiple of batch)
     float two_gamma;
     float radius2;
@@ -61,6 +50,7 @@ struct SearchArgs {
     int32_t *out_ids;
     float *out_d2;
     int32_t *n_scanned, *n_exact;
+    uint32_t *work;   // optional [nq][kWorkCounters]: what the launch touched (see WorkCounter)
     uint32_t *mask;
     int64_t mask_words;
     // range only
@@ -95,6 +85,18 @@ struct Ctl {
     int32_t nresult;     // range: results in this chunk
     int32_t nexact;
     int32_t nposs;       // cruise: number of possibles found in the stretch
+    uint32_t work[8];    // WorkCounter totals of this workgroup (only kept when asked for)
+};
+
+// Optional accounting of what a search touched, per query (trim_stats.work).
+enum WorkCounter {
+    kWorkFirstPass = 0,  // candidates whose first code bytes and landmark distance were read
+    kWorkSkipped = 1,    // candidates passed over with their whole list, never read
+    kWorkCodeBytes = 2,  // bytes of codes, scan-head records and landmark distances requested
+    kWorkLookups = 3,    // table lookups issued
+    kWorkRows = 4,       // raw rows read for an exact distance
+    kWorkFullCode = 5,   // candidates whose code was read beyond the first pass
+    kWorkCounters = 8
 };
 // Where the code bytes of one stored vector are.  Row-major: consecutive.  Tiled: the vectors
 // are grouped in blocks of 64, and piece p (code bytes 16p..16p+15) of the 64 vectors of a
@@ -351,7 +353,9 @@ __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *
 // does not carry the registers of the wide result sets.  That instance is held to 80
 // registers (6 waves per SIMD), so that three 512-thread workgroups share a CU.
 constexpr int kSmallKWavesPerSimd = 6;
-template <int MODE, int VEC, int E>
+// ACCT: the instance that keeps the work counters (SearchArgs::work); the plain one carries none
+// of that code.
+template <int MODE, int VEC, int E, bool ACCT>
 __global__ __launch_bounds__(1024)
 __attribute__((amdgpu_waves_per_eu(MODE == kKnn && E == 1 ? kSmallKWavesPerSimd : 4)))
 void search_kernel(const SearchArgs a) {
@@ -381,6 +385,9 @@ void search_kernel(const SearchArgs a) {
     const int tid = threadIdx.x;
     const int T = blockDim.x;
     const int lane = tid & (kWave - 1);
+    // optional accounting of the work done (same for every thread); totals gather in LDS
+    constexpr bool acct = ACCT;
+    auto tally = [&](int which, uint32_t v) { atomicAdd(&ctl->work[which], v); };
     // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of the
     // (optionally sorted) query order so that concurrent workgroups of an XCD scan the same
     // lists and share its L2.
@@ -392,13 +399,6 @@ void search_kernel(const SearchArgs a) {
     const int split = blockIdx.y;
     const int nseg = a.nseg > 0 ? a.nseg : 1;
 
-    {   // the table must sit at LDS address kTabLds; the value is laundered through an empty
-        // asm so that the compiler cannot fold the test (it assumes globals are never at 0)
-        uint32_t tab_at = lds_addr(tab);
-        asm volatile("" : "+v"(tab_at));
-        if (tab_at != kTabLds) return;
-    }
-    TRIM_TICK_INIT();
     // ---- prologue: query, segment table, table ----
     for (int t = tid; t < a.d; t += T) q_lds[t] = a.queries[(size_t)q * a.d + t];
     if (MODE == kKnn)
@@ -441,6 +441,7 @@ void search_kernel(const SearchArgs a) {
         ctl->tau = MODE == kRange ? a.radius2 : __builtin_inff();
         ctl->nresult = 0;
         ctl->nexact = 0;
+        for (int i = 0; i < kWorkCounters; ++i) ctl->work[i] = 0;
     }
     if (a.P == 1) fill_table(tab, a, q_lds, q, 0, a.M);
     __syncthreads();
@@ -482,6 +483,7 @@ void search_kernel(const SearchArgs a) {
     if (MODE == kKnn && a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr) {
         constexpr int kH0 = VEC >= 2 ? 8 : 4;
         const size_t rec_bytes = list_record_bytes(a.M);
+        if (acct && tid == 0) tally(kWorkCodeBytes, (uint32_t)(nseg * rec_bytes));
         // two segments per round and wave, 32 subspaces per step: all the loads of a step are
         // issued before the first is used
         for (int p0 = 2 * (tid >> 6); p0 < nseg; p0 += 2 * (T >> 6)) {
@@ -661,14 +663,13 @@ void search_kernel(const SearchArgs a) {
                         }
                     });
         __syncthreads();
-        TRIM_TICK(4);
         if (MODE == kKnn && tid < kWave) merge_batch<E>(sd2, spos, ns, rd2, rid, ctl, a.k, lane);
         if (tid == 0) {
             ctl->nexact += ns;
             ctl->nsurv = 0;
+            if (acct) tally(kWorkRows, (uint32_t)ns);
         }
         __syncthreads();
-        TRIM_TICK(5);
     };
 
     // ---- stage B by replay (k <= 64): the possibles of a stretch or span, already laid out in
@@ -706,7 +707,6 @@ void search_kernel(const SearchArgs a) {
         refine_rows(np, [&](int i) { return locate(c0 + spos[i]); },
                     [&](int i, float d2, int32_t id) { sd2[i] = d2; s_id[i] = id; });
         __syncthreads();
-        TRIM_TICK(14);
         if (tid < kWave) {
             uint32_t *mrow = a.mask ? a.mask + (size_t)q * a.mask_words : nullptr;
             int n;
@@ -720,11 +720,13 @@ void search_kernel(const SearchArgs a) {
                     : replay_batches<E, false>(spos, s_g, sd2, s_id, np, a.batch, c0, mrow, a.mask_words,
                                                rd2, rid, ctl, a.k, lane);
             }
-            if (lane == 0) ctl->nexact += n;
+            if (lane == 0) {
+                ctl->nexact += n;
+                if (acct) tally(kWorkRows, (uint32_t)np);
+            }
         }
     };
 
-    TRIM_TICK(0);
     // ---- seed: the first k candidates populate R, all with exact distances ----
     if (kseed > 0) {
         for (int i0 = 0; i0 < kseed; i0 += T) append(i0 + tid < kseed, i0 + tid);
@@ -732,7 +734,6 @@ void search_kernel(const SearchArgs a) {
         refine_and_select(kseed);
     }
 
-    TRIM_TICK(1);
     // ---- main loop over spans of candidates (a whole number of batches each) ----
     // Stage A bounds every candidate of the span with no barrier in between and
     // keeps the bounds in LDS; it counts, per batch, the candidates that pass the
@@ -770,14 +771,12 @@ void search_kernel(const SearchArgs a) {
     };
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
-    int ramp = MODE == kKnn ? a.first_batch : a.batch;  // next batch size while below a.batch
     // next span length while the spans of a small-batch search still grow (a multiple of batch)
     int small_span = (MODE == kKnn && a.batch < kSmallBatch) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
     for (int c0 = c_begin + kseed; c0 < c_end;) {
         __syncthreads();  // every thread is done with the previous stretch
         const float tau0 = ctl->tau;
         const float sqrt_tau0 = abandon_scale(tau0);  // scaled: see abandon_threshold
-        const bool ramping = ramp < a.batch;  // the batches before the first full-size one
 
         // ---- cruise: once tau is finite, bound a long stretch of candidates with no block-wide
         // barrier at all.  Every wave runs its own software pipeline over interleaved blocks of
@@ -791,7 +790,7 @@ void search_kernel(const SearchArgs a) {
         // (The first span after the seed is always taken span by span: it is what makes tau tight.)
         int replay_np = -1;  // >= 0: the candidates [c0, c0 + advance) end in a replay of that many possibles
         int advance = 0;
-        if (cruise > 0 && !ramping && small_span >= a.span && c0 > c_begin + kseed &&
+        if (cruise > 0 && small_span >= a.span && c0 > c_begin + kseed &&
             tau0 < __builtin_inff() && c_end - c0 > a.span) {
             const int S = c0 + cruise < c_end ? cruise : c_end - c0;
             const int nb = (S + a.bucket - 1) / a.bucket;   // buckets (= batches unless they are very small)
@@ -857,6 +856,15 @@ void search_kernel(const SearchArgs a) {
                                 j += 4;
                             }
                         }
+                        if (acct) {
+                            // the first two chunks were loaded ahead whether or not the sum got
+                            // that far; a sum stopped inside a 16-byte piece comes back as +inf
+                            // and has looked up only the piece's first 8 subspaces
+                            const int loaded = two_chunks && j < 8 * DV ? 8 * DV : j;
+                            tally(kWorkCodeBytes, (uint32_t)(loaded + 4));
+                            tally(kWorkLookups, (uint32_t)(j - (DV == 4 && sum == __builtin_inff() ? 8 : 0)));
+                            tally(kWorkFullCode, 1u);
+                        }
                         if (!(sum > thr - restv[j >> 2])) {
                             const float g = plb_from_s(sum, d_b, a.two_gamma);
                             if (g <= tau0) {
@@ -903,14 +911,20 @@ void search_kernel(const SearchArgs a) {
                             const float2 sr = seglist[s_seg];
                             const int sl = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sr.x));
                             const int rs = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sr.y));
-                            if (sl > st_bits) continue;          // same for the whole wave
+                            if (sl > st_bits) {                  // same for the whole wave
+                                if (acct && lane == 0) tally(kWorkSkipped, U * kWave);
+                                continue;
+                            }
                             blk_rest = __builtin_bit_cast(float, rs);
                         } else if (s_seg + 1 < nseg) {
                             // the block ends in the next list: passed over if both lists are
                             const int e2 = __builtin_amdgcn_readfirstlane(segp[s_seg + 2]);
                             const int sl1 = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seglist[s_seg].x));
                             const int sl2 = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, seglist[s_seg + 1].x));
-                            if (cf + U * kWave <= e2 && sl1 > st_bits && sl2 > st_bits) continue;
+                            if (cf + U * kWave <= e2 && sl1 > st_bits && sl2 > st_bits) {
+                                if (acct && lane == 0) tally(kWorkSkipped, U * kWave);
+                                continue;
+                            }
                         }
                     }
                     if (full) {
@@ -951,12 +965,15 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
                         for (int u = 0; u < U; ++u) sg[u] <<= 16;
                     }
-                    TRIM_TICK(8);
+                    if (acct && lane == 0) {
+                        const uint32_t nv = cb + U * kWave <= S ? U * kWave : S - cb;  // candidates of the block
+                        tally(kWorkFirstPass, nv);
+                        tally(kWorkCodeBytes, nv * (full ? (uint32_t)sizeof(HeadRecord) : H0 + 4u));
+                        tally(kWorkLookups, nv * H0);
+                    }
                     if (d_n > 0) drain_finish();
-                    TRIM_TICK(9);
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
                     if (count >= kWave) drain_issue();
-                    TRIM_TICK(10);
                     float sums[U];
                     if constexpr (H0 == 8 && U % 2 == 0) {
 #pragma unroll
@@ -967,7 +984,6 @@ void search_kernel(const SearchArgs a) {
                         for (int u = 0; u < U; ++u)
                             sums[u] = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
                     }
-                    TRIM_TICK(11);
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
                         if (u == U / 2 && count >= 2 * kWave) {
@@ -993,14 +1009,11 @@ void search_kernel(const SearchArgs a) {
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
-                    TRIM_TICK(12);
                 }
                 if (d_n > 0) drain_finish();
                 while (count > 0) { drain_issue(); drain_finish(); }
-                TRIM_TICK(13);
             }
             __syncthreads();
-            TRIM_TICK(6);
             const int np = ctl->nposs;
             if (np <= a.poss_cap) {
                 // Stage B of a stretch.  The possibles are put in batch order (counting sort on
@@ -1051,12 +1064,10 @@ void search_kernel(const SearchArgs a) {
 
         // The first stretch after the seed is a single batch: its threshold (from the k seeds)
         // is loose, so nothing is abandoned early; one batch is enough to make tau tight.
-        // While the batches still grow, each is taken alone.
         // Small batches: the first spans are short too (64 candidates or one batch, then doubling), so that
         // tau is tight before a full span's possibles have to fit the replay.
-        int span_len = ramping ? ramp : c0 == c_begin + kseed ? a.batch : a.span;
-        if (ramping) ramp = 2 * ramp < a.batch ? 2 * ramp : a.batch;
-        if (!ramping && small_span < a.span) {
+        int span_len = c0 == c_begin + kseed ? a.batch : a.span;
+        if (small_span < a.span) {
             span_len = small_span;
             small_span *= 2;
         }
@@ -1074,7 +1085,6 @@ void search_kernel(const SearchArgs a) {
         // partial sum of a queued candidate waits in plbs[].
         int wlo, whi;
         wave_slice(span, wlo, whi);
-        TRIM_TICK(2);
         uint16_t *qin = wq + (size_t)wave * a.wqcap;
         uint16_t *qout = wq + (size_t)(nwaves + wave) * a.wqcap;
         int qn = 0;  // length of this wave's queue (same in every lane)
@@ -1083,7 +1093,7 @@ void search_kernel(const SearchArgs a) {
         // bounded in one go instead, two per lane, with all their loads issued together.
         constexpr int kDirectChunks = 2;  // code chunks of 4*VEC bytes a lane keeps per candidate
         const bool direct = MODE == kKnn && VEC == 4 && a.P == 1 && a.M <= 4 * VEC * kDirectChunks &&
-                            a.M % (4 * VEC) == 0 && (ramping || c0 == c_begin + kseed);
+                            a.M % (4 * VEC) == 0 && c0 == c_begin + kseed;
         if (direct) {
             constexpr int UD = 2;
             for (int base = wlo; base < whi; base += UD * kWave) {
@@ -1122,7 +1132,15 @@ void search_kernel(const SearchArgs a) {
                     }
                 }
             }
+            if (acct && lane == 0 && whi > wlo) {
+                const uint32_t nv = whi - wlo;
+                tally(kWorkFirstPass, nv);
+                tally(kWorkFullCode, nv);
+                tally(kWorkCodeBytes, nv * (uint32_t)(a.M + 4));
+                tally(kWorkLookups, nv * (uint32_t)a.M);
+            }
         }
+        int rnd = 0;  // rounds taken so far (the second one reads the rest of a code for the first time)
         for (int ph = 0; ph < (direct ? 0 : a.P); ++ph) {
             if (a.P > 1) {
                 __syncthreads();
@@ -1166,7 +1184,12 @@ void search_kernel(const SearchArgs a) {
                             qnext += __popcll(m);
                         }
                     }
-                    TRIM_TICK(6);
+                    if (acct && lane == 0 && whi > wlo) {
+                        const uint32_t nv = whi - wlo;
+                        tally(kWorkFirstPass, nv);
+                        tally(kWorkCodeBytes, nv * (H0 + 4u));
+                        tally(kWorkLookups, nv * (uint32_t)h1);
+                    }
                 } else {
                     // ---- later rounds: dense over the wave's queue ----
                     // With 16-byte code loads a round takes up to 104 subspaces (an 8-byte piece
@@ -1204,20 +1227,25 @@ void search_kernel(const SearchArgs a) {
                             const float thr = abandon_threshold(b, sqrt_tau0);
                             float sum = slice_round ? 0.0f : plbs[cl];
                             int j = h0;
+                            int used16 = 0;  // 16-byte pieces of a bulk round whose sum was begun
+                            // (a sum stopped inside a 16-byte piece comes back as +inf: still
+                            // above every threshold, and the accounting can tell)
                             if (bulk) {
                                 if (lead8) sum = gather_add<2>(sum, kTabLds + h0 * (kC * 4), w8, thr);
 #pragma unroll
                                 for (int c = 0; c < kPieces; ++c)
-                                    if (c < n16 && !(sum > thr))
-                                        sum = gather_add<4>(sum, kTabLds + (ja + 16 * c) * (kC * 4),
-                                                            w16[c], thr);
+                                    if (c < n16 && !(sum > thr)) {
+                                        sum = gather_add<4, true>(sum, kTabLds + (ja + 16 * c) * (kC * 4),
+                                                                  w16[c], thr);
+                                        ++used16;
+                                    }
                                 j = h1;
                             }
                             while (j < h1) {  // widest aligned load that fits, test after each
                                 if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
                                     uint32_t w[4];
                                     load_codes<4>(w, cr.at(jp + j));
-                                    sum = gather_add<4>(sum, kTabLds + j * (kC * 4), w, thr);
+                                    sum = gather_add<4, true>(sum, kTabLds + j * (kC * 4), w, thr);
                                     j += 16;
                                 } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= h1) {
                                     uint32_t w[2];
@@ -1231,6 +1259,15 @@ void search_kernel(const SearchArgs a) {
                                     j += 4;
                                 }
                                 if (sum > thr) break;
+                            }
+                            if (acct) {
+                                const int bytes = bulk ? (lead8 ? 8 : 0) + 16 * n16 : j - h0;
+                                const int looks = (bulk ? (lead8 ? 8 : 0) + 16 * used16 : j - h0) -
+                                                  (VEC == 4 && sum == __builtin_inff() ? 8 : 0);
+                                tally(kWorkCodeBytes, (uint32_t)(bytes + 4));
+                                tally(kWorkLookups, (uint32_t)looks);
+                                if (slice_round) tally(kWorkFirstPass, 1u);
+                                else if (rnd == 1) tally(kWorkFullCode, 1u);
                             }
                             if (sum > thr) {
                                 plbs[cl] = __builtin_inff();
@@ -1251,15 +1288,14 @@ void search_kernel(const SearchArgs a) {
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
-                TRIM_TICK(7);
                 qn = qnext;
                 uint16_t *t = qin; qin = qout; qout = t;
                 h0 = h1;
+                ++rnd;
                 if (qn == 0) break;  // this wave has nobody left in this phase
             }
         }
         __syncthreads();
-        TRIM_TICK(2);
         // Several batches in the span and a result set of at most 64: replay (see above), unless
         // the possibles do not fit its arrays (a loose threshold: then batch by batch as below).
         int np_span = -1;
@@ -1300,17 +1336,13 @@ void search_kernel(const SearchArgs a) {
             __syncthreads();
             const int ns = ctl->nsurv;
             __syncthreads();  // nobody appends for the next batch before everyone has read ns
-            TRIM_TICK(3);
             if (ns > 0) refine_and_select(ns);
         }
-        TRIM_TICK(3);
         if (replay_np < 0) advance = span;
         }  // span path
         if (replay_np > 0) {
             __syncthreads();   // the possibles are in place
-            TRIM_TICK(13);
             refine_and_replay(replay_np, c0);
-            TRIM_TICK(15);
         }
         c0 += advance;
     }
@@ -1329,13 +1361,17 @@ void search_kernel(const SearchArgs a) {
             if (a.n_scanned) a.n_scanned[q] = total;
             if (a.n_exact) a.n_exact[q] = ctl->nexact;
         }
-    } else if (tid == 0) {
-        a.chunk_counts[(size_t)q * a.nsplit + split] = ctl->nresult;
-        if (a.n_scanned && split == 0) a.n_scanned[q] = total;
-        if (a.n_exact && ctl->nexact) atomicAdd(&a.n_exact[q], ctl->nexact);
+        if (acct && tid < kWorkCounters) a.work[(size_t)q * kWorkCounters + tid] = ctl->work[tid];
+    } else {
+        if (tid == 0) {
+            a.chunk_counts[(size_t)q * a.nsplit + split] = ctl->nresult;
+            if (a.n_scanned && split == 0) a.n_scanned[q] = total;
+            if (a.n_exact && ctl->nexact) atomicAdd(&a.n_exact[q], ctl->nexact);
+        }
+        // (the host zeroed the array: a query's chunks add up)
+        if (acct && tid < kWorkCounters && ctl->work[tid])
+            atomicAdd(&a.work[(size_t)q * kWorkCounters + tid], ctl->work[tid]);
     }
-    TRIM_TICK(7);
-    TRIM_TICK_FLUSH();
 }
 
 }  // namespace trim

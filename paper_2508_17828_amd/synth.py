@@ -36,7 +36,6 @@ class Workload:
     mode: str = "knn"             # "knn" | "range"
     gammas: Tuple[float, ...] = (0.0,)
     batch: int = 1024
-    first_batch: int = 0      # batches double from this size up to batch (0: all alike)
     range_percentile: float = 0.0  # percent of sampled pair distances inside the radius
     seed: int = 0
     kmeans_iters: int = 10

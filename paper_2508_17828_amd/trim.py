@@ -55,7 +55,11 @@ class _Candidates(C.Structure):
 
 
 class _Stats(C.Structure):
-    _fields_ = [("n_scanned", C.c_void_p), ("n_exact", C.c_void_p)]
+    _fields_ = [("n_scanned", C.c_void_p), ("n_exact", C.c_void_p), ("work", C.c_void_p)]
+
+
+TRIM_WORK_COUNTERS = 8
+WORK_NAMES = ("first_pass", "skipped", "code_bytes", "lookups", "rows", "full_code")
 
 
 _lib = None
@@ -91,7 +95,7 @@ def lib() -> C.CDLL:
         L.trim_build_lut.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                      C.c_void_p, C.c_int32, C.c_void_p]
         L.trim_search_knn.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
-                                      C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.trim_list_bounds_bytes.restype = C.c_size_t
         L.trim_list_bounds_bytes.argtypes = [C.c_int32, C.c_int32]
@@ -269,8 +273,8 @@ def trim_build_lut(queries: torch.Tensor, codebooks: torch.Tensor, mfma: bool = 
 def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, batch: int,
                     probes: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
                     want_stats: bool = True, want_mask: bool = False, out=None,
-                    query_order: Optional[torch.Tensor] = None, first_batch: int = 0):
-    """Returns dict(ids [nq][k] int32, d2 [nq][k] float32, n_scanned, n_exact, mask)."""
+                    query_order: Optional[torch.Tensor] = None, want_work: bool = False):
+    """Returns dict(ids [nq][k] int32, d2 [nq][k] float32, n_scanned, n_exact, mask, work)."""
     nq = queries.shape[0]
     dev = queries.device
     if out is None:
@@ -284,7 +288,12 @@ def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, b
     if want_stats:
         ns = torch.empty((nq,), dtype=torch.int32, device=dev)
         ne = torch.empty((nq,), dtype=torch.int32, device=dev)
-        stats = _Stats(_ptr(ns, torch.int32, "n_scanned"), _ptr(ne, torch.int32, "n_exact"))
+        stats = _Stats(_ptr(ns, torch.int32, "n_scanned"), _ptr(ne, torch.int32, "n_exact"), None)
+    work = None
+    if want_work:
+        work = torch.empty((nq, TRIM_WORK_COUNTERS), dtype=torch.int32, device=dev)
+        stats = stats or _Stats(None, None, None)
+        stats.work = work.data_ptr()
     mask = None
     mw = 0
     if want_mask:
@@ -294,13 +303,13 @@ def trim_search_knn(index: Index, queries: torch.Tensor, k: int, gamma: float, b
     _check(lib().trim_search_knn(C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
                                  _ptr(lut, torch.float32, "lut"),
                                  C.byref(cand) if cand is not None else None, k, gamma, batch,
-                                 first_batch, _ptr(query_order, torch.int32, "query_order"),
+                                 _ptr(query_order, torch.int32, "query_order"),
                                  _ptr(out_ids, torch.int32, "out_ids"),
                                  _ptr(out_d2, torch.float32, "out_d2"),
                                  C.byref(stats) if stats is not None else None,
                                  _ptr(mask, torch.int32, "mask"), mw, _stream()),
            "trim_search_knn")
-    return dict(ids=out_ids, d2=out_d2, n_scanned=ns, n_exact=ne, mask=mask)
+    return dict(ids=out_ids, d2=out_d2, n_scanned=ns, n_exact=ne, mask=mask, work=work)
 
 
 def trim_range_workspace_bytes(nq: int, max_candidates: int) -> int:
@@ -310,7 +319,8 @@ def trim_range_workspace_bytes(nq: int, max_candidates: int) -> int:
 def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma: float,
                       probes: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
                       capacity: int = 0, want_stats: bool = True, want_mask: bool = False,
-                      workspace: Optional[torch.Tensor] = None, static_scratch: bool = False):
+                      workspace: Optional[torch.Tensor] = None, static_scratch: bool = False,
+                      want_work: bool = False):
     """CSR results in scan order: dict(offsets [nq+1] int64, ids, d2, n_scanned, n_exact, mask).
 
     Synchronises once to read the result count; raises TrimCapacityError if a caller-given
@@ -329,7 +339,12 @@ def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma:
     if want_stats:
         ns = torch.empty((nq,), dtype=torch.int32, device=dev)
         ne = torch.empty((nq,), dtype=torch.int32, device=dev)
-        stats = _Stats(_ptr(ns, torch.int32, "n_scanned"), _ptr(ne, torch.int32, "n_exact"))
+        stats = _Stats(_ptr(ns, torch.int32, "n_scanned"), _ptr(ne, torch.int32, "n_exact"), None)
+    work = None
+    if want_work:
+        work = torch.empty((nq, TRIM_WORK_COUNTERS), dtype=torch.int32, device=dev)
+        stats = stats or _Stats(None, None, None)
+        stats.work = work.data_ptr()
     mask = None
     mw = 0
     if want_mask:
@@ -365,7 +380,7 @@ def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma:
     if req > capacity:
         raise TrimCapacityError(req, capacity)
     return dict(offsets=offsets, ids=out_ids[:req], d2=out_d2[:req], n_scanned=ns, n_exact=ne,
-                mask=mask, required=req)
+                mask=mask, required=req, work=work)
 
 
 def trim_ivf_probe(queries: torch.Tensor, centroids: torch.Tensor, nprobe: int) -> torch.Tensor:

@@ -57,11 +57,11 @@ def test_host_side_validation(L):
     assert L.trim_version().decode().count(".") == 1
     assert L.trim_range_workspace_bytes(100, 10_000) >= 100 * 10_000 // 8
     # null index / bad sizes are refused before any HIP call
-    assert L.trim_search_knn(None, None, 1, None, None, 10, 0.0, 64, 0, None, None, None, None, None, 0, None) == -1
+    assert L.trim_search_knn(None, None, 1, None, None, 10, 0.0, 64, None, None, None, None, None, 0, None) == -1
     view = trim._IndexView(10, 128, 32, None, None, None, None, None)
-    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, 0, None, None, None, None, None, 0, None) == -1
+    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, None, None, None, None, None, 0, None) == -1
     view = trim._IndexView(0, 128, 6, None, None, None, None, None)
-    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, 0, None, None, None, None, None, 0, None) == -2
+    assert L.trim_search_knn(C.byref(view), None, 1, None, None, 10, 0.0, 64, None, None, None, None, None, 0, None) == -2
     assert L.trim_encode(None, 5, 128, None, 32, None, None, None) == -1
     assert L.trim_encode(None, 0, 128, None, 32, None, None, None) == 0
     assert L.trim_encode(None, 5, 128, None, 6, None, None, None) == -2
@@ -90,3 +90,21 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2508_17828_amd" not in text, f
+
+
+def test_build_refuses_search_kernels_with_static_lds(L):
+    """The search kernels address their distance table from LDS address 0.  The build parses the
+    compiler's resource remarks and refuses a library in which one of them carries static LDS;
+    the built library's own record shows none does."""
+    from paper_2508_17828_amd import build
+    remarks = ("x.h:1:1: remark: Function Name: _ZN4trim13search_kernelILi0ELi4ELi1ELb0EEEvNS_10SearchArgsE [-R]\n"
+               "x.h:1:1: remark:     VGPRs: 80 [-R]\nx.h:1:1: remark:     AGPRs: 0 [-R]\n"
+               "x.h:1:1: remark:     ScratchSize [bytes/lane]: 0 [-R]\nx.h:1:1: remark:     Occupancy [waves/SIMD]: 6 [-R]\n"
+               "x.h:1:1: remark:     SGPRs Spill: 0 [-R]\nx.h:1:1: remark:     VGPRs Spill: 0 [-R]\n"
+               "x.h:1:1: remark:     LDS Size [bytes/block]: %d [-R]\n")
+    build.check_resources(build.kernel_resources(remarks % 0))
+    with pytest.raises(RuntimeError):
+        build.check_resources(build.kernel_resources(remarks % 64))
+    rec = [l.split() for l in open(build.RESOURCES)]
+    search = [r for r in rec if "search_kernel" in r[0]]
+    assert len(search) >= 12 and all("static_lds=0" in r for r in search)

@@ -27,12 +27,27 @@ def c2(oracle):
     return dict(w=w, bw=bw, host=host, queries=h(bw.queries), probes=probes, trim=trim)
 
 
-def test_encode_sampled_rows(c2, oracle):
+def test_encode_every_row(c2, oracle):
+    """The index the other tests hand to the oracle was encoded by the library: all 1,000,000
+    codes and landmark distances equal the oracle's own encoding."""
     host = c2["host"]
-    rows = np.sort(synth.sample_indices(77, 0, host.n, 4000))
-    codes, dlx = oracle.encode(np.ascontiguousarray(host.base[rows]), host.codebooks)
-    np.testing.assert_array_equal(codes, host.codes[rows])
-    np.testing.assert_array_equal(dlx.view(np.uint32), host.dlx[rows].view(np.uint32))
+    codes, dlx = oracle.encode(host.base, host.codebooks)
+    np.testing.assert_array_equal(codes, host.codes)
+    np.testing.assert_array_equal(dlx.view(np.uint32), host.dlx.view(np.uint32))
+
+
+def test_strict_scan_of_all_n_is_brute_force(c2, oracle):
+    """No candidate structure, gamma = 0, batches of 4096 over all 1,000,000 vectors: the launch
+    shape of an exhaustive search.  Ids and distances equal the oracle's brute force."""
+    T, w, bw, host = c2["trim"], c2["w"], c2["bw"], c2["host"]
+    nq = 200
+    r = T.trim_search_knn(bw.index, bw.queries[:nq].contiguous(), w.k, 0.0, 4096)
+    bi, bd = oracle.brute_knn(host, np.ascontiguousarray(c2["queries"][:nq]), w.k)
+    np.testing.assert_array_equal(r["ids"].cpu().numpy(), bi)
+    np.testing.assert_array_equal(r["d2"].cpu().numpy().view(np.uint32), bd.view(np.uint32))
+    assert np.all(r["n_scanned"].cpu().numpy() == w.n)
+    fi, _ = oracle.brute_knn_f64(host.base, np.ascontiguousarray(c2["queries"][:nq]), w.k, ids=host.ids)
+    assert np.mean(fi == bi) > 0.999     # binary64 order differs only at near-ties
 
 
 def test_probe_selection_sampled_queries(c2, oracle):
@@ -85,7 +100,8 @@ def test_knn_every_query_against_oracle(c2, oracle, gamma, batch, k):
     counters of every query equal the oracle's (the oracle scans them on all host threads; the
     per-candidate masks are compared on the sampled queries above)."""
     T, w, bw, host = c2["trim"], c2["w"], c2["bw"], c2["host"]
-    full = T.trim_search_knn(bw.index, bw.queries, k, gamma, batch, probes=c2["probes"])
+    order = T.trim_query_order(c2["probes"], w.nlist)      # as the benchmark launches it
+    full = T.trim_search_knn(bw.index, bw.queries, k, gamma, batch, probes=c2["probes"], query_order=order)
     ref = oracle.search_knn(host, c2["queries"], k, gamma, batch, c2["probes"].cpu().numpy())
     np.testing.assert_array_equal(full["ids"].cpu().numpy(), ref["ids"])
     np.testing.assert_array_equal(full["d2"].cpu().numpy().view(np.uint32), ref["d2"].view(np.uint32))

@@ -200,13 +200,11 @@ def test_ivf_probe_keys_crowded_in_few_columns(T, oracle):
             np.testing.assert_array_equal(got.cpu().numpy(), oracle.ivf_probe(q, cen, nprobe))
 
 
-def check_knn(T, oracle, b, k, gamma, batch, prebuilt_lut=False, first_batch=0):
+def check_knn(T, oracle, b, k, gamma, batch, prebuilt_lut=False):
     gi, q, probes = to_dev(T, b)
     lut = T.trim_build_lut(q, gi.codebooks) if prebuilt_lut else None
-    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, lut=lut, want_mask=True,
-                            first_batch=first_batch)
-    ref = oracle.search_knn(b.index, b.queries, k, gamma, batch, b.probes, want_mask=True,
-                            first_batch=first_batch or None)
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, lut=lut, want_mask=True)
+    ref = oracle.search_knn(b.index, b.queries, k, gamma, batch, b.probes, want_mask=True)
     np.testing.assert_array_equal(got["n_scanned"].cpu().numpy(), ref["n_scanned"])
     mw = ref["mask"].shape[1]
     np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
@@ -233,16 +231,6 @@ def test_knn_shapes(T, oracle, name, k, batch, gamma):
     if gamma == 0.0:
         bi, _ = oracle.brute_knn(case(name).index, case(name).queries, k, case(name).probes)
         np.testing.assert_array_equal(got["ids"].cpu().numpy(), bi)
-
-
-@pytest.mark.parametrize("name,k,batch,first", [("c2s", 10, 1024, 64), ("c2s", 10, 1024, 1),
-                                                ("c2s", 70, 333, 5), ("c5s", 10, 1024, 128),
-                                                ("c3s", 100, 4096, 256), ("c4s", 10, 2048, 64),
-                                                ("c1", 10, 100, 7), ("c1", 10, 4096, 4096)])
-@pytest.mark.parametrize("gamma", [0.0, 0.5])
-def test_knn_growing_batches(T, oracle, name, k, batch, first, gamma):
-    """Batches that double from `first` up to `batch` (first = batch: the fixed-size rule)."""
-    check_knn(T, oracle, case(name), k, gamma, batch, first_batch=first)
 
 
 @pytest.mark.parametrize("name", ["c2s", "c4s"])
@@ -441,6 +429,45 @@ def test_tiled_codes_are_a_copy_and_change_no_result(T, oracle, name):
         T.trim_pack_codes_tiled(torch.zeros((4, 24), dtype=torch.uint8, device="cuda"))
 
 
+@pytest.mark.parametrize("name,k,batch,gamma", [("c2s", 10, 1024, 0.4), ("c5s", 10, 64, 0.0), ("c3s", 100, 512, 0.3),
+                                                ("c4s", 10, 2048, 0.5), ("c1", 10, 256, 0.6)])
+def test_work_counters_account_for_every_candidate(T, oracle, name, k, batch, gamma):
+    """The optional accounting of a search: results are those of a launch without it, and the
+    counters add up: every candidate is a seed, was read in the first pass, or was passed over
+    with its list (a stretch that had to be redone is read twice); exact distances computed
+    cover the counted survivors; lookups and bytes lie between what the first pass alone and
+    a full evaluation of every candidate would need."""
+    b = case(name)
+    gi, q, probes = to_dev(T, b)
+    M = b.index.M
+    plain = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True)
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True, want_work=True)
+    for key in ("ids", "d2", "n_scanned", "n_exact", "mask"):
+        np.testing.assert_array_equal(u32(got[key]), u32(plain[key]), err_msg=key)
+    w = got["work"].cpu().numpy().astype(np.int64)
+    ns, ne = got["n_scanned"].cpu().numpy().astype(np.int64), got["n_exact"].cpu().numpy().astype(np.int64)
+    seeds = np.minimum(k, ns)
+    first, skipped, cbytes, looks, rows, fullc = (w[:, i] for i in range(6))
+    assert np.all(first + skipped + seeds >= ns)
+    assert np.mean(first + skipped + seeds == ns) > 0.5          # redone stretches are the exception
+    assert np.all(rows >= ne) and np.all(rows <= ns)
+    assert np.all(fullc <= first) and np.all(looks <= first * M) and np.all(looks >= 4 * first)
+    assert np.all(cbytes >= 8 * first) and np.all(cbytes <= first * (2 * M + 24) + 64 * 1024 * M)
+    assert np.all(w[:, 6:] == 0)
+    # range mode: the chunks of a query add up; no list is passed over there
+    radius = helpers.radius_at_percentile(b, 2.0)
+    r0 = T.trim_search_range(gi, q, radius, gamma, probes=probes)
+    r1 = T.trim_search_range(gi, q, radius, gamma, probes=probes, want_work=True)
+    for key in ("offsets", "ids", "d2", "n_scanned", "n_exact"):
+        np.testing.assert_array_equal(u32(r1[key]) if r1[key].dtype.is_floating_point else r1[key].cpu().numpy(),
+                                      u32(r0[key]) if r0[key].dtype.is_floating_point else r0[key].cpu().numpy(), err_msg=key)
+    w = r1["work"].cpu().numpy().astype(np.int64)
+    np.testing.assert_array_equal(w[:, 0], r1["n_scanned"].cpu().numpy())
+    np.testing.assert_array_equal(w[:, 1], 0)
+    np.testing.assert_array_equal(w[:, 4], r1["n_exact"].cpu().numpy())
+    assert np.all(w[:, 3] <= w[:, 0] * M) and np.all(w[:, 3] >= 4 * w[:, 0])
+
+
 def test_knn_is_deterministic(T, oracle):
     b = case("c5s")
     gi, q, probes = to_dev(T, b)
@@ -485,11 +512,10 @@ def test_argument_errors(T):
     b = case("c1")
     gi, q, _ = to_dev(T, b)
     for kw in (dict(k=0), dict(k=T.TRIM_MAX_K + 1), dict(batch=0), dict(batch=T.TRIM_MAX_BATCH + 1),
-               dict(gamma=-0.1), dict(gamma=float("nan")), dict(first_batch=65), dict(first_batch=-1)):
-        args = dict(k=10, gamma=0.0, batch=64, first_batch=0); args.update(kw)
+               dict(gamma=-0.1), dict(gamma=float("nan"))):
+        args = dict(k=10, gamma=0.0, batch=64); args.update(kw)
         with pytest.raises(T.TrimError):
-            T.trim_search_knn(gi, q, args["k"], args["gamma"], args["batch"],
-                              first_batch=args["first_batch"])
+            T.trim_search_knn(gi, q, args["k"], args["gamma"], args["batch"])
     assert not T.trim_shape_supported(130, 16) and not T.trim_shape_supported(128, 6)
     assert T.trim_shape_supported(128, 32) and T.trim_shape_supported(1536, 192)
     with pytest.raises(TypeError):

@@ -82,7 +82,7 @@ def test_random_configuration(oracle, seed):
     import torch
     from paper_2508_17828_amd import trim as T
     T.lib()
-    w, k, batch, first, gamma = (draw(seed) if seed < 1000 else draw_long(seed - 1000) if seed < 2000
+    w, k, batch, _, gamma = (draw(seed) if seed < 1000 else draw_long(seed - 1000) if seed < 2000
                                  else draw_ivf_long(seed - 2000))
     b = helpers.build(w, pq_train_max=4096, ivf_train_per_list=32)
     ix = b.index
@@ -97,12 +97,11 @@ def test_random_configuration(oracle, seed):
     if ix.list_offsets is not None and (seed % 3 != 0 or seed >= 2000):   # list-level pruning on in two draws of three
         gi.list_bounds = T.trim_pack_list_bounds(gi)
     q, probes = t(b.queries), t(b.probes)
-    what = f"seed {seed}: n={w.n} d={w.d} M={w.M} k={k} batch={batch} first={first} gamma={gamma} " \
+    what = f"seed {seed}: n={w.n} d={w.d} M={w.M} k={k} batch={batch} gamma={gamma} " \
            f"nlist={w.nlist} nprobe={w.nprobe} law={w.law}"
     print(what, flush=True)
-    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True, first_batch=first)
-    ref = oracle.search_knn(ix, b.queries, k, gamma, batch, b.probes, want_mask=True,
-                            first_batch=first or None)
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, want_mask=True)
+    ref = oracle.search_knn(ix, b.queries, k, gamma, batch, b.probes, want_mask=True)
     mw = ref["mask"].shape[1]
     np.testing.assert_array_equal(got["mask"].cpu().numpy().view(np.uint32)[:, :mw], ref["mask"], err_msg=what)
     np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"], err_msg=what)

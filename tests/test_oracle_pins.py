@@ -244,6 +244,36 @@ def test_strict_knn_equals_brute_force(oracle, which, request):
     assert r["n_exact"].sum() < 0.8 * r["n_scanned"].sum()      # it does prune
 
 
+def test_float64_brute_force_is_the_definition(oracle, tiny, tiny_ivf):
+    """brute_knn_f64 (the ground truth behind recall@k, Section 2.1) against numpy's float64
+    distances over ALL n, ids through the position -> id map, ties to the smaller id; with
+    planted duplicates so that the tie rule is exercised; short inputs are padded."""
+    for b in (tiny, tiny_ivf):
+        ix, k = b.index, 7
+        base = ix.base.copy()
+        base[11] = base[3]; base[200] = base[3]            # three equal rows: ties on every query
+        ids = ix.ids if ix.ids is not None else np.arange(ix.n, dtype=np.int32)
+        got_i, got_d = oracle.brute_knn_f64(base, b.queries, k, ids=ix.ids)
+        q64, x64 = b.queries.astype(np.float64), base.astype(np.float64)
+        for qi in range(b.queries.shape[0]):
+            d2 = ((q64[qi][None, :] - x64) ** 2).sum(1)
+            o = np.lexsort((ids, d2))[:k]
+            np.testing.assert_array_equal(got_i[qi], ids[o])
+            np.testing.assert_allclose(got_d[qi], d2[o], rtol=1e-13)
+        # a query equal to the triplicated row: the three copies come first, by ascending id
+        gi, gd = oracle.brute_knn_f64(base, np.ascontiguousarray(base[3:4]), 3, ids=ix.ids)
+        assert list(gi[0]) == sorted(int(ids[p]) for p in (3, 11, 200)) and np.all(gd == 0.0)
+    # fewer than k vectors: padded with (-1, +inf)
+    gi, gd = oracle.brute_knn_f64(np.ascontiguousarray(tiny.index.base[:4]), tiny.queries[:2], 6)
+    assert np.all(gi[:, 4:] == -1) and np.all(np.isinf(gd[:, 4:])) and np.all(gi[:, :4] >= 0)
+    # and it agrees with the binary32 brute force wherever the binary64 distances are well apart
+    bi, _ = oracle.brute_knn(tiny.index, tiny.queries, 10)
+    fi, fd = oracle.brute_knn_f64(tiny.index.base, tiny.queries, 10)
+    for qi in range(tiny.queries.shape[0]):
+        if np.min(np.diff(fd[qi])) > 1e-5 * fd[qi][-1]:
+            np.testing.assert_array_equal(bi[qi], fi[qi])
+
+
 @pytest.mark.parametrize("which", ["tiny", "tiny_ivf"])
 def test_strict_range_equals_brute_force(oracle, which, request):
     b = request.getfixturevalue(which)
@@ -329,48 +359,6 @@ def test_batch_one_is_the_sequential_rule(oracle, tiny):
             nexact += 1
         assert [p for _, p in R] == list(r["ids"][qi])
         assert nexact == r["n_exact"][qi]
-
-
-def test_batch_schedule_is_the_stated_doubling_rule(oracle, tiny):
-    """Batches of first_batch, 2*first_batch, ... capped at batch, each with tau frozen at its
-    start: replayed here candidate by candidate from the bound and the exact distance alone."""
-    b, k, gam = tiny, 5, 0.5
-    ix = b.index
-    lut = oracle.build_lut(b.queries, ix.codebooks)
-    for first, cap in ((3, 40), (1, 8), (16, 16)):
-        r = oracle.search_knn(ix, b.queries, k, gam, cap, want_mask=True, first_batch=first)
-        sizes = []
-        for qi in range(3):
-            q = b.queries[qi]
-            R = [(oracle.exact_d2(q, ix.base[pos]), pos) for pos in range(k)]
-            R.sort()
-            nexact, idx, size = k, k, first
-            while idx < ix.n:
-                tau = R[k - 1][0]
-                end = min(idx + size, ix.n)
-                if qi == 0:
-                    sizes.append(end - idx)
-                pos = np.arange(idx, end)
-                _, g = oracle.plb_pairs(lut, ix.codes, ix.dlx, np.full(len(pos), qi), pos, gam)
-                keep = pos[g <= tau]
-                got = np.array([(r["mask"][qi, p // 32] >> (p % 32)) & 1 for p in pos], bool)
-                np.testing.assert_array_equal(got, g <= tau)
-                R += [(oracle.exact_d2(q, ix.base[p]), int(p)) for p in keep]
-                R.sort(); R = R[:k]
-                nexact += len(keep)
-                idx, size = end, min(cap, 2 * size)
-            assert [p for _, p in R] == list(r["ids"][qi])
-            assert nexact == r["n_exact"][qi]
-        full = [x for x in sizes[:-1]]
-        assert full[0] == first and all(y == min(cap, 2 * x) for x, y in zip(full, full[1:]))
-    # first_batch = batch is the plain fixed-size rule; with gamma = 0 no schedule changes the result
-    a0 = oracle.search_knn(ix, b.queries, k, gam, 16, want_mask=True)
-    a1 = oracle.search_knn(ix, b.queries, k, gam, 16, want_mask=True, first_batch=16)
-    for key in ("ids", "d2", "n_exact", "mask"):
-        np.testing.assert_array_equal(a0[key], a1[key])
-    bi, _ = oracle.brute_knn(ix, b.queries, k)
-    for first, cap in ((1, 64), (5, 333), (64, 1024)):
-        np.testing.assert_array_equal(oracle.search_knn(ix, b.queries, k, 0.0, cap, first_batch=first)["ids"], bi)
 
 
 def test_short_candidate_lists_are_padded(oracle):
