@@ -449,9 +449,12 @@ def test_work_counters_account_for_every_candidate(T, oracle, name, k, batch, ga
     seeds = np.minimum(k, ns)
     first, skipped, cbytes, looks, rows, fullc = (w[:, i] for i in range(6))
     assert np.all(first + skipped + seeds >= ns)
-    assert np.mean(first + skipped + seeds == ns) > 0.5          # redone stretches are the exception
+    assert np.all(first + skipped + seeds <= 2 * ns)
+    if name in ("c1", "c2s", "c5s"):     # (c3s: the one long stretch overflows its list of possibles and is redone)
+        assert np.mean(first + skipped + seeds == ns) > 0.5
     assert np.all(rows >= ne) and np.all(rows <= ns)
-    assert np.all(fullc <= first) and np.all(looks <= first * M) and np.all(looks >= 4 * first)
+    # (a candidate that passes the first 8 subspaces has its sum redone from the start: M + 8 lookups at most)
+    assert np.all(fullc <= first) and np.all(looks <= first * (M + 8)) and np.all(looks >= 4 * first)
     assert np.all(cbytes >= 8 * first) and np.all(cbytes <= first * (2 * M + 24) + 64 * 1024 * M)
     assert np.all(w[:, 6:] == 0)
     # range mode: the chunks of a query add up; no list is passed over there
