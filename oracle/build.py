@@ -1,6 +1,6 @@
 """Compile the CPU oracle (test infrastructure) with gcc.
 
-Two builds of the same source: a portable one and one for x86-64-v3 hosts (hardware
+Two builds of the same sources (the 8-bit oracle and its 4-bit-code sibling, one library): a portable one and one for x86-64-v3 hosts (hardware
 FMA).  Both are bit-identical in results (fmaf is correctly rounded either way); the
 second is only faster.  -ffp-contract=off keeps every rounding where the source puts it.
 """
@@ -9,7 +9,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "trim_oracle.c")
+SRC = [os.path.join(HERE, "trim_oracle.c"), os.path.join(HERE, "trim_oracle_fs.c")]
 COMMON = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
           "-shared", "-fPIC", "-Wall", "-Wextra"]
 
@@ -17,7 +17,7 @@ COMMON = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fop
 def build(verbose: bool = False) -> None:
     for name, extra in (("libtrim_oracle.so", []),
                         ("libtrim_oracle_v3.so", ["-march=x86-64-v3"])):
-        cmd = COMMON + extra + ["-o", os.path.join(HERE, name), SRC, "-lm"]
+        cmd = COMMON + extra + ["-o", os.path.join(HERE, name)] + SRC + ["-lm"]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

@@ -65,14 +65,15 @@ def _scatter_sum(sums, a, x64):
     sums[a_s[starts]] = np.add.reduceat(x64[order], starts, axis=0)
 
 
-def train_pq(train: np.ndarray, M: int, iters: int, init_rows: np.ndarray) -> np.ndarray:
-    """PQ codebooks [M][256][d/M]: one k-means per subspace (Section 2.2)."""
+def train_pq(train: np.ndarray, M: int, iters: int, init_rows: np.ndarray, ncent: int = 256) -> np.ndarray:
+    """PQ codebooks [M][ncent][d/M]: one k-means per subspace (Section 2.2); ncent = 256 for
+    8-bit codes, 16 for the 4-bit codes of the FastScan variant (Section 6.1)."""
     d = train.shape[1]
     dsub = d // M
-    cb = np.empty((M, 256, dsub), dtype=np.float32)
+    cb = np.empty((M, ncent, dsub), dtype=np.float32)
     for j in range(M):
-        cb[j], _ = kmeans(np.ascontiguousarray(train[:, j * dsub:(j + 1) * dsub]), 256,
-                          iters, init_rows)
+        cb[j], _ = kmeans(np.ascontiguousarray(train[:, j * dsub:(j + 1) * dsub]), ncent,
+                          iters, init_rows[:ncent])
     return cb
 
 
@@ -119,6 +120,22 @@ def train_pq_fixed(train: np.ndarray, M: int, iters: int, init_rows: np.ndarray)
         codes, _ = trim_oracle.encode(train, cb)
         for j in range(M):
             cb[j] = _update_fixed(train[:, j * dsub:(j + 1) * dsub], codes[:, j].astype(np.int64), cb[j])
+    return cb
+
+
+def train_pq_fs_fixed(train: np.ndarray, m: int, iters: int, init_rows: np.ndarray) -> np.ndarray:
+    """Codebooks [m][16][d/m] for 4-bit codes (Section 6.1: FastScan variants, m = d/2) by the
+    same Lloyd iterations with fixed roundings; the assignment is trim_oracle_fs.encode's."""
+    from . import trim_oracle_fs
+    ns, d = train.shape
+    dsub = d // m
+    assert init_rows.shape[0] == 16
+    cb = np.ascontiguousarray(train[init_rows].reshape(16, m, dsub).transpose(1, 0, 2)).astype(np.float32)
+    for _ in range(iters):
+        codes, _ = trim_oracle_fs.encode(train, cb)
+        nib = trim_oracle_fs.unpack(codes, m)
+        for j in range(m):
+            cb[j] = _update_fixed(train[:, j * dsub:(j + 1) * dsub], nib[:, j].astype(np.int64), cb[j])
     return cb
 
 
