@@ -69,6 +69,9 @@ typedef struct trim_index_view {
     const float *codebooks; /* [M][256][d/M] */
     const void *scan_head;  /* [n] records of 12 bytes or NULL: see trim_pack_scan_head */
     const void *codes_tiled; /* tiled copy of codes or NULL: see trim_pack_codes_tiled */
+    int32_t code_bits;      /* 0 or 8: the layout above.  4: the 4-bit codes of the FastScan variant
+                               (see trim_fs_encode): M subspaces of 16 centroids, M % 16 == 0,
+                               codes [n][M/2], codebooks [M][16][d/M] */
 } trim_index_view;
 
 /* Which stored positions a query scans, and in what order: the lists probes[q][0],
@@ -125,6 +128,36 @@ typedef struct trim_stats {
 /* 1 if (d, M) can be searched by this build, else 0.  Needs d % 4 == 0, d % M == 0,
  * M % 4 == 0, d/M <= 64, and room in the 160 KB of LDS for the kernel's working set. */
 int trim_shape_supported(int32_t d, int32_t M);
+/* The same for an index with 4-bit codes (code_bits = 4): needs d % 4 == 0, d % M == 0,
+ * M % 16 == 0, d/M <= 64. */
+int trim_fs_shape_supported(int32_t d, int32_t M);
+
+/*
+ * The index of the paper's FastScan-compatible variant (Section 6.1, parameter setting: 4-bit
+ * codes with m = d/2 subspaces; evaluated in Section 6.2.2): every subspace has 16 centroids, so
+ * a landmark code takes 4 bits per subspace and a query's distance table 16 entries per
+ * subspace.  The method is unchanged (landmark = PQ reconstruction, Section 3.1; Equation 3; the
+ * scan of Section 4.2); trim_search_knn, trim_search_range, trim_pack_scan_head,
+ * trim_pack_codes_tiled and trim_pack_list_bounds take such an index when
+ * trim_index_view.code_bits = 4.  The table keeps binary32 entries (Section 3.1 computes
+ * Gamma(l,q) exactly from it), summed left to right over the M subspaces.  A row of 16 table
+ * entries spans 16 banks of the on-chip memory, so lanes that look up different centroids
+ * never collide, which the 256-entry rows of 8-bit codes cannot avoid.
+ *
+ * trim_fs_encode: codes_out [n][M/2] device, two codes per byte, subspace 2i in the low half of
+ * byte i, subspace 2i+1 in the high half (nearest centroid, smallest index on ties);
+ * dlx_out [n] = Gamma(l,x).  codebooks [M][16][d/M] device.  M even.
+ * trim_fs_build_lut: lut_out [nq][M][16] device (may be passed to the searches as `lut`).
+ * trim_fs_train_pq: Lloyd's k-means with 16 centroids per subspace and the fixed roundings of
+ * trim_train_pq; init_rows [16] device; assign_ws [ns][M] bytes of work space (on return: the
+ * last iteration's assignment, one byte per subspace).
+ */
+int trim_fs_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
+                   uint8_t *codes_out, float *dlx_out, void *stream);
+int trim_fs_build_lut(const float *queries, int64_t nq, int32_t d, const float *codebooks, int32_t M,
+                      float *lut_out, void *stream);
+int trim_fs_train_pq(const float *train, int64_t ns, int32_t d, int32_t M, int32_t iters,
+                     const int32_t *init_rows, float *codebooks_out, uint8_t *assign_ws, void *stream);
 
 /*
  * Preprocessing step 1 of Section 3.3: codes_out[x][j] = index of the centroid of subspace j
@@ -183,6 +216,8 @@ int trim_estimate_gamma(const trim_index_view *index, const int32_t *sample_rows
  * trim_index_view.scan_head is given, provided it was packed from the same codes and dlx
  * (it is not checked against them).  Needs M % 8 == 0 (else TRIM_UNSUPPORTED_SHAPE).
  * codes [n][M] device, dlx [n] device, head_out [n][12 bytes] device, 4-byte aligned.
+ * Here and in trim_pack_codes_tiled M is the number of BYTES of a stored code: the number of
+ * subspaces for 8-bit codes, half of it for 4-bit codes (the head then covers 16 subspaces).
  */
 #define TRIM_SCAN_HEAD_BYTES 12
 int trim_pack_scan_head(const uint8_t *codes, const float *dlx, int64_t n, int32_t M,
@@ -328,7 +363,9 @@ int trim_query_order(const int32_t *probes, int64_t nq, int32_t nprobe, int32_t 
  * over all subspaces, if it exceeds (max landmark distance + sqrt(tau))^2, shows that Equation 3
  * is above tau for the whole list at every gamma >= 0.
  * list_offsets [nlist+1] device; the index needs codes and dlx.  out: device,
- * trim_list_bounds_bytes(nlist, index->M) bytes, 16-byte aligned.
+ * trim_list_bounds_bytes(nlist, bytes of one stored code) bytes, 16-byte aligned (the bytes of a
+ * code: index->M for 8-bit codes, index->M / 2 for 4-bit codes, where a "code" above is a code
+ * byte, i.e. the pair of codes of two neighbouring subspaces).
  */
 size_t trim_list_bounds_bytes(int32_t nlist, int32_t M);
 int trim_pack_list_bounds(const trim_index_view *index, const int64_t *list_offsets, int32_t nlist,
@@ -351,6 +388,9 @@ int trim_pack_list_bounds(const trim_index_view *index, const int64_t *list_offs
  * sequence of the scan's own table sums (one lookup and one addition per code byte), and
  * writes its sum to sink [blocks * 512] (device).  1 <= iters <= 2^20.
  * blocks * 512 * iters * 32 / time = lookups per second with nothing else going on.
+ * entry_floats = 16: the same for 4-bit codes, a [64][16] table and 64 lookups per iteration
+ * (blocks * 512 * iters * 64 lookups); rows of 16 entries never make two lanes collide, so this
+ * is also the rate of conflict-free 4-byte reads of the on-chip memory.
  * entry_floats = 2 or 4: the table has 8 rows of 256 entries of that many binary32 values
  * (what a table shared by 2 or 4 queries would hold); every thread performs iters * 8 lookups
  * of a whole entry and adds its values up.  Other values: TRIM_INVALID_ARG.

@@ -64,10 +64,11 @@ def check_resources(res) -> None:
                            "address 0): " + ", ".join(bad))
 
 
-def build(verbose: bool = False, extra=()) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = OUT + ".tmp"
-    cmd = [hipcc] + FLAGS + list(extra) + ["-o", tmp, os.path.join(CSRC, "trim_api.hip")]
+# The search kernel's instances: one object per (mode, result entries per lane, bits per code).
+INSTANCES = [(0, e, b) for b in (8, 4) for e in (1, 2, 4, 16)] + [(1, 1, 8), (1, 1, 4)]
+
+
+def _compile(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     p = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
@@ -76,12 +77,34 @@ def build(verbose: bool = False, extra=()) -> str:
         print("\n".join(rest), file=sys.stderr, flush=True)
     if p.returncode != 0:
         raise subprocess.CalledProcessError(p.returncode, cmd)
-    res = kernel_resources(p.stderr)
-    try:
-        check_resources(res)
-    except RuntimeError:
-        os.remove(tmp)
-        raise
+    return kernel_resources(p.stderr)
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    """Compile the API translation unit and every group of search-kernel instances (in parallel),
+    check the kernels' resources, link libtrim.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    cflags = [f for f in FLAGS if f != "-shared"] + list(extra) + ["-c"]
+    jobs = [([hipcc] + cflags + ["-o", os.path.join(objdir, "trim_api.o"), os.path.join(CSRC, "trim_api.hip")])]
+    for mode, e, bits in INSTANCES:
+        obj = os.path.join(objdir, f"search_m{mode}_e{e}_c{bits}.o")
+        jobs.append([hipcc] + cflags + [f"-DTRIM_INST_MODE={mode}", f"-DTRIM_INST_E={e}",
+                                        f"-DTRIM_INST_BITS={bits}", "-o", obj,
+                                        os.path.join(CSRC, "trim_search_inst.hip")])
+    workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 4))))
+    res = {}
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        for r in pool.map(lambda c: _compile(c, verbose), jobs):
+            res.update(r)
+    check_resources(res)
+    tmp = OUT + ".tmp"
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + [j[j.index("-o") + 1] for j in jobs]
+    if verbose:
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     os.replace(tmp, OUT)
     with open(RESOURCES, "w") as f:
         for name in sorted(res):

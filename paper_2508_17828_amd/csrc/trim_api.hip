@@ -10,17 +10,23 @@
 #include <mutex>
 
 #include "trim_aux.h"
-#include "trim_search.h"
+#include "trim_launch.h"
 
 // Scratch area of trim_search_range_static (see below): device memory inside the library's code
 // object; every GPU the library runs on holds its own copy at its own address.
 static __device__ __align__(256) unsigned char scratch[TRIM_STATIC_SCRATCH_BYTES];
 
+namespace trim {
+thread_local int g_last_hip_error = 0;
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return TRIM_HIP_ERROR;
+}
+}  // namespace trim
+
 namespace {
 
 using namespace trim;
-
-thread_local int g_last_hip_error = 0;
 
 static_assert(kWorkCounters == TRIM_WORK_COUNTERS && kWorkFirstPass == TRIM_WORK_FIRST_PASS &&
               kWorkSkipped == TRIM_WORK_SKIPPED && kWorkCodeBytes == TRIM_WORK_CODE_BYTES &&
@@ -29,28 +35,10 @@ static_assert(kWorkCounters == TRIM_WORK_COUNTERS && kWorkFirstPass == TRIM_WORK
 
 constexpr size_t kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
 
-int hip_fail(hipError_t e) {
-    g_last_hip_error = (int)e;
-    return TRIM_HIP_ERROR;
-}
-
-#define HIP_TRY(expr)                                   \
-    do {                                                \
-        hipError_t _e = (expr);                         \
-        if (_e != hipSuccess) return hip_fail(_e);      \
-    } while (0)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t up16(size_t x) { return (x + 15u) & ~size_t(15); }
 
-struct Plan {
-    int threads;
-    int P, Mp, vec;
-    size_t lds;
-    uint32_t off_q, off_segp, off_segd, off_rest, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
-    uint32_t off_plb, off_cnt, off_wq;
-    int span, wqcap, cruise, poss_cap, scap, rcap, bucket;
-};
 
 // Decide table phases, block size and LDS layout for a search launch.
 // cap = survivor-list capacity (max(batch,k) for kNN, round size for range).
@@ -76,8 +64,8 @@ constexpr Tier kTiers[] = {{256, 40960, false}, {512, 53760, true}, {512, 81920,
 
 // One attempt: table phases P, a footprint tier, a span; need_poss: only layouts with a possibles
 // list (a cruise) count.
-bool fit_plan(int d, int M, int nsegs, int cap, int batch, int k, bool range, int P, const Tier &tier,
-              int span, bool need_poss, Plan *pl) {
+bool fit_plan(int d, int M, int row_bytes, int nsegs, int cap, int batch, int k, bool range, int P,
+              const Tier &tier, int span, bool need_poss, Plan *pl) {
     const int Mp = M / P;
     const int nbatch = span / batch;
     // cruise stretches (kNN): up to 61440 candidates (16-bit queue entries).  Their possibles
@@ -89,7 +77,7 @@ bool fit_plan(int d, int M, int nsegs, int cap, int batch, int k, bool range, in
     if (cruise / batch > 1024) bucket = batch * (((cruise + 1023) / 1024 + batch - 1) / batch);
     const int nbucket = cruise > 0 ? (cruise + bucket - 1) / bucket : 0;
     const int ncnt = nbucket > nbatch ? nbucket : nbatch;
-    const size_t tab = (size_t)Mp * kC * 4;
+    const size_t tab = (size_t)Mp * row_bytes;
     const bool can_cruise = cruise > 0 && P == 1;  // table phases need block-wide barriers
     if (need_poss && !can_cruise) return false;
     const int nwaves = tier.threads / 64;
@@ -155,8 +143,11 @@ bool fit_plan(int d, int M, int nsegs, int cap, int batch, int k, bool range, in
     return false;
 }
 
-bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
-    if (d <= 0 || M <= 0 || d % 4 || d % M || M % 4 || d / M > 64) return false;
+// M counts code bytes; fs: 4-bit codes (two subspaces of 16 centroids per byte), else 8-bit.
+bool make_plan(int d, int M, bool fs, int nseg, int cap, int batch, int k, bool range, Plan *pl) {
+    if (d <= 0 || M <= 0 || d % 4 || M % 4) return false;
+    if (fs ? (d % (2 * M) || M % 8 || d / (2 * M) > 64) : (d % M || d / M > 64)) return false;
+    const int row_bytes = fs ? (int)kByteRow<true> : (int)kByteRow<false>;
     const int nsegs = nseg > 0 ? nseg : 1;
     int nbatch = (range ? kSpanRange : kSpanKnn) / batch;
     if (nbatch < 1) nbatch = 1;
@@ -173,7 +164,7 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                 // below the last tier a layout must leave room for a cruise when one is possible
                 // at all (else the next tier is tried first)
                 const bool cruise_possible = !range && P == 1 && 61440 / batch * batch >= 2 * span;
-                if (fit_plan(d, M, nsegs, cap, batch, k, range, P, tier, span, cruise_possible, pl)) return true;
+                if (fit_plan(d, M, row_bytes, nsegs, cap, batch, k, range, P, tier, span, cruise_possible, pl)) return true;
                 continue;
             }
             // One workgroup per CU whatever the span: kNN takes the longest span that fits (fewer
@@ -184,73 +175,45 @@ bool make_plan(int d, int M, int nseg, int cap, int batch, int k, bool range, Pl
                     for (int target = kSpanLong; target > span; target -= 1024) {
                         const int longer = target / batch * batch;
                         if (longer <= span || longer / batch > kMaxBatchesPerSpan) continue;
-                        if (fit_plan(d, M, nsegs, cap, batch, k, range, P, tier, longer, pass == 0, pl)) return true;
+                        if (fit_plan(d, M, row_bytes, nsegs, cap, batch, k, range, P, tier, longer, pass == 0, pl)) return true;
                     }
             }
-            if (fit_plan(d, M, nsegs, cap, batch, k, range, P, tier, span, false, pl)) return true;
+            if (fit_plan(d, M, row_bytes, nsegs, cap, batch, k, range, P, tier, span, false, pl)) return true;
         }
     }
     return false;
 }
 
-template <int MODE, int E, bool ACCT>
-int launch_search_a(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
-    void (*fn)(const SearchArgs) = nullptr;
-    switch (pl.vec) {
-        case 4: fn = search_kernel<MODE, 4, E, ACCT>; break;
-        case 2: fn = search_kernel<MODE, 2, E, ACCT>; break;
-        default: fn = search_kernel<MODE, 1, E, ACCT>; break;
+// The search kernel's instances are compiled in translation units of their own
+// (trim_search_inst.hip); this picks the one for a launch.
+int launch_search(bool range, bool fs, const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
+    if (range) return fs ? launch_search_range_e1_c4(a, pl, grid, st) : launch_search_range_e1_c8(a, pl, grid, st);
+    // k decides how many result entries a lane of the merging wave holds (result_slots)
+    switch (result_slots(a.k)) {
+        case 1: return fs ? launch_search_knn_e1_c4(a, pl, grid, st) : launch_search_knn_e1_c8(a, pl, grid, st);
+        case 2: return fs ? launch_search_knn_e2_c4(a, pl, grid, st) : launch_search_knn_e2_c8(a, pl, grid, st);
+        case 4: return fs ? launch_search_knn_e4_c4(a, pl, grid, st) : launch_search_knn_e4_c8(a, pl, grid, st);
+        default: return fs ? launch_search_knn_e16_c4(a, pl, grid, st) : launch_search_knn_e16_c8(a, pl, grid, st);
     }
-    // The kernel addresses its distance table with immediate offsets from LDS address 0, so it
-    // must own the workgroup's LDS from the first byte: an instance that was built with static
-    // LDS in front of the dynamic area is refused here instead of being launched.
-    static std::atomic<int> lds_checked[3];   // per instance (MODE, E, ACCT) and code-load width
-    std::atomic<int> &seen = lds_checked[pl.vec == 4 ? 2 : pl.vec == 2 ? 1 : 0];
-    if (seen.load(std::memory_order_acquire) == 0) {
-        hipFuncAttributes fa;
-        HIP_TRY(hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(fn)));
-        seen.store(fa.sharedSizeBytes == 0 ? 1 : -1, std::memory_order_release);
-    }
-    if (seen.load(std::memory_order_acquire) < 0) return TRIM_INTERNAL;
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds));
-    hipLaunchKernelGGL(fn, grid, dim3(pl.threads), pl.lds, st, a);
-    HIP_TRY(hipGetLastError());
-    return TRIM_OK;
 }
 
-template <int MODE, int E>
-int launch_search_e(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
-    return a.work ? launch_search_a<MODE, E, true>(a, pl, grid, st)
-                  : launch_search_a<MODE, E, false>(a, pl, grid, st);
-}
-
-// k decides how many result entries a lane of the merging wave holds (result_slots).
-template <int MODE>
-int launch_search(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
-    if constexpr (MODE == kRange) {
-        return launch_search_e<MODE, 1>(a, pl, grid, st);
-    } else {
-        switch (result_slots(a.k)) {
-            case 1: return launch_search_e<MODE, 1>(a, pl, grid, st);
-            case 2: return launch_search_e<MODE, 2>(a, pl, grid, st);
-            case 4: return launch_search_e<MODE, 4>(a, pl, grid, st);
-            default: return launch_search_e<MODE, 16>(a, pl, grid, st);
-        }
-    }
-}
+// 4-bit codes (two per byte, 16 centroids per subspace)?  Bytes of one stored code.
+inline bool is_fs(const trim_index_view *ix) { return ix->code_bits == 4; }
+inline int code_bytes(const trim_index_view *ix) { return is_fs(ix) ? ix->M / 2 : ix->M; }
 
 int check_index(const trim_index_view *ix) {
     if (!ix) return TRIM_INVALID_ARG;
     if (ix->n < 0 || ix->n >= (int64_t(1) << 31)) return TRIM_INVALID_ARG;
     if (ix->d <= 0 || ix->M <= 0) return TRIM_INVALID_ARG;
-    if (!trim_shape_supported(ix->d, ix->M)) return TRIM_UNSUPPORTED_SHAPE;
+    if (ix->code_bits != 0 && ix->code_bits != 8 && ix->code_bits != 4) return TRIM_INVALID_ARG;
+    if (!(is_fs(ix) ? trim_fs_shape_supported(ix->d, ix->M) : trim_shape_supported(ix->d, ix->M)))
+        return TRIM_UNSUPPORTED_SHAPE;
     if (ix->n > 0 && (!ix->base || !ix->codes || !ix->dlx)) return TRIM_INVALID_ARG;
     if (!aligned16(ix->base) || !aligned16(ix->codes) || !aligned16(ix->codebooks))
         return TRIM_INVALID_ARG;
-    if (ix->scan_head && ((reinterpret_cast<uintptr_t>(ix->scan_head) & 3u) || ix->M % 8))
+    if (ix->scan_head && ((reinterpret_cast<uintptr_t>(ix->scan_head) & 3u) || code_bytes(ix) % 8))
         return TRIM_INVALID_ARG;
-    if (ix->codes_tiled && (!aligned16(ix->codes_tiled) || ix->M % 16)) return TRIM_INVALID_ARG;
+    if (ix->codes_tiled && (!aligned16(ix->codes_tiled) || code_bytes(ix) % 16)) return TRIM_INVALID_ARG;
     return TRIM_OK;
 }
 
@@ -267,7 +230,9 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
                  uint32_t *mask, int64_t mask_words, const Plan &pl) {
     a.base = ix->base; a.codes = ix->codes; a.dlx = ix->dlx; a.ids = ix->ids;
     a.codebooks = ix->codebooks; a.head = static_cast<const uint32_t *>(ix->scan_head);
-    a.codes_tiled = static_cast<const uint8_t *>(ix->codes_tiled); a.n = ix->n; a.d = ix->d; a.M = ix->M; a.dsub = ix->d / ix->M;
+    a.codes_tiled = static_cast<const uint8_t *>(ix->codes_tiled); a.n = ix->n; a.d = ix->d;
+    a.M = code_bytes(ix);       // the kernel counts code bytes
+    a.dsub = ix->d / ix->M;     // length of one subspace's sub-vectors (8- or 4-bit codes alike)
     a.queries = queries; a.lut = lut; a.order = nullptr;
     a.list_offsets = cand ? cand->list_offsets : nullptr;
     a.probes = cand ? cand->probes : nullptr;
@@ -292,6 +257,10 @@ void fill_common(SearchArgs &a, const trim_index_view *ix, const float *queries,
     a.off_wq = pl.off_wq; a.wqcap = pl.wqcap; a.cruise = pl.cruise; a.poss_cap = pl.poss_cap; a.scap = pl.scap; a.rcap = pl.rcap; a.bucket = pl.bucket;
     a.small_addr = ix->n < (int64_t(1) << 24) && ix->n * (int64_t)ix->M < (int64_t(1) << 32) &&
                    ix->M < (1 << 24);
+    // Thresholds that count on the remaining table minima (and list summaries) rest on an error
+    // bound of 2 * (table additions) * 2^-24 <= 3.1e-5 (see abandon_threshold): at most 256
+    // additions per table sum, and the whole table resident.
+    a.use_rest = pl.P == 1 && ix->M <= 256;
 }
 
 int fill_u32(uint32_t *p, size_t count, uint32_t v, hipStream_t st) {
@@ -399,7 +368,7 @@ int range_search(const trim_index_view *index, const float *queries, int64_t nq,
     if (!workspace || workspace_bytes < L.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return TRIM_WORKSPACE;
     Plan pl;
-    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, kRangeRound, kRangeRound, 1, true, &pl))
+    if (!make_plan(index->d, code_bytes(index), is_fs(index), cand ? cand->nprobe : 0, kRangeRound, kRangeRound, 1, true, &pl))
         return TRIM_UNSUPPORTED_SHAPE;
 
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -440,7 +409,7 @@ int range_search(const trim_index_view *index, const float *queries, int64_t nq,
     a.nq = nq;
     const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
     if (slots * pl.threads >= (int64_t(1) << 32)) return TRIM_INVALID_ARG;  // threads per launch
-    if ((rc = launch_search<kRange>(a, pl, dim3((unsigned)slots, (unsigned)L.nsplit), st))) return rc;
+    if ((rc = launch_search(true, is_fs(index), a, pl, dim3((unsigned)slots, (unsigned)L.nsplit), st))) return rc;
     hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(1024), 0, st, counts, nq, L.nsplit, cbase,
                        out_offsets, required);
     HIP_TRY(hipGetLastError());
@@ -460,7 +429,14 @@ extern "C" {
 
 int trim_shape_supported(int32_t d, int32_t M) {
     Plan pl;
-    return make_plan(d, M, 64, 2048, 2048, 10, true, &pl) ? 1 : 0;
+    if (d <= 0 || M <= 0 || d % M) return 0;
+    return make_plan(d, M, false, 64, 2048, 2048, 10, true, &pl) ? 1 : 0;
+}
+
+int trim_fs_shape_supported(int32_t d, int32_t M) {
+    Plan pl;
+    if (d <= 0 || M <= 0 || M % 2 || d % M) return 0;
+    return make_plan(d, M / 2, true, 64, 2048, 2048, 10, true, &pl) ? 1 : 0;
 }
 
 int trim_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
@@ -495,8 +471,9 @@ int trim_pack_list_bounds(const trim_index_view *index, const int64_t *list_offs
     const int rc = check_index(index);
     if (rc != TRIM_OK) return rc;
     if (nlist <= 0 || !list_offsets || !out || !aligned16(out)) return TRIM_INVALID_ARG;
-    hipLaunchKernelGGL(list_bounds_kernel, dim3((unsigned)nlist), dim3(256), (size_t)index->M * 32,
-                       static_cast<hipStream_t>(stream), index->codes, index->dlx, index->n, index->M,
+    const int Mb = code_bytes(index);   // summaries are kept per code byte
+    hipLaunchKernelGGL(list_bounds_kernel, dim3((unsigned)nlist), dim3(256), (size_t)Mb * 32,
+                       static_cast<hipStream_t>(stream), index->codes, index->dlx, index->n, Mb,
                        list_offsets, static_cast<uint8_t *>(out));
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
@@ -527,6 +504,9 @@ int trim_ceiling_lds_gather(int32_t blocks, int32_t iters, int32_t entry_floats,
             break;
         case 4:
             hipLaunchKernelGGL(lds_gather_wide_kernel<4>, dim3(blocks), dim3(512), 8 * kC * 16, st, iters, seed, sink);
+            break;
+        case 16:
+            hipLaunchKernelGGL(lds_gather_fs_kernel, dim3(blocks), dim3(512), 64 * kC4 * 4, st, iters, seed, sink);
             break;
         default:
             return TRIM_INVALID_ARG;
@@ -603,6 +583,7 @@ int trim_estimate_gamma(const trim_index_view *index, const int32_t *sample_rows
                         const float *sample_queries, int32_t Q, float p, float *gamma_x_out,
                         float *gamma_out, void *stream) {
     if (!index || index->n <= 0 || index->d <= 0 || index->M <= 0) return TRIM_INVALID_ARG;
+    if (index->code_bits == 4) return TRIM_UNSUPPORTED_SHAPE;   // 8-bit landmark codes only
     if (index->d % 4 || index->d % index->M) return TRIM_UNSUPPORTED_SHAPE;
     if (S <= 0 || Q <= 0 || !(p >= 0.0f && p <= 1.0f)) return TRIM_INVALID_ARG;
     if (Q > 16384) return TRIM_UNSUPPORTED_SHAPE;
@@ -648,6 +629,65 @@ int trim_pack_codes_tiled(const uint8_t *codes, int64_t n, int32_t M, void *tile
     hipLaunchKernelGGL(pack_codes_tiled_kernel, dim3((unsigned)blocks), dim3(256), 0,
                        static_cast<hipStream_t>(stream), codes, n, M, static_cast<uint4 *>(tiled_out));
     HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_fs_encode(const float *base, int64_t n, int32_t d, const float *codebooks, int32_t M,
+                   uint8_t *codes_out, float *dlx_out, void *stream) {
+    if (n < 0 || d <= 0 || M <= 0) return TRIM_INVALID_ARG;
+    if (d % M || M % 2) return TRIM_UNSUPPORTED_SHAPE;
+    const int dsub = d / M;
+    if ((size_t)2 * kC4 * dsub * 4 > 64 * 1024) return TRIM_UNSUPPORTED_SHAPE;
+    if (n == 0) return TRIM_OK;
+    if (!base || !codebooks || !codes_out || !dlx_out) return TRIM_INVALID_ARG;
+    hipLaunchKernelGGL(encode_fs_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256),
+                       (size_t)2 * kC4 * dsub * 4, static_cast<hipStream_t>(stream), base, n, d, codebooks,
+                       M, dsub, codes_out, dlx_out);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_fs_train_pq(const float *train, int64_t ns, int32_t d, int32_t M, int32_t iters,
+                     const int32_t *init_rows, float *codebooks_out, uint8_t *assign_ws, void *stream) {
+    if (ns <= 0 || d <= 0 || M <= 0 || iters < 0) return TRIM_INVALID_ARG;
+    if (d % M || M % 2 || M > 65535) return TRIM_UNSUPPORTED_SHAPE;
+    if (!train || !init_rows || !codebooks_out || !assign_ws) return TRIM_INVALID_ARG;
+    const int dsub = d / M;
+    if ((size_t)2 * kC4 * dsub * 4 > 64 * 1024) return TRIM_UNSUPPORTED_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int per = kC4 * dsub;  // centroid coordinates per subspace
+    for (int j = 0; j < M; ++j) {
+        hipLaunchKernelGGL(kmeans_init_kernel, dim3((per + 255) / 256), dim3(256), 0, st, train, ns,
+                           (int64_t)d, j * dsub, dsub, init_rows, kC4, codebooks_out + (size_t)j * per);
+    }
+    HIP_TRY(hipGetLastError());
+    for (int it = 0; it < iters; ++it) {
+        hipLaunchKernelGGL(encode_fs_kernel<false>, dim3((unsigned)((ns + 255) / 256)), dim3(256),
+                           (size_t)2 * kC4 * dsub * 4, st, train, ns, d, codebooks_out, M, dsub, assign_ws,
+                           static_cast<float *>(nullptr));
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(kmeans_update_kernel<1>, dim3((per + 255) / 256, M), dim3(256), 0, st, train,
+                           ns, (int64_t)d, 0, dsub, static_cast<const void *>(assign_ws), (int64_t)M, kC4,
+                           codebooks_out);
+        HIP_TRY(hipGetLastError());
+    }
+    return TRIM_OK;
+}
+
+int trim_fs_build_lut(const float *queries, int64_t nq, int32_t d, const float *codebooks, int32_t M,
+                      float *lut_out, void *stream) {
+    if (nq < 0 || d <= 0 || M <= 0) return TRIM_INVALID_ARG;
+    if (d % M || M % 2) return TRIM_UNSUPPORTED_SHAPE;
+    if (nq == 0) return TRIM_OK;
+    if (!queries || !codebooks || !lut_out) return TRIM_INVALID_ARG;
+    const int bper = 64;   // code bytes per block: 2048 entries
+    for (int64_t q0 = 0; q0 < nq; q0 += 65535) {
+        const int64_t cnt = nq - q0 < 65535 ? nq - q0 : 65535;
+        hipLaunchKernelGGL(lut_fs_kernel, dim3((M / 2 + bper - 1) / bper, (unsigned)cnt), dim3(256),
+                           (size_t)d * 4, static_cast<hipStream_t>(stream), queries + (size_t)q0 * d, d,
+                           codebooks, M, d / M, bper, lut_out + (size_t)q0 * M * kC4);
+        HIP_TRY(hipGetLastError());
+    }
     return TRIM_OK;
 }
 
@@ -702,7 +742,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     if (survivor_mask && mask_words <= 0) return TRIM_INVALID_ARG;
     Plan pl;
     const int cap = batch > k ? batch : k;
-    if (!make_plan(index->d, index->M, cand ? cand->nprobe : 0, cap, batch, k, false, &pl))
+    if (!make_plan(index->d, code_bytes(index), is_fs(index), cand ? cand->nprobe : 0, cap, batch, k, false, &pl))
         return TRIM_UNSUPPORTED_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (survivor_mask && (rc = fill_u32(survivor_mask, (size_t)nq * mask_words, 0u, st))) return rc;
@@ -714,7 +754,7 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
     a.nq = nq; a.order = query_order;
     const int64_t slots = (nq + kXcds - 1) / kXcds * kXcds;
     if (slots * pl.threads >= (int64_t(1) << 32)) return TRIM_INVALID_ARG;  // threads per launch
-    if ((rc = launch_search<kKnn>(a, pl, dim3((unsigned)slots, 1), st))) return rc;
+    if ((rc = launch_search(false, is_fs(index), a, pl, dim3((unsigned)slots, 1), st))) return rc;
     return TRIM_OK;
 }
 
@@ -814,7 +854,7 @@ const char *trim_strerror(int status) {
     }
 }
 
-int trim_last_hip_error(void) { return g_last_hip_error; }
+int trim_last_hip_error(void) { return trim::g_last_hip_error; }
 
 const char *trim_version(void) { return "0.1"; }
 

@@ -72,6 +72,38 @@ __global__ __launch_bounds__(512) void lds_gather_kernel(int iters, uint32_t see
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The same for 4-bit codes: a [64][16] table (32 code bytes of two subspaces each); every lane
+// sums, per iteration, the 64 entries its 32 code bytes select, with the scan's own routine.
+// A row of 16 consecutive words spans 16 banks, so these lookups never collide: this is also the
+// rate of conflict-free 4-byte LDS reads.  lookups = grid * 512 * iters * 64.
+__global__ __launch_bounds__(512) void lds_gather_fs_kernel(int iters, uint32_t seed,
+                                                            float *__restrict__ sink) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *tab = reinterpret_cast<float *>(smem);  // [64][16]
+    for (int i = threadIdx.x; i < 64 * kC4; i += blockDim.x) tab[i] = (float)((i * 2654435761u) >> 20);
+    __syncthreads();
+    const uint32_t tab_base = lds_addr(tab);
+    uint32_t w[8];
+    uint32_t h = seed ^ ((blockIdx.x * 512u + threadIdx.x) * 0x9e3779b9u);
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+        w[v] = h;
+    }
+    float s = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+        const uint32_t lo[4] = {w[0], w[1], w[2], w[3]};
+        const uint32_t hi[4] = {w[4], w[5], w[6], w[7]};
+        s = gather_add<4, false, true>(s, tab_base, lo, __builtin_inff());
+        s = gather_add<4, false, true>(s, tab_base + 16 * kByteRow<true>, hi, __builtin_inff());
+        const uint32_t t = w[0];
+#pragma unroll
+        for (int v = 0; v < 7; ++v) w[v] = w[v + 1];
+        w[7] = (t << 7 | t >> 25) ^ (uint32_t)it;
+    }
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // The same with entries of W binary32 values (W = 2, 4: what a table shared by W queries would
 // hold): 8 rows of 256 entries, every thread performs iters * 8 lookups of one whole entry and
 // adds its W values up.
@@ -396,6 +428,64 @@ __global__ __launch_bounds__(256) void encode_kernel(const float *__restrict__ b
         }
     }
     if (valid) dlx[i] = trim::sqrt_rn(tot);
+}
+
+// ---- PQ encode with 16 centroids per subspace (4-bit codes; Section 6.1, FastScan variants) ----
+// One thread per vector; a subspace's 16 centroids are read through the cache (every thread of
+// the block reads the same ones).  PACKED: two codes per byte, the even subspace's in the low
+// half (the stored index); else one byte per subspace (the assignments training works on).
+template <bool PACKED>
+__global__ __launch_bounds__(256) void encode_fs_kernel(const float *__restrict__ base, int64_t n, int d,
+                                                        const float *__restrict__ codebooks, int m,
+                                                        int dsub, uint8_t *__restrict__ codes,
+                                                        float *__restrict__ dlx) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *cb = reinterpret_cast<float *>(smem);  // [2][16][dsub]: the two subspaces of one code byte
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool valid = i < n;
+    const float *x = base + (size_t)(valid ? i : 0) * d;
+    float tot = 0.0f;
+    for (int jb = 0; jb < m / 2; ++jb) {
+        __syncthreads();
+        for (int e = threadIdx.x; e < 2 * kC4 * dsub; e += blockDim.x)
+            cb[e] = codebooks[(size_t)jb * 2 * kC4 * dsub + e];
+        __syncthreads();
+        uint32_t byte = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = 2 * jb + h;
+            float best = __builtin_inff();
+            int arg = 0;
+            for (int c = 0; c < kC4; ++c) {
+                float acc = 0.0f;
+                for (int t = 0; t < dsub; ++t) {
+                    const float e = x[j * dsub + t] - cb[(h * kC4 + c) * dsub + t];
+                    acc = __builtin_fmaf(e, e, acc);
+                }
+                if (acc < best) { best = acc; arg = c; }
+            }
+            tot = tot + best;
+            if (PACKED) byte |= (uint32_t)arg << (4 * h);
+            else if (valid) codes[(size_t)i * m + j] = (uint8_t)arg;
+        }
+        if (PACKED && valid) codes[(size_t)i * (m / 2) + jb] = (uint8_t)byte;
+    }
+    if (valid && dlx) dlx[i] = trim::sqrt_rn(tot);
+}
+
+// ---- stand-alone distance table for 4-bit codes: lut[q][j][c], c < 16 ----
+// grid (ceil(m/2 / bper), nq); each block writes the entries of bper code bytes of one query.
+__global__ __launch_bounds__(256) void lut_fs_kernel(const float *__restrict__ queries, int d,
+                                                     const float *__restrict__ codebooks, int m,
+                                                     int dsub, int bper, float *__restrict__ lut) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *q_lds = reinterpret_cast<float *>(smem);
+    const int64_t q = blockIdx.y;
+    const int b0 = blockIdx.x * bper;
+    const int nb = b0 + bper <= m / 2 ? bper : m / 2 - b0;
+    for (int t = threadIdx.x; t < d; t += blockDim.x) q_lds[t] = queries[(size_t)q * d + t];
+    __syncthreads();
+    build_table_rows<true>(lut + ((size_t)q * m + 2 * b0) * kC4, q_lds, codebooks, dsub, b0, nb);
 }
 
 // ---- stand-alone distance table (Section 3.3, query-processing operation 1) ----

@@ -15,7 +15,18 @@
 namespace trim {
 
 constexpr int kC = 256;          // centroids per subspace (the paper's C)
+constexpr int kC4 = 16;          // centroids per subspace with 4-bit codes (Section 6.1: FastScan variants)
 constexpr int kWave = 64;
+
+// Layout of a query's distance table in LDS, per code BYTE.  8-bit codes: a byte selects one of
+// the 256 entries of its subspace's row.  4-bit codes (FS): a byte holds the codes of two
+// subspaces (even one in the low half) and selects one of 16 entries in each of two rows of 16;
+// the 16 consecutive words of such a row lie in 16 different LDS banks, so lanes that read
+// different entries never collide.  Everything outside the table (code loads, scan head, list
+// summaries, thresholds every 8 bytes) works on code bytes and is the same for both.
+template <bool FS> constexpr int kByteEntries = FS ? 2 * kC4 : kC;      // table entries per code byte
+template <bool FS> constexpr uint32_t kByteRow = kByteEntries<FS> * 4;  // their bytes
+template <bool FS> constexpr int kByteLookups = FS ? 2 : 1;             // lookups per code byte
 
 struct Hit {
     float d2;
@@ -57,12 +68,23 @@ __device__ __forceinline__ float subvec_sqdist(const float *__restrict__ x,
 // Distance-table rows [j0, j0+nj) of one query (Section 2.2 / Section 3.3 operation 1):
 // out[(j-j0)*256 + c] = || q_j - centroid_{j,c} ||^2.  q points at the whole query (LDS or
 // global), out at LDS or global.  All threads of the block take part.
+// FS: j0 and nj count code bytes; byte j covers subspaces 2j and 2j+1 of 16 centroids each, dsub
+// is the length of one of THOSE sub-vectors, and the entries of a byte are [2][16].
+template <bool FS = false>
 __device__ __forceinline__ void build_table_rows(float *__restrict__ out,
                                                  const float *__restrict__ q,
                                                  const float *__restrict__ codebooks, int dsub,
                                                  int j0, int nj) {
     const int T = blockDim.x;
     int e = threadIdx.x;
+    if constexpr (FS) {
+        // entry e of the slab: subspace 2*j0 + e/16, centroid e%16 -- exactly the [m][16] order
+        for (; e < nj * kByteEntries<true>; e += T) {
+            const int sj = 2 * j0 + (e >> 4);
+            out[e] = subvec_sqdist(q + sj * dsub, codebooks + ((size_t)sj * kC4 + (e & 15)) * dsub, dsub);
+        }
+        return;
+    }
     if (dsub == 4) {  // four entries per step so that four centroid loads are in flight
         for (; e + 3 * T < nj * kC; e += 4 * T) {
             float4 cv[4];
@@ -256,9 +278,51 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) {
 // latencies overlap; the additions stay in subspace order.
 // MARK: a sum stopped half way is returned as +inf (for callers whose later tests use larger
 // thresholds than the half-way one: see the remaining-minimum thresholds of the cruise).
-template <int VEC, bool MARK = false>
+// 4 * (low half of byte B of w) and 4 * (its high half): byte offsets into a row of 16 entries.
+template <int B>
+__device__ __forceinline__ uint32_t lo_nibble_times4(uint32_t w) {
+    return B == 0 ? (w << 2) & 0x3cu : (w >> (8 * B - 2)) & 0x3cu;
+}
+template <int B>
+__device__ __forceinline__ uint32_t hi_nibble_times4(uint32_t w) { return (w >> (8 * B + 2)) & 0x3cu; }
+
+// The same for 4-bit codes: every code byte adds two entries, the even subspace's (low half)
+// first; reads of 8 bytes (16 subspaces) are issued together; tests after every 8 bytes.
+template <int VEC, bool MARK>
+__device__ __forceinline__ float gather_add_fs(float s, uint32_t tab_base, const uint32_t (&w)[VEC],
+                                               float thr) {
+    constexpr uint32_t kRow = kByteRow<true>;   // bytes of table per code byte
+    constexpr uint32_t kHalf = kC4 * 4;         // from the even subspace's row to the odd one's
+#pragma unroll
+    for (int v0 = 0; v0 < VEC; v0 += 2) {
+        float t[16];
+#pragma unroll
+        for (int dv = 0; dv < 2; ++dv) {
+            if (v0 + dv < VEC) {
+                const uint32_t cw = w[v0 + dv < VEC ? v0 + dv : 0];
+                const uint32_t row = tab_base + ((v0 + dv) * 4) * kRow;
+                t[8 * dv + 0] = lds_f32(row + lo_nibble_times4<0>(cw));
+                t[8 * dv + 1] = lds_f32(row + kHalf + hi_nibble_times4<0>(cw));
+                t[8 * dv + 2] = lds_f32(row + 1 * kRow + lo_nibble_times4<1>(cw));
+                t[8 * dv + 3] = lds_f32(row + 1 * kRow + kHalf + hi_nibble_times4<1>(cw));
+                t[8 * dv + 4] = lds_f32(row + 2 * kRow + lo_nibble_times4<2>(cw));
+                t[8 * dv + 5] = lds_f32(row + 2 * kRow + kHalf + hi_nibble_times4<2>(cw));
+                t[8 * dv + 6] = lds_f32(row + 3 * kRow + lo_nibble_times4<3>(cw));
+                t[8 * dv + 7] = lds_f32(row + 3 * kRow + kHalf + hi_nibble_times4<3>(cw));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (v0 + i / 8 < VEC) s = s + t[i];
+        if (v0 + 2 < VEC && s > thr) return MARK ? __builtin_inff() : s;
+    }
+    return s;
+}
+
+template <int VEC, bool MARK = false, bool FS = false>
 __device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const uint32_t (&w)[VEC],
                                             float thr) {
+    if constexpr (FS) return gather_add_fs<VEC, MARK>(s, tab_base, w, thr);
     constexpr int kRow = kC * 4;  // bytes per table row
 #pragma unroll
     for (int v0 = 0; v0 < VEC; v0 += 2) {
@@ -287,8 +351,14 @@ __device__ __forceinline__ float gather_add(float s, uint32_t tab_base, const ui
 
 // Table sums of two candidates over the same 8 subspaces (2 code dwords each), with the
 // sixteen LDS reads issued before the first addition so that their latencies overlap.
+template <bool FS = false>
 __device__ __forceinline__ void gather8_pair(uint32_t tab_base, const uint32_t (&wa)[2],
                                              const uint32_t (&wb)[2], float &sa, float &sb) {
+    if constexpr (FS) {   // 16 subspaces per candidate: one candidate's reads at a time
+        sa = gather_add_fs<2, false>(0.0f, tab_base, wa, __builtin_inff());
+        sb = gather_add_fs<2, false>(0.0f, tab_base, wb, __builtin_inff());
+        return;
+    }
     float ta[8], tb[8];
 #pragma unroll
     for (int v = 0; v < 2; ++v) {

@@ -66,6 +66,7 @@ struct SearchArgs {
     int32_t wqcap;     // entries per wave in each of the two work-queue arrays
     int32_t cruise;    // candidates per cruise stretch (multiple of batch; 0 = disabled)
     int32_t small_addr;  // n < 2^24 and n*M < 2^32: 24-bit multiply and 32-bit offsets suffice
+    int32_t use_rest;    // kNN: thresholds take the remaining table minima (and list summaries) into account
     int32_t poss_cap;  // capacity of the possibles list
     int32_t scap;      // entries of spos[] and of sd2[] (>= survivor capacity and >= poss_cap)
     int32_t rcap;      // entries behind sd2[scap] (bounds of a replay; >= poss_cap)
@@ -121,15 +122,16 @@ constexpr int kSmallBatch = 512;  // below this: short first spans and the bulk 
 constexpr int kRing = 256;  // entries of a wave's ring queue in cruise mode
 
 // Load or build the table rows [j0, j0+nj) of query q into LDS.
+template <bool FS>
 __device__ __forceinline__ void fill_table(float *tab, const SearchArgs &a, const float *q_lds,
                                            int64_t q, int j0, int nj) {
     if (a.lut) {
         const float4 *src =
-            reinterpret_cast<const float4 *>(a.lut + ((size_t)q * a.M + j0) * kC);
+            reinterpret_cast<const float4 *>(a.lut + ((size_t)q * a.M + j0) * kByteEntries<FS>);
         float4 *dst = reinterpret_cast<float4 *>(tab);
-        for (int e = threadIdx.x; e < nj * (kC / 4); e += blockDim.x) dst[e] = src[e];
+        for (int e = threadIdx.x; e < nj * (kByteEntries<FS> / 4); e += blockDim.x) dst[e] = src[e];
     } else {
-        build_table_rows(tab, q_lds, a.codebooks, a.dsub, j0, nj);
+        build_table_rows<FS>(tab, q_lds, a.codebooks, a.dsub, j0, nj);
     }
 }
 
@@ -355,7 +357,9 @@ __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *
 constexpr int kSmallKWavesPerSimd = 6;
 // ACCT: the instance that keeps the work counters (SearchArgs::work); the plain one carries none
 // of that code.
-template <int MODE, int VEC, int E, bool ACCT>
+// FS: 4-bit codes, two per code byte, with rows of 16 table entries (see kByteRow); SearchArgs::M
+// counts code bytes in either case.
+template <int MODE, int VEC, int E, bool ACCT, bool FS>
 __global__ __launch_bounds__(1024)
 __attribute__((amdgpu_waves_per_eu(MODE == kKnn && E == 1 ? kSmallKWavesPerSimd : 4)))
 void search_kernel(const SearchArgs a) {
@@ -443,20 +447,30 @@ void search_kernel(const SearchArgs a) {
         ctl->nexact = 0;
         for (int i = 0; i < kWorkCounters; ++i) ctl->work[i] = 0;
     }
-    if (a.P == 1) fill_table(tab, a, q_lds, q, 0, a.M);
+    if (a.P == 1) fill_table<FS>(tab, a, q_lds, q, 0, a.M);
     __syncthreads();
     // restv[i] = sum over the subspaces j >= 4i of the smallest entry of table row j: what the
     // subspaces still to come add to a running sum at the very least (see abandon_threshold).
     // Here: the sums of four rows' minima, one wave per group; turned into suffix sums below.
-    if (MODE == kKnn && a.P == 1) {
+    if (MODE == kKnn && a.use_rest) {
         for (int i = tid >> 6; i < a.M / 4; i += T >> 6) {
             float gsum = 0.0f;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float4 v = *reinterpret_cast<const float4 *>(tab + (size_t)(4 * i + r) * kC + 4 * lane);
-                float m = __builtin_fminf(__builtin_fminf(v.x, v.y), __builtin_fminf(v.z, v.w));
+                float m;
+                if constexpr (FS) {
+                    // the byte's two rows of 16: lanes 0..15 and 16..31 take a minimum each, and
+                    // the least a byte can add is their sum
+                    m = tab[(size_t)(4 * i + r) * kByteEntries<true> + (lane & 31)];
 #pragma unroll
-                for (int off = 32; off > 0; off >>= 1) m = __builtin_fminf(m, __shfl_xor(m, off));
+                    for (int off = 8; off > 0; off >>= 1) m = __builtin_fminf(m, __shfl_xor(m, off));
+                    m = m + __shfl_xor(m, 16);
+                } else {
+                    const float4 v = *reinterpret_cast<const float4 *>(tab + (size_t)(4 * i + r) * kC + 4 * lane);
+                    m = __builtin_fminf(__builtin_fminf(v.x, v.y), __builtin_fminf(v.z, v.w));
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) m = __builtin_fminf(m, __shfl_xor(m, off));
+                }
                 gsum = gsum + m;
                 if (lane == 0) rowmin[4 * i + r] = m;
             }
@@ -468,7 +482,7 @@ void search_kernel(const SearchArgs a) {
         float acc = 0.0f;
         restv[a.Mp / 4] = 0.0f;
         for (int i = a.Mp / 4 - 1; i >= 0; --i) {
-            acc = (MODE == kKnn && a.P == 1) ? acc + restv[i] : 0.0f;
+            acc = (MODE == kKnn && a.use_rest) ? acc + restv[i] : 0.0f;
             restv[i] = acc;
         }
     }   // (read after the next barrier: the seed's, or the one at the top of the main loop)
@@ -480,7 +494,7 @@ void search_kernel(const SearchArgs a) {
     // landmark distance), so while lb exceeds that, nothing in the list can survive.
     // Two segments per wave and round; a lane takes 16 recorded codes of one subspace (4 lanes
     // per subspace, 32 subspaces of either list per step, all loads of a step issued together).
-    if (MODE == kKnn && a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr) {
+    if (MODE == kKnn && a.use_rest && a.nseg > 0 && a.list_bounds != nullptr) {
         constexpr int kH0 = VEC >= 2 ? 8 : 4;
         const size_t rec_bytes = list_record_bytes(a.M);
         if (acct && tid == 0) tally(kWorkCodeBytes, (uint32_t)(nseg * rec_bytes));
@@ -518,14 +532,17 @@ void search_kernel(const SearchArgs a) {
                     for (int g = 0; g < 2; ++g) {
                         const int j = j0 + 16 * g + (lane >> 2);
                         const bool on = rec[t] && j < a.M;
-                        const float *row = tab + (size_t)(on ? j : 0) * kC;
+                        const float *row = tab + (size_t)(on ? j : 0) * kByteEntries<FS>;
                         const uint32_t w4[4] = {cw[t][g].x, cw[t][g].y, cw[t][g].z, cw[t][g].w};
                         float m = __builtin_inff();
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
 #pragma unroll
-                            for (int b = 0; b < 4; ++b)
-                                m = __builtin_fminf(m, row[(w4[v] >> (8 * b)) & 255u]);
+                            for (int b = 0; b < 4; ++b) {
+                                const uint32_t c = (w4[v] >> (8 * b)) & 255u;
+                                // what a vector with this code byte adds (4-bit codes: both halves)
+                                m = __builtin_fminf(m, FS ? row[c & 15u] + row[kC4 + (c >> 4)] : row[c]);
+                            }
                         m = __builtin_fminf(m, __shfl_xor(m, 1));
                         m = __builtin_fminf(m, __shfl_xor(m, 2));
                         if (on && (cnt[t][g] == 0 || cnt[t][g] == kSetAny)) m = rowmin[j];
@@ -831,10 +848,10 @@ void search_kernel(const SearchArgs a) {
                         // every test of a running sum is against the threshold less what the
                         // subspaces still to come add at the least (restv; a half-way stop inside
                         // a 16-subspace piece comes back as +inf)
-                        float sum = gather_add<DV, true>(0.0f, kTabLds, d_w0, thr - restv[DV == 4 ? 2 : 0]);
+                        float sum = gather_add<DV, true, FS>(0.0f, kTabLds, d_w0, thr - restv[DV == 4 ? 2 : 0]);
                         int j = 4 * DV;
                         if (two_chunks && !(sum > thr - restv[j >> 2])) {
-                            sum = gather_add<DV, true>(sum, kTabLds + 4 * DV * (kC * 4), d_w1,
+                            sum = gather_add<DV, true, FS>(sum, kTabLds + 4 * DV * kByteRow<FS>, d_w1,
                                                        thr - restv[DV == 4 ? 6 : 0]);
                             j = 8 * DV;
                         }
@@ -842,17 +859,17 @@ void search_kernel(const SearchArgs a) {
                             if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
                                 uint32_t w[4];
                                 load_codes<4>(w, cr.at(j));
-                                sum = gather_add<4, true>(sum, kTabLds + j * (kC * 4), w, thr - restv[(j >> 2) + 2]);
+                                sum = gather_add<4, true, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr - restv[(j >> 2) + 2]);
                                 j += 16;
                             } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= a.M) {
                                 uint32_t w[2];
                                 load_codes<2>(w, cr.at(j));
-                                sum = gather_add<2>(sum, kTabLds + j * (kC * 4), w, thr);
+                                sum = gather_add<2, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
                                 j += 8;
                             } else {
                                 uint32_t w[1];
                                 load_codes<1>(w, cr.at(j));
-                                sum = gather_add<1>(sum, kTabLds + j * (kC * 4), w, thr);
+                                sum = gather_add<1, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
                                 j += 4;
                             }
                         }
@@ -862,7 +879,7 @@ void search_kernel(const SearchArgs a) {
                             // and has looked up only the piece's first 8 subspaces
                             const int loaded = two_chunks && j < 8 * DV ? 8 * DV : j;
                             tally(kWorkCodeBytes, (uint32_t)(loaded + 4));
-                            tally(kWorkLookups, (uint32_t)(j - (DV == 4 && sum == __builtin_inff() ? 8 : 0)));
+                            tally(kWorkLookups, (uint32_t)(j - (DV == 4 && sum == __builtin_inff() ? 8 : 0)) * kByteLookups<FS>);
                             tally(kWorkFullCode, 1u);
                         }
                         if (!(sum > thr - restv[j >> 2])) {
@@ -886,7 +903,7 @@ void search_kernel(const SearchArgs a) {
                     float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, restv[H0 / 4])));
                 // list-level pruning: a list is passed over while its slack > st (both compared as
                 // integers: st > 0, and a negative slack is a negative integer)
-                const bool have_lb = a.P == 1 && a.nseg > 0 && a.list_bounds != nullptr;
+                const bool have_lb = a.use_rest && a.nseg > 0 && a.list_bounds != nullptr;
                 const int st_bits = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sqrt_tau0));
                 for (int blk = wave; blk < nblk; blk += nwaves) {
                     // this block's loads fly while the previous drain is finished; the next
@@ -969,7 +986,7 @@ void search_kernel(const SearchArgs a) {
                         const uint32_t nv = cb + U * kWave <= S ? U * kWave : S - cb;  // candidates of the block
                         tally(kWorkFirstPass, nv);
                         tally(kWorkCodeBytes, nv * (full ? (uint32_t)sizeof(HeadRecord) : H0 + 4u));
-                        tally(kWorkLookups, nv * H0);
+                        tally(kWorkLookups, nv * H0 * kByteLookups<FS>);
                     }
                     if (d_n > 0) drain_finish();
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
@@ -978,11 +995,11 @@ void search_kernel(const SearchArgs a) {
                     if constexpr (H0 == 8 && U % 2 == 0) {
 #pragma unroll
                         for (int u = 0; u < U; u += 2)
-                            gather8_pair(kTabLds, w[u], w[u + 1], sums[u], sums[u + 1]);
+                            gather8_pair<FS>(kTabLds, w[u], w[u + 1], sums[u], sums[u + 1]);
                     } else {
 #pragma unroll
                         for (int u = 0; u < U; ++u)
-                            sums[u] = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
+                            sums[u] = gather_add<H0 / 4, false, FS>(0.0f, kTabLds, w[u], __builtin_inff());
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -1123,7 +1140,7 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
                     for (int c = 0; c < kDirectChunks; ++c)
                         if (c * 4 * VEC < a.M)
-                            sum = gather_add<VEC>(sum, kTabLds + c * 4 * VEC * (kC * 4), w[u][c],
+                            sum = gather_add<VEC, false, FS>(sum, kTabLds + c * 4 * VEC * kByteRow<FS>, w[u][c],
                                                   __builtin_inff());
                     if (cl < whi) {
                         const float g = plb_from_s(sum, b[u], a.two_gamma);
@@ -1137,14 +1154,14 @@ void search_kernel(const SearchArgs a) {
                 tally(kWorkFirstPass, nv);
                 tally(kWorkFullCode, nv);
                 tally(kWorkCodeBytes, nv * (uint32_t)(a.M + 4));
-                tally(kWorkLookups, nv * (uint32_t)a.M);
+                tally(kWorkLookups, nv * (uint32_t)a.M * kByteLookups<FS>);
             }
         }
         int rnd = 0;  // rounds taken so far (the second one reads the rest of a code for the first time)
         for (int ph = 0; ph < (direct ? 0 : a.P); ++ph) {
             if (a.P > 1) {
                 __syncthreads();
-                fill_table(tab, a, q_lds, q, ph * a.Mp, a.Mp);
+                fill_table<FS>(tab, a, q_lds, q, ph * a.Mp, a.Mp);
                 __syncthreads();
             }
             const bool last_ph = ph == a.P - 1;
@@ -1167,7 +1184,7 @@ void search_kernel(const SearchArgs a) {
                         issue_loads(c0, base, whi, w, bq, sg_unused);
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
-                            const float sum = gather_add<H0 / 4>(0.0f, kTabLds, w[u], __builtin_inff());
+                            const float sum = gather_add<H0 / 4, false, FS>(0.0f, kTabLds, w[u], __builtin_inff());
                             const int cl = base + u * kWave + lane;
                             const float thr = abandon_threshold(bq[u], sqrt_tau0);
                             const bool valid = cl < whi;
@@ -1188,7 +1205,7 @@ void search_kernel(const SearchArgs a) {
                         const uint32_t nv = whi - wlo;
                         tally(kWorkFirstPass, nv);
                         tally(kWorkCodeBytes, nv * (H0 + 4u));
-                        tally(kWorkLookups, nv * (uint32_t)h1);
+                        tally(kWorkLookups, nv * (uint32_t)h1 * kByteLookups<FS>);
                     }
                 } else {
                     // ---- later rounds: dense over the wave's queue ----
@@ -1231,11 +1248,11 @@ void search_kernel(const SearchArgs a) {
                             // (a sum stopped inside a 16-byte piece comes back as +inf: still
                             // above every threshold, and the accounting can tell)
                             if (bulk) {
-                                if (lead8) sum = gather_add<2>(sum, kTabLds + h0 * (kC * 4), w8, thr);
+                                if (lead8) sum = gather_add<2, false, FS>(sum, kTabLds + h0 * kByteRow<FS>, w8, thr);
 #pragma unroll
                                 for (int c = 0; c < kPieces; ++c)
                                     if (c < n16 && !(sum > thr)) {
-                                        sum = gather_add<4, true>(sum, kTabLds + (ja + 16 * c) * (kC * 4),
+                                        sum = gather_add<4, true, FS>(sum, kTabLds + (ja + 16 * c) * kByteRow<FS>,
                                                                   w16[c], thr);
                                         ++used16;
                                     }
@@ -1245,17 +1262,17 @@ void search_kernel(const SearchArgs a) {
                                 if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
                                     uint32_t w[4];
                                     load_codes<4>(w, cr.at(jp + j));
-                                    sum = gather_add<4, true>(sum, kTabLds + j * (kC * 4), w, thr);
+                                    sum = gather_add<4, true, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
                                     j += 16;
                                 } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= h1) {
                                     uint32_t w[2];
                                     load_codes<2>(w, cr.at(jp + j));
-                                    sum = gather_add<2>(sum, kTabLds + j * (kC * 4), w, thr);
+                                    sum = gather_add<2, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
                                     j += 8;
                                 } else {
                                     uint32_t w[1];
                                     load_codes<1>(w, cr.at(jp + j));
-                                    sum = gather_add<1>(sum, kTabLds + j * (kC * 4), w, thr);
+                                    sum = gather_add<1, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
                                     j += 4;
                                 }
                                 if (sum > thr) break;
@@ -1265,7 +1282,7 @@ void search_kernel(const SearchArgs a) {
                                 const int looks = (bulk ? (lead8 ? 8 : 0) + 16 * used16 : j - h0) -
                                                   (VEC == 4 && sum == __builtin_inff() ? 8 : 0);
                                 tally(kWorkCodeBytes, (uint32_t)(bytes + 4));
-                                tally(kWorkLookups, (uint32_t)looks);
+                                tally(kWorkLookups, (uint32_t)looks * kByteLookups<FS>);
                                 if (slice_round) tally(kWorkFirstPass, 1u);
                                 else if (rnd == 1) tally(kWorkFullCode, 1u);
                             }

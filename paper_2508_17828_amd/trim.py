@@ -20,7 +20,8 @@ TRIM_MAX_K = 1024
 TRIM_MAX_BATCH = 4096
 TRIM_MAX_NPROBE = 4096
 
-EXPORTS = ("trim_shape_supported", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
+EXPORTS = ("trim_shape_supported", "trim_fs_shape_supported", "trim_fs_encode", "trim_fs_build_lut",
+           "trim_fs_train_pq", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_search_range_static", "trim_static_scratch_bytes", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_list_bounds_bytes", "trim_pack_list_bounds",
@@ -46,7 +47,8 @@ class TrimCapacityError(RuntimeError):
 class _IndexView(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("M", C.c_int32), ("base", C.c_void_p),
                 ("codes", C.c_void_p), ("dlx", C.c_void_p), ("ids", C.c_void_p),
-                ("codebooks", C.c_void_p), ("scan_head", C.c_void_p), ("codes_tiled", C.c_void_p)]
+                ("codebooks", C.c_void_p), ("scan_head", C.c_void_p), ("codes_tiled", C.c_void_p),
+                ("code_bits", C.c_int32)]
 
 
 class _Candidates(C.Structure):
@@ -79,6 +81,13 @@ def lib() -> C.CDLL:
         L.trim_range_workspace_bytes.restype = C.c_size_t
         L.trim_range_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
         L.trim_shape_supported.argtypes = [C.c_int32, C.c_int32]
+        L.trim_fs_shape_supported.argtypes = [C.c_int32, C.c_int32]
+        L.trim_fs_encode.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
+        L.trim_fs_build_lut.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_void_p]
+        L.trim_fs_train_pq.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_encode.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_pack_scan_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
@@ -153,6 +162,7 @@ class Index:
     scan_head: Optional[torch.Tensor] = None      # [n][12] uint8, from trim_pack_scan_head
     codes_tiled: Optional[torch.Tensor] = None    # uint8, from trim_pack_codes_tiled
     list_bounds: Optional[torch.Tensor] = None    # uint8, from trim_pack_list_bounds
+    code_bits: int = 8                            # 4: codes [n][M/2], codebooks [M][16][d/M] (trim_fs_encode)
 
     @property
     def n(self): return self.base.shape[0]
@@ -167,7 +177,7 @@ class Index:
                           _ptr(self.ids, torch.int32, "ids"),
                           _ptr(self.codebooks, torch.float32, "codebooks"),
                           _ptr(self.scan_head, torch.uint8, "scan_head"),
-                          _ptr(self.codes_tiled, torch.uint8, "codes_tiled"))
+                          _ptr(self.codes_tiled, torch.uint8, "codes_tiled"), self.code_bits)
 
     def _cand(self, probes: Optional[torch.Tensor], max_candidates: int = 0):
         if probes is None:
@@ -184,6 +194,54 @@ class Index:
 
 def trim_shape_supported(d: int, M: int) -> bool:
     return bool(lib().trim_shape_supported(d, M))
+
+
+def trim_fs_shape_supported(d: int, M: int) -> bool:
+    return bool(lib().trim_fs_shape_supported(d, M))
+
+
+def _codebook_fs_M(codebooks: torch.Tensor, d: int) -> int:
+    M = codebooks.shape[0]
+    if codebooks.dim() != 3 or codebooks.shape[1] != 16 or M * codebooks.shape[2] != d or M % 2:
+        raise TypeError(f"codebooks: need shape [M][16][d/M] with d={d} and M even, got {tuple(codebooks.shape)}")
+    return M
+
+
+def trim_fs_encode(base: torch.Tensor, codebooks: torch.Tensor):
+    n, d = base.shape
+    M = _codebook_fs_M(codebooks, d)
+    codes = torch.empty((n, M // 2), dtype=torch.uint8, device=base.device)
+    dlx = torch.empty((n,), dtype=torch.float32, device=base.device)
+    _check(lib().trim_fs_encode(_ptr(base, torch.float32, "base"), n, d,
+                                _ptr(codebooks, torch.float32, "codebooks"), M,
+                                _ptr(codes, torch.uint8, "codes"), _ptr(dlx, torch.float32, "dlx"),
+                                _stream()), "trim_fs_encode")
+    return codes, dlx
+
+
+def trim_fs_build_lut(queries: torch.Tensor, codebooks: torch.Tensor, out: Optional[torch.Tensor] = None):
+    nq, d = queries.shape
+    M = _codebook_fs_M(codebooks, d)
+    if out is None:
+        out = torch.empty((nq, M, 16), dtype=torch.float32, device=queries.device)
+    _check(lib().trim_fs_build_lut(_ptr(queries, torch.float32, "queries"), nq, d,
+                                   _ptr(codebooks, torch.float32, "codebooks"), M,
+                                   _ptr(out, torch.float32, "lut"), _stream()), "trim_fs_build_lut")
+    return out
+
+
+def trim_fs_train_pq(train: torch.Tensor, M: int, iters: int, init_rows: torch.Tensor) -> torch.Tensor:
+    ns, d = train.shape
+    if d % M or M % 2 or init_rows.numel() != 16:
+        raise TypeError(f"trim_fs_train_pq: need d % M == 0, M even and 16 initial rows, got d={d}, M={M}, "
+                        f"{init_rows.numel()} rows")
+    codebooks = torch.empty((M, 16, d // M), dtype=torch.float32, device=train.device)
+    assign = torch.empty((ns, M), dtype=torch.uint8, device=train.device)
+    _check(lib().trim_fs_train_pq(_ptr(train, torch.float32, "train"), ns, d, M, iters,
+                                  _ptr(init_rows, torch.int32, "init_rows"),
+                                  _ptr(codebooks, torch.float32, "codebooks"),
+                                  _ptr(assign, torch.uint8, "assign_ws"), _stream()), "trim_fs_train_pq")
+    return codebooks
 
 
 def trim_train_pq(train: torch.Tensor, M: int, iters: int, init_rows: torch.Tensor) -> torch.Tensor:
@@ -406,7 +464,7 @@ def trim_pack_list_bounds(index: "Index") -> torch.Tensor:
     list-level pruning of trim_search_knn."""
     assert index.list_offsets is not None
     nlist = index.list_offsets.shape[0] - 1
-    out = torch.empty((lib().trim_list_bounds_bytes(nlist, index.M),), dtype=torch.uint8,
+    out = torch.empty((lib().trim_list_bounds_bytes(nlist, index.codes.shape[1]),), dtype=torch.uint8,
                       device=index.base.device)
     view = index._view()
     _check(lib().trim_pack_list_bounds(C.byref(view), _ptr(index.list_offsets, torch.int64, "list_offsets"),

@@ -1,0 +1,164 @@
+"""GPU parity for the index with 4-bit codes (Section 6.1: FastScan variants, m = d/2 subspaces
+of 16 centroids): trim_fs_encode, trim_fs_build_lut, trim_fs_train_pq and the searches over such
+an index, through the C ABI, against oracle/trim_oracle_fs.  Same bars as test_gpu_parity.py:
+codes, landmark distances, tables, survivor masks, counters, ids and distances bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import index_build
+from oracle import trim_oracle_fs as fs
+from paper_2508_17828_amd import synth
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def T():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2508_17828_amd import trim
+    trim.lib()
+    return trim
+
+
+CASES = {
+    "c1": ("C1", 0, 0, -1, -1),                 # 10k x 128 -> 64 subspaces, 32 code bytes, all n scanned
+    "c2s": ("C2", 60_000, 96, 64, 8),            # inverted lists, scan head, list summaries
+    "c3s": ("C3", 12_000, 24, -1, -1),           # d=960 -> 480 subspaces (240 code bytes), k=100
+    "c4s": ("C4", 16_000, 32, 32, 6),            # d=1536 -> 768 subspaces, 48 KB table
+    "c5s": ("C5", 80_000, 64, 128, 16),          # many short lists
+}
+
+
+def case(name):
+    return helpers.cached_fs(*CASES[name])
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def to_dev(T, b, head=True, bounds=True, tiled=False):
+    import torch
+    ix = b.index
+    t = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    gi = T.Index(t(ix.base), t(ix.codes), t(ix.dlx), t(ix.codebooks), ids=t(ix.ids),
+                 list_offsets=t(ix.list_offsets), code_bits=4,
+                 max_list_len=int(np.diff(ix.list_offsets).max()) if ix.list_offsets is not None else 0)
+    nbytes = ix.codes.shape[1]
+    if head and nbytes % 8 == 0:
+        gi.scan_head = T.trim_pack_scan_head(gi.codes, gi.dlx)
+    if tiled and nbytes % 16 == 0:
+        gi.codes_tiled = T.trim_pack_codes_tiled(gi.codes)
+    if bounds and ix.list_offsets is not None:
+        gi.list_bounds = T.trim_pack_list_bounds(gi)
+    return gi, t(b.queries), t(b.probes)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_encode_and_table(T, oracle, name):
+    b = case(name)
+    gi, q, _ = to_dev(T, b, head=False, bounds=False)
+    codes, dlx = T.trim_fs_encode(gi.base, gi.codebooks)
+    np.testing.assert_array_equal(codes.cpu().numpy(), b.index.codes)
+    np.testing.assert_array_equal(u32(dlx), b.index.dlx.view(np.uint32))
+    lut = T.trim_fs_build_lut(q, gi.codebooks)
+    np.testing.assert_array_equal(u32(lut), fs.build_lut(b.queries, b.index.codebooks).view(np.uint32))
+
+
+def test_training_is_bit_equal_to_the_oracle(T, oracle):
+    import torch
+    w = synth.scaled(synth.WORKLOADS["C2"], 20_000, 4)
+    base = synth.base_vectors(w)
+    tr, init = synth.kmeans_draws(w, 4096, 16, stream=0)
+    train = np.ascontiguousarray(base[tr])
+    ref = index_build.train_pq_fs_fixed(train, w.d // 2, 4, init)
+    got = T.trim_fs_train_pq(torch.from_numpy(train).cuda(), w.d // 2, 4,
+                             torch.from_numpy(init.astype(np.int32)).cuda())
+    np.testing.assert_array_equal(u32(got), ref.view(np.uint32))
+
+
+def check_knn(T, b, k, gamma, batch, prebuilt_lut=False, **dev):
+    gi, q, probes = to_dev(T, b, **dev)
+    lut = T.trim_fs_build_lut(q, gi.codebooks) if prebuilt_lut else None
+    got = T.trim_search_knn(gi, q, k, gamma, batch, probes=probes, lut=lut, want_mask=True)
+    ref = fs.search_knn(b.index, b.queries, k, gamma, batch, b.probes, want_mask=True)
+    np.testing.assert_array_equal(got["n_scanned"].cpu().numpy(), ref["n_scanned"])
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
+    np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"])
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_array_equal(u32(got["d2"]), ref["d2"].view(np.uint32))
+    return got, ref
+
+
+@pytest.mark.parametrize("name,k,batch", [("c1", 10, 256), ("c1", 10, 1), ("c2s", 10, 1024), ("c2s", 1, 64),
+                                          ("c2s", 70, 333), ("c5s", 10, 1024), ("c5s", 10, 16),
+                                          ("c3s", 100, 512), ("c3s", 100, 4096), ("c4s", 10, 2048),
+                                          ("c2s", 300, 5), ("c2s", 1024, 4096)])
+@pytest.mark.parametrize("gamma", [0.0, 0.5, 0.8])
+def test_knn(T, oracle, name, k, batch, gamma):
+    got, _ = check_knn(T, case(name), k, gamma, batch)
+    if gamma == 0.0:
+        b = case(name)
+        bi, _ = oracle.brute_knn(b.index, b.queries, k, b.probes)     # 8-bit oracle's brute force: no codes involved
+        np.testing.assert_array_equal(got["ids"].cpu().numpy(), bi)
+
+
+@pytest.mark.parametrize("name", ["c2s", "c4s"])
+def test_knn_layout_copies_and_prebuilt_table_change_nothing(T, oracle, name):
+    check_knn(T, case(name), 10, 0.5, 512, prebuilt_lut=True)
+    check_knn(T, case(name), 10, 0.5, 512, head=False, bounds=False)
+    check_knn(T, case(name), 100, 0.3, 256, tiled=True)
+    gi, q, probes = to_dev(T, case(name))
+    order = T.trim_query_order(probes, gi.list_offsets.shape[0] - 1)
+    a = T.trim_search_knn(gi, q, 10, 0.4, 128, probes=probes)
+    b = T.trim_search_knn(gi, q, 10, 0.4, 128, probes=probes, query_order=order)
+    np.testing.assert_array_equal(a["ids"].cpu().numpy(), b["ids"].cpu().numpy())
+
+
+@pytest.mark.parametrize("name,percent,gamma", [("c1", 1.0, 0.0), ("c2s", 2.0, 0.5), ("c4s", 5.0, 0.7),
+                                                ("c3s", 1.0, 0.3), ("c5s", 0.5, 0.0)])
+def test_range(T, oracle, name, percent, gamma):
+    b = case(name)
+    gi, q, probes = to_dev(T, b, tiled=name == "c4s")
+    radius = helpers.radius_at_percentile(b, percent)
+    got = T.trim_search_range(gi, q, radius, gamma, probes=probes, want_mask=True)
+    ref = fs.search_range(b.index, b.queries, radius, gamma, b.probes, want_mask=True)
+    np.testing.assert_array_equal(got["offsets"].cpu().numpy(), ref["offsets"])
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_array_equal(u32(got["d2"]), ref["d2"].view(np.uint32))
+    np.testing.assert_array_equal(got["n_exact"].cpu().numpy(), ref["n_exact"])
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
+    assert ref["offsets"][-1] > 0
+
+
+def test_work_counters_count_two_lookups_per_code_byte(T, oracle):
+    b = case("c2s")
+    gi, q, probes = to_dev(T, b)
+    got = T.trim_search_knn(gi, q, 10, 0.4, 1024, probes=probes, want_work=True)
+    plain = T.trim_search_knn(gi, q, 10, 0.4, 1024, probes=probes)
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), plain["ids"].cpu().numpy())
+    w = got["work"].cpu().numpy().astype(np.int64)
+    ns = got["n_scanned"].cpu().numpy()
+    nbytes = b.index.codes.shape[1]
+    assert np.all(w[:, 0] + w[:, 1] + np.minimum(10, ns) >= ns)
+    assert np.all(w[:, 3] >= 16 * w[:, 0]) and np.all(w[:, 3] <= 2 * (nbytes + 8) * w[:, 0])
+    assert np.all(w[:, 4] >= got["n_exact"].cpu().numpy())
+
+
+def test_argument_errors(T):
+    import torch
+    b = case("c1")
+    gi, q, _ = to_dev(T, b)
+    assert T.trim_fs_shape_supported(128, 64) and T.trim_fs_shape_supported(1536, 768)
+    assert not T.trim_fs_shape_supported(128, 60) and not T.trim_fs_shape_supported(100, 50)
+    bad = T.Index(gi.base, gi.codes, gi.dlx, gi.codebooks, code_bits=5)
+    with pytest.raises(T.TrimError):
+        T.trim_search_knn(bad, q, 10, 0.0, 64)
+    with pytest.raises(TypeError):
+        T.trim_fs_encode(gi.base, gi.codebooks[:, :15].contiguous())
+    with pytest.raises(T.TrimError):          # the estimator of gamma reads 8-bit codes only
+        T.trim_estimate_gamma(gi, torch.zeros(4, dtype=torch.int32, device="cuda"), q, 0.9)
