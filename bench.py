@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--no-list-bounds", action="store_true",
                     help="time the search without the per-list summaries only (no list-level pruning)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the machine-ceiling measurements")
+    ap.add_argument("--code-bits", type=int, default=8, choices=(8, 4),
+                    help="4: index the workload with the 4-bit codes of the FastScan variant "
+                         "(d/2 subspaces of 16 centroids) instead of its M subspaces of 256")
     return ap.parse_args()
 
 
@@ -81,13 +84,18 @@ def machine_ceilings(trim):
     look = max(blocks * 512 * iters * 32 / (_event_ms(
         lambda: trim.trim_ceiling_lds_gather(blocks, iters, 12345, fsink), 5) * 1e-3) / 1e9
         for blocks in (768, 1024))
-    return dict(stream_read_GBps=round(read, 1), lds_random_lookup_Glookups=round(look, 1))
+    look16 = max(blocks * 512 * iters * 64 / (_event_ms(
+        lambda: trim.trim_ceiling_lds_gather(blocks, iters, 12345, fsink, entry_floats=16), 5) * 1e-3) / 1e9
+        for blocks in (768, 1024))
+    return dict(stream_read_GBps=round(read, 1), lds_random_lookup_Glookups=round(look, 1),
+                lds_rows_of_16_lookup_Glookups=round(look16, 1))
 
 
-def host_index(trim_oracle, ix, centroids):
+def host_index(orc, ix, centroids):
+    """The device index as the oracle's plain arrays (orc: trim_oracle, or trim_oracle_fs for 4-bit codes)."""
     h = lambda t: None if t is None else t.cpu().numpy()
-    return trim_oracle.Index(h(ix.base), h(ix.codes), h(ix.dlx), h(ix.codebooks), ids=h(ix.ids),
-                             list_offsets=h(ix.list_offsets), centroids=h(centroids))
+    return orc.Index(h(ix.base), h(ix.codes), h(ix.dlx), h(ix.codebooks), ids=h(ix.ids),
+                     list_offsets=h(ix.list_offsets), centroids=h(centroids))
 
 
 def set_threads(n):
@@ -122,17 +130,17 @@ def work_totals(trim, work):
     return {name: int(tot[i]) for i, name in enumerate(trim.WORK_NAMES)}
 
 
-def touched_bytes(w, nq, k_or_results, wt, use_lut):
+def touched_bytes(w, nq, k_or_results, wt, use_lut, ncent=256):
     """Bytes the launch requested from memory, by the kernel's own counters: codes / scan heads /
     landmark distances / list summaries, raw rows (+ id) of every exact distance, the query, the
     PQ centroids (or the prebuilt table) behind each query's distance table, the results."""
-    table_src = nq * (w.M * 1024 if use_lut else w.d * 256 * 4)
+    table_src = nq * (w.M * 1024 if use_lut else w.d * ncent * 4)
     return dict(codes=wt["code_bytes"], rows=wt["rows"] * (4 * w.d + 4), queries=nq * 4 * w.d,
                 table_source=table_src, results=k_or_results * 8,
                 total=wt["code_bytes"] + wt["rows"] * (4 * w.d + 4) + nq * 4 * w.d + table_src + k_or_results * 8)
 
 
-def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel):
+def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel, fs=False):
     """The dominant kernel against the resource that binds it.  Long codes streamed once per
     query are bound by HBM; short codes shared by many queries through the caches are bound by
     the rate of table lookups out of LDS."""
@@ -150,23 +158,21 @@ def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel):
                     "counters), part of it served by the caches; bytes beyond L2 are in profiles/")
     lds = dict(lookups=wt["lookups"], Glookups_per_s=round(looks, 1), peak_Glookups=LDS_PEAK_GLOOKUPS,
                frac_of_peak=round(looks / LDS_PEAK_GLOOKUPS, 4),
-               random_lookup_ceiling_Glookups=ceil.get("lds_random_lookup_Glookups"),
-               frac_of_random_lookup_ceiling=(round(looks / ceil["lds_random_lookup_Glookups"], 4)
-                                              if ceil.get("lds_random_lookup_Glookups") else None),
+               lookup_ceiling_Glookups=ceil.get("lds_rows_of_16_lookup_Glookups" if fs else
+                                                "lds_random_lookup_Glookups"),
+               frac_of_lookup_ceiling=None,
                note="peak = 256 CUs x 128 B/clk x 2.4 GHz / 4 B; the ceiling is the scan's own lookup-and-"
-                    "add sequence on random byte codes with nothing else going on (bank conflicts), "
-                    "measured in this run")
-    # HBM binds when the bytes the kernel asked for (never more than the algorithmic model
-    # credits) are a larger share of the HBM peak than its lookups are of the lookup ceiling; a
-    # rate above the peak can only have come out of the caches and bounds nothing
-    gbs = min(alg, tch)
-    f_lds = looks / (ceil.get("lds_random_lookup_Glookups") or LDS_PEAK_GLOOKUPS)
-    if gbs <= HBM_PEAK_GBS and gbs / HBM_PEAK_GBS >= f_lds:
-        head = dict(bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(gbs / HBM_PEAK_GBS, 4),
-                    achieved_is="algorithmic bytes / kernel time" if alg <= tch else
-                                "touched bytes / kernel time (fewer than the algorithmic bytes: the first "
-                                "pass reads a 12-byte record per candidate and lists are passed over)")
+                    "add sequence on random codes with nothing else going on (8-bit codes: 256-entry "
+                    "rows, bank conflicts; 4-bit codes: rows of 16, no conflicts), measured in this run")
+    if lds["lookup_ceiling_Glookups"]:
+        lds["frac_of_lookup_ceiling"] = round(looks / lds["lookup_ceiling_Glookups"], 4)
+    # The task's accounting is algorithmic bytes against the HBM peak.  Where that rate exceeds
+    # the peak, the bytes cannot have come from HBM (queries share the codes through the caches,
+    # lists are passed over): HBM bounds nothing there, and the kernel is priced against the
+    # table-lookup rate of LDS instead, with the byte rates listed beside it.
+    if alg <= HBM_PEAK_GBS:
+        head = dict(bound="hbm", achieved=round(alg, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(alg / HBM_PEAK_GBS, 4))
     else:
         head = dict(bound="lds", achieved=round(looks, 1), peak=LDS_PEAK_GLOOKUPS, unit="Glookup/s",
                     frac=round(looks / LDS_PEAK_GLOOKUPS, 4))
@@ -329,8 +335,10 @@ def main():
     w = synth.WORKLOADS[args.workload]
     batch = args.batch or w.batch
     t0 = time.time()
-    bw = index_setup.build_workload(w)
+    bw = index_setup.build_workload(w, code_bits=args.code_bits)
     ix, queries = bw.index, bw.queries
+    fs = args.code_bits == 4
+    code_bytes = ix.codes.shape[1]
     torch.cuda.synchronize()
     setup_s = time.time() - t0
     nq, k = w.nq, w.k
@@ -340,11 +348,15 @@ def main():
         return trim.trim_ivf_probe(q, bw.centroids, w.nprobe) if w.nlist else None
 
     if w.mode == "range":
+        if fs:
+            print("bench.py: --code-bits 4 is timed on the kNN workloads", file=sys.stderr)
+            sys.exit(2)
         print(json.dumps(bench_range(args, w, bw, probes_for, setup_s, ceil)))
         return
 
-    from oracle import trim_oracle
-    oix = host_index(trim_oracle, ix, bw.centroids)
+    from oracle import trim_oracle, trim_oracle_fs
+    orc = trim_oracle_fs if fs else trim_oracle      # the scan's oracle for this code width
+    oix = host_index(orc, ix, bw.centroids)
     qh = queries.cpu().numpy()
 
     # ---- ground truth on a query subset: exact kNN over ALL n in float64 by the CPU oracle ----
@@ -411,11 +423,13 @@ def main():
     acc = run_once(main_ix, gamma, want_work=True)
     wt = work_totals(trim, acc["work"])
     assert np.array_equal(acc["ids"].cpu().numpy(), got)
-    touched = touched_bytes(w, nq, nq * k, wt, False)
+    touched = touched_bytes(w, nq, nq * k, wt, False, 16 if fs else 256)
     # the task's byte model: codes + landmark distance per scanned candidate, raw row + id per
     # exact distance, the query itself and the k results; the table never leaves LDS
-    alg_bytes = (chosen["n_scanned"] * (w.M + 4) + chosen["n_exact"] * (4 * w.d + 4) + nq * (4 * w.d + 8 * k))
-    roof = roofline_object(w, nq, t["scan_mean"], alg_bytes, wt, touched, ceil, "search_kernel<knn>")
+    alg_bytes = (chosen["n_scanned"] * (code_bytes + 4) + chosen["n_exact"] * (4 * w.d + 4) +
+                 nq * (4 * w.d + 8 * k))
+    roof = roofline_object(w, nq, t["scan_mean"], alg_bytes, wt, touched, ceil,
+                           "search_kernel<knn, 4-bit codes>" if fs else "search_kernel<knn>", fs)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     cpu = None
@@ -425,7 +439,7 @@ def main():
         def chunk(lo, hi):
             qs = np.ascontiguousarray(qh[lo:hi])
             ph = trim_oracle.ivf_probe(qs, ch, w.nprobe) if w.nlist else None
-            ro = trim_oracle.search_knn(oix, qs, k, gamma, batch, ph)
+            ro = orc.search_knn(oix, qs, k, gamma, batch, ph)
             return bool(np.array_equal(ro["ids"], got[lo:hi]))
 
         nthr = trim_oracle.num_threads()
@@ -448,7 +462,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(t["ms_per_step"], 4),
         "ms_per_step_median": round(t["step_median"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.n} base x {nq} queries, d={w.d}, PQ M={w.M}x256, "
+        "config": {"workload": f"{w.name}: {w.n} base x {nq} queries, d={w.d}, "
+                               + (f"PQ M={w.d // 2}x16 (4-bit codes), " if fs else f"PQ M={w.M}x256, ") +
                                f"IVF nlist={w.nlist} nprobe={w.nprobe}, kNN k={k}",
                    "gamma": gamma, "batch": batch, "recall_at_k": chosen["recall"],
                    "recall_truth": f"exact kNN over all n in float64 by the CPU oracle, first {nt} queries "

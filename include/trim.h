@@ -208,6 +208,23 @@ int trim_estimate_gamma(const trim_index_view *index, const int32_t *sample_rows
                         float *gamma_out, void *stream);
 
 /*
+ * The same for queries with a known distribution, the standard normal (Section 3.2: the theorem
+ * that gives Z^2 = A / (A + B + C) for Z = cos(theta), with A = (Q1 + h1)^2, B = (Q2 - h2)^2,
+ * C the sum of the other d - 2 squared coordinates, h1 = (x - l).l / |x - l|,
+ * h2 = sqrt(|l|^2 - h1^2); and the transform theorem, F_{1-Z}(y) = 1/2 -+ F_{Z^2}((1-y)^2) / 2,
+ * minus for y <= 1, applied as printed).  The distribution of Z^2 is sampled: normals [Q][d]
+ * (device) holds standard-normal variates supplied by the caller, of which only the first two
+ * coordinates and the sum of the other d - 2 squares of every row are used.  For each sampled
+ * data vector, gamma_x = the largest y on the grid y_i = 2 i / (grid - 1), 0 <= i < grid, with
+ * F_{1-Z}(y_i) <= 1 - p (0 if there is none); the global gamma is the smallest gamma_x.
+ * Arithmetic is binary64; results are written as binary32.  work: device, Q * 3 doubles,
+ * 8-byte aligned.  1 <= Q <= 16384, 2 <= grid <= 2^24, d >= 3, 8-bit codes only.
+ */
+int trim_estimate_gamma_normal(const trim_index_view *index, const int32_t *sample_rows, int32_t S,
+                               const float *normals, int32_t Q, float p, int32_t grid, double *work,
+                               float *gamma_x_out, float *gamma_out, void *stream);
+
+/*
  * Storage layout for the scan (the stored landmark codes and distances of Section 3.3,
  * preprocessing): head_out[x] = the 12 bytes {codes[x][0..7], dlx[x]}.  The kNN scan bounds
  * every candidate over its first 8 subspaces before it looks at the rest of the code, and

@@ -160,6 +160,9 @@ bool make_plan(int d, int M, bool fs, int nseg, int cap, int batch, int k, bool 
         for (int t = 0; t < nt; ++t) {
             const Tier &tier = kTiers[t];
             if (tier.needs_6_waves && (range || result_slots(k) != 1)) continue;
+            // a short table would fit four small workgroups per CU (16 waves); the instance built
+            // for six waves per SIMD does better as three 512-thread ones (24 waves)
+            if (t == 0 && !range && result_slots(k) == 1 && fs) continue;
             if (t + 1 < nt) {
                 // below the last tier a layout must leave room for a cruise when one is possible
                 // at all (else the next tier is tried first)
@@ -609,6 +612,38 @@ int trim_estimate_gamma(const trim_index_view *index, const int32_t *sample_rows
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gamma_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(gamma_kernel, dim3((unsigned)S), dim3(256), lds, st, a);
+    HIP_TRY(hipGetLastError());
+    return TRIM_OK;
+}
+
+int trim_estimate_gamma_normal(const trim_index_view *index, const int32_t *sample_rows, int32_t S,
+                               const float *normals, int32_t Q, float p, int32_t grid, double *work,
+                               float *gamma_x_out, float *gamma_out, void *stream) {
+    if (!index || index->n <= 0 || index->d <= 0 || index->M <= 0) return TRIM_INVALID_ARG;
+    if (index->code_bits == 4) return TRIM_UNSUPPORTED_SHAPE;   // 8-bit landmark codes only
+    if (index->d % index->M || index->d < 3) return TRIM_UNSUPPORTED_SHAPE;
+    if (S <= 0 || Q <= 0 || grid < 2 || !(p >= 0.0f && p <= 1.0f)) return TRIM_INVALID_ARG;
+    if (Q > 16384 || grid > (1 << 24)) return TRIM_UNSUPPORTED_SHAPE;
+    if (!index->base || !index->codes || !index->codebooks || !sample_rows || !normals || !work || !gamma_out)
+        return TRIM_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(work) & 7u) return TRIM_INVALID_ARG;
+    int npow2 = 1;
+    while (npow2 < Q) npow2 <<= 1;
+    const size_t lds = (size_t)npow2 * 8;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = fill_u32(reinterpret_cast<uint32_t *>(gamma_out), 1, 0x7f800000u, st);  // +inf
+    if (rc) return rc;
+    hipLaunchKernelGGL(normal_triples_kernel, dim3((unsigned)((Q + 255) / 256)), dim3(256), 0, st, normals,
+                       (int64_t)Q, index->d, work);
+    HIP_TRY(hipGetLastError());
+    GammaNormalArgs a{};
+    a.base = index->base; a.codes = index->codes; a.codebooks = index->codebooks; a.rows = sample_rows;
+    a.triples = work; a.n = index->n; a.d = index->d; a.M = index->M; a.Q = Q; a.npow2 = npow2;
+    a.grid = grid; a.one_minus_p = 1.0 - (double)p;
+    a.gamma_x = gamma_x_out; a.gamma_bits = reinterpret_cast<uint32_t *>(gamma_out);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(gamma_normal_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(gamma_normal_kernel, dim3((unsigned)S), dim3(256), lds, st, a);
     HIP_TRY(hipGetLastError());
     return TRIM_OK;
 }

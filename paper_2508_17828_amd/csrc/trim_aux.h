@@ -373,6 +373,121 @@ __global__ __launch_bounds__(256) void gamma_kernel(const GammaArgs a) {
     }
 }
 
+// ---- gamma from a confidence level p for standard-normal queries (Section 3.2) ----
+// The theorem of Section 3.2 gives, for a query Q ~ N(0, I) rotated so that x - l lies on the
+// first axis and l in the plane of the first two: Z^2 = A / (A + B + C), A = (Q1 + h1)^2,
+// B = (Q2 - h2)^2, C = the sum of the squares of the other d - 2 coordinates,
+// h1 = (x - l).l / |x - l|, h2 = sqrt(|l|^2 - h1^2); the transform theorem turns the
+// distribution of Z^2 into that of 1 - Z.  Only (Q1, Q2, C) of a variate row matter, and they
+// do not depend on x: a first kernel reduces every row of normal variates to that triple.
+__global__ void normal_triples_kernel(const float *__restrict__ normals, int64_t Q, int d,
+                                      double *__restrict__ triples) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= Q) return;
+    const float *row = normals + (size_t)r * d;
+    double c = 0.0;
+    for (int t = 2; t < d; ++t) c += (double)row[t] * (double)row[t];
+    triples[3 * r + 0] = (double)row[0];
+    triples[3 * r + 1] = (double)row[1];
+    triples[3 * r + 2] = c;
+}
+
+// One workgroup per sampled data vector: h1 and h2 in binary64, Z^2 for every triple, a bitonic
+// sort of the Z^2 in LDS, then the largest y on the grid y_i = 2 i / (grid - 1) whose
+// F_{1-Z}(y_i) = 1/2 -+ F_{Z^2}((1 - y_i)^2) / 2 (minus for y <= 1) is at most 1 - p
+// (F_{1-Z} rises with y: binary search over i).  gamma = min over the vectors (32-bit atomic
+// minimum on the bit pattern of the non-negative binary32 result).
+struct GammaNormalArgs {
+    const float *base;
+    const uint8_t *codes;
+    const float *codebooks;
+    const int32_t *rows;
+    const double *triples;
+    int64_t n;
+    int32_t d, M, Q, npow2, grid;
+    double one_minus_p;
+    float *gamma_x;
+    uint32_t *gamma_bits;
+};
+
+__global__ __launch_bounds__(256) void gamma_normal_kernel(const GammaNormalArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *z2 = reinterpret_cast<double *>(smem);   // [npow2]
+    __shared__ double red[3][256];
+    const int tid = threadIdx.x;
+    int64_t r = a.rows[blockIdx.x];
+    r = r < 0 ? 0 : (r >= a.n ? a.n - 1 : r);
+    const int dsub = a.d / a.M;
+    double ul = 0.0, uu = 0.0, ll = 0.0;
+    for (int t = tid; t < a.d; t += blockDim.x) {
+        const int j = t / dsub;
+        const double lt = (double)a.codebooks[((size_t)j * kC + a.codes[(size_t)r * a.M + j]) * dsub + t % dsub];
+        const double ut = (double)a.base[(size_t)r * a.d + t] - lt;
+        ul += ut * lt; uu += ut * ut; ll += lt * lt;
+    }
+    red[0][tid] = ul; red[1][tid] = uu; red[2][tid] = ll;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+        if (tid < h) { red[0][tid] += red[0][tid + h]; red[1][tid] += red[1][tid + h]; red[2][tid] += red[2][tid + h]; }
+        __syncthreads();
+    }
+    // a vector equal to its landmark has no angle: 1 - Z counts as 1 for every query (cos = 0)
+    const bool no_angle = !(red[1][0] > 0.0);
+    const double h1 = no_angle ? 0.0 : red[0][0] / sqrt(red[1][0]);
+    const double h2sq = red[2][0] - h1 * h1;
+    const double h2 = h2sq > 0.0 ? sqrt(h2sq) : 0.0;
+    for (int i = tid; i < a.npow2; i += blockDim.x) {
+        double v = __builtin_inf();
+        if (i < a.Q) {
+            const double q1 = a.triples[3 * (size_t)i], q2 = a.triples[3 * (size_t)i + 1], c = a.triples[3 * (size_t)i + 2];
+            const double A = (q1 + h1) * (q1 + h1), B = (q2 - h2) * (q2 - h2);
+            v = no_angle ? 0.0 : A / (A + B + c);
+        }
+        z2[i] = v;
+    }
+    __syncthreads();
+    for (int k = 2; k <= a.npow2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < a.npow2; i += blockDim.x) {
+                const int p = i ^ j;
+                if (p > i) {
+                    const double x = z2[i], y = z2[p];
+                    const bool up = (i & k) == 0;
+                    if ((x > y) == up) { z2[i] = y; z2[p] = x; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        // F_{1-Z}(y_i) for grid point i: the share of Z^2 values <= (1 - y_i)^2, halved either way
+        auto cdf = [&](int i) {
+            const double y = i == a.grid - 1 ? 2.0 : (double)i * (2.0 / (double)(a.grid - 1));
+            const double v = (1.0 - y) * (1.0 - y);
+            int lo = 0, hi = a.Q;                 // first index with z2 > v
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (z2[mid] <= v) lo = mid + 1; else hi = mid; }
+            const double f = (double)lo / (double)a.Q;
+            return y <= 1.0 ? 0.5 - 0.5 * f : 0.5 + 0.5 * f;
+        };
+        const double limit = a.one_minus_p + 1e-12;
+        int lo = -1, hi = a.grid - 1;             // largest i with cdf(i) <= limit (-1: none)
+        if (cdf(hi) <= limit) lo = hi;
+        else {
+            if (cdf(0) <= limit) lo = 0;
+            int l2 = lo < 0 ? -1 : 0;
+            while (l2 >= 0 && hi - l2 > 1) {
+                const int mid = (l2 + hi) >> 1;
+                if (cdf(mid) <= limit) l2 = mid; else hi = mid;
+            }
+            lo = l2;
+        }
+        const double y = lo < 0 ? 0.0 : (lo == a.grid - 1 ? 2.0 : (double)lo * (2.0 / (double)(a.grid - 1)));
+        const float g = (float)y;
+        if (a.gamma_x) a.gamma_x[blockIdx.x] = g;
+        atomicMin(a.gamma_bits, __float_as_uint(g));
+    }
+}
+
 // ---- PQ encode (Section 3.3, preprocessing step 1) ----
 // One thread per vector; the block stages one subspace's 256 centroids in LDS at a time.
 // DSUB > 0: sub-vector length known at compile time (kept in registers); DSUB == 0: generic.

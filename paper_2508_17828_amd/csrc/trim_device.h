@@ -278,13 +278,6 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) {
 // latencies overlap; the additions stay in subspace order.
 // MARK: a sum stopped half way is returned as +inf (for callers whose later tests use larger
 // thresholds than the half-way one: see the remaining-minimum thresholds of the cruise).
-// 4 * (low half of byte B of w) and 4 * (its high half): byte offsets into a row of 16 entries.
-template <int B>
-__device__ __forceinline__ uint32_t lo_nibble_times4(uint32_t w) {
-    return B == 0 ? (w << 2) & 0x3cu : (w >> (8 * B - 2)) & 0x3cu;
-}
-template <int B>
-__device__ __forceinline__ uint32_t hi_nibble_times4(uint32_t w) { return (w >> (8 * B + 2)) & 0x3cu; }
 
 // The same for 4-bit codes: every code byte adds two entries, the even subspace's (low half)
 // first; reads of 8 bytes (16 subspaces) are issued together; tests after every 8 bytes.
@@ -301,14 +294,18 @@ __device__ __forceinline__ float gather_add_fs(float s, uint32_t tab_base, const
             if (v0 + dv < VEC) {
                 const uint32_t cw = w[v0 + dv < VEC ? v0 + dv : 0];
                 const uint32_t row = tab_base + ((v0 + dv) * 4) * kRow;
-                t[8 * dv + 0] = lds_f32(row + lo_nibble_times4<0>(cw));
-                t[8 * dv + 1] = lds_f32(row + kHalf + hi_nibble_times4<0>(cw));
-                t[8 * dv + 2] = lds_f32(row + 1 * kRow + lo_nibble_times4<1>(cw));
-                t[8 * dv + 3] = lds_f32(row + 1 * kRow + kHalf + hi_nibble_times4<1>(cw));
-                t[8 * dv + 4] = lds_f32(row + 2 * kRow + lo_nibble_times4<2>(cw));
-                t[8 * dv + 5] = lds_f32(row + 2 * kRow + kHalf + hi_nibble_times4<2>(cw));
-                t[8 * dv + 6] = lds_f32(row + 3 * kRow + lo_nibble_times4<3>(cw));
-                t[8 * dv + 7] = lds_f32(row + 3 * kRow + kHalf + hi_nibble_times4<3>(cw));
+                // the low halves and the high halves of the word's four bytes, each in a byte of
+                // its own: one sub-dword-addressed shift per lookup turns a byte into 4 * code
+                const uint32_t lo = cw & 0x0f0f0f0fu;
+                const uint32_t hi = (cw >> 4) & 0x0f0f0f0fu;
+                t[8 * dv + 0] = lds_f32(row + byte_times4<0>(lo));
+                t[8 * dv + 1] = lds_f32(row + kHalf + byte_times4<0>(hi));
+                t[8 * dv + 2] = lds_f32(row + 1 * kRow + byte_times4<1>(lo));
+                t[8 * dv + 3] = lds_f32(row + 1 * kRow + kHalf + byte_times4<1>(hi));
+                t[8 * dv + 4] = lds_f32(row + 2 * kRow + byte_times4<2>(lo));
+                t[8 * dv + 5] = lds_f32(row + 2 * kRow + kHalf + byte_times4<2>(hi));
+                t[8 * dv + 6] = lds_f32(row + 3 * kRow + byte_times4<3>(lo));
+                t[8 * dv + 7] = lds_f32(row + 3 * kRow + kHalf + byte_times4<3>(hi));
             }
         }
 #pragma unroll

@@ -59,6 +59,15 @@ WORKLOADS = {
     "C5": Workload("C5", 10_000_000, 10_000, 128, 32, 4096, "clip255", nlist=4096,
                    nprobe=64, k=10, gammas=(0.0, 0.5, 0.8), batch=1024,
                    range_percentile=0.01, seed=5),
+    # Two more of the paper's dataset shapes (Table 1), as synthetic stand-ins like the rest:
+    # 5M x 384 (the shape of its 384-dimensional image-descriptor set), IVF 4096 / nprobe 64
+    # (Section 6.1: C' = 4096), PQ 48x256, kNN k=10;
+    "T384": Workload("T384", 5_000_000, 10_000, 384, 48, 2048, "clip255", nlist=4096, nprobe=64,
+                     k=10, gammas=(0.0, 0.5, 0.8), batch=1024, seed=6),
+    # 2M x 768 unit-norm embeddings (the shape of its 768-dimensional text-embedding set),
+    # IVF 2048 / nprobe 64, PQ 96x256, kNN k=10.
+    "W768": Workload("W768", 2_000_000, 10_000, 768, 96, 512, "unit", nlist=2048, nprobe=64,
+                     k=10, gammas=(0.0, 0.5, 0.8), batch=1024, seed=7),
 }
 
 

@@ -21,7 +21,7 @@ TRIM_MAX_BATCH = 4096
 TRIM_MAX_NPROBE = 4096
 
 EXPORTS = ("trim_shape_supported", "trim_fs_shape_supported", "trim_fs_encode", "trim_fs_build_lut",
-           "trim_fs_train_pq", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
+           "trim_fs_train_pq", "trim_train_pq", "trim_train_ivf", "trim_estimate_gamma", "trim_estimate_gamma_normal", "trim_encode", "trim_pack_scan_head", "trim_codes_tiled_bytes", "trim_pack_codes_tiled",
            "trim_build_lut", "trim_search_knn",
            "trim_search_range", "trim_search_range_static", "trim_static_scratch_bytes", "trim_range_workspace_bytes", "trim_ivf_probe", "trim_query_order",
            "trim_list_bounds_bytes", "trim_pack_list_bounds",
@@ -98,6 +98,9 @@ def lib() -> C.CDLL:
                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.trim_estimate_gamma.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_float,
                                           C.c_void_p, C.c_void_p, C.c_void_p]
+        L.trim_estimate_gamma_normal.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                                 C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                 C.c_void_p]
         L.trim_codes_tiled_bytes.restype = C.c_size_t
         L.trim_codes_tiled_bytes.argtypes = [C.c_int64, C.c_int32]
         L.trim_pack_codes_tiled.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
@@ -282,6 +285,22 @@ def trim_estimate_gamma(index: "Index", sample_rows: torch.Tensor, sample_querie
                                      _ptr(sample_queries, torch.float32, "sample_queries"), Q, p,
                                      _ptr(gx, torch.float32, "gamma_x"), _ptr(g, torch.float32, "gamma"),
                                      _stream()), "trim_estimate_gamma")
+    return g, gx
+
+
+def trim_estimate_gamma_normal(index: "Index", sample_rows: torch.Tensor, normals: torch.Tensor, p: float,
+                               grid: int = 20001):
+    """Returns (gamma [1] float32 on the device, gamma_x [S] float32)."""
+    S, Q = sample_rows.numel(), normals.shape[0]
+    gx = torch.empty((S,), dtype=torch.float32, device=normals.device)
+    g = torch.empty((1,), dtype=torch.float32, device=normals.device)
+    work = torch.empty((Q, 3), dtype=torch.float64, device=normals.device)
+    view = index._view()
+    _check(lib().trim_estimate_gamma_normal(C.byref(view), _ptr(sample_rows, torch.int32, "sample_rows"), S,
+                                            _ptr(normals, torch.float32, "normals"), Q, p, grid,
+                                            _ptr(work, torch.float64, "work"),
+                                            _ptr(gx, torch.float32, "gamma_x"), _ptr(g, torch.float32, "gamma"),
+                                            _stream()), "trim_estimate_gamma_normal")
     return g, gx
 
 

@@ -1,8 +1,10 @@
 """GPU parity at the full sizes of the remaining workloads, in the launch configurations
 bench.py times: C3 (1M x 960, M=120, all n scanned, k=100, all 1,000 queries), C4 (1M x 1536,
 M=192: table in two LDS phases, IVF 1024/64, range search; 2,048 queries, which the launch takes
-one chunk per query like the benchmark's 10,000, and 256 queries, which it splits into chunks)
-and C5 (10M x 128, IVF 4096/64, kNN and range, 256 queries).  Every launched query is compared
+one chunk per query like the benchmark's 10,000, and 256 queries, which it splits into chunks),
+C5 (10M x 128, IVF 4096/64, kNN and range, 256 queries), and the two further dataset shapes of
+Table 1, T384 (5M x 384, IVF 4096/64, M=48) and W768 (2M x 768 unit vectors, IVF 2048/64, M=96),
+256 queries each.  Every launched query is compared
 with the oracle, which scans them on all host threads."""
 import numpy as np
 import pytest
@@ -108,4 +110,15 @@ def test_c5_full_base(oracle):
     for gamma in (0.0, 0.5):
         check_knn(oracle, w, bw, host, queries, probes, trim, gamma, order=True)
     radius = radius_from_pairs(w, host, queries, w.range_percentile)
+    check_range(oracle, bw, host, queries, probes, trim, radius, 0.5)
+
+
+@pytest.mark.parametrize("name", ["T384", "W768"])
+def test_further_dataset_shapes_full_base(oracle, name):
+    w, bw, host, queries, probes, trim = build(name, 256, oracle)
+    check_encode_rows(oracle, host, 101)
+    check_probes(oracle, w, host, queries, probes)
+    for gamma in (0.0, 0.5):
+        check_knn(oracle, w, bw, host, queries, probes, trim, gamma, order=True)
+    radius = radius_from_pairs(w, host, queries, 0.01)
     check_range(oracle, bw, host, queries, probes, trim, radius, 0.5)

@@ -164,6 +164,28 @@ def test_gamma_from_confidence_level(T, oracle, name):
         T.trim_estimate_gamma(gi, torch.from_numpy(rows).cuda(), gq, 1.5)
 
 
+def test_gamma_for_normal_queries(T, oracle):
+    """The standard-normal route of Section 3.2 (Z^2 = A / (A + B + C) and the transform theorem)
+    against oracle/gamma_estimator.gamma_normal_queries on the same variates.  Both sides work
+    in binary64 on a grid of 20001 values of y; an order statistic that differs in its last bits
+    can move the answer by one grid step (1e-4)."""
+    import torch
+    from oracle import gamma_estimator as ge
+    b = case("c2s")
+    gi, _, _ = to_dev(T, b)
+    rng = np.random.default_rng(21)
+    rows = np.sort(rng.choice(b.index.n, 12, replace=False)).astype(np.int32)
+    normals = rng.standard_normal((3000, b.index.d)).astype(np.float32)
+    lm = ge.landmarks(b.index.codes[rows], b.index.codebooks)
+    for p in (1.0, 0.95, 0.6, 0.3):
+        g, gx = T.trim_estimate_gamma_normal(gi, torch.from_numpy(rows).cuda(), torch.from_numpy(normals).cuda(), p)
+        ref = np.array([ge.gamma_normal_queries(b.index.base[r], lm[i], normals, p) for i, r in enumerate(rows)])
+        np.testing.assert_allclose(gx.cpu().numpy(), ref, atol=1.5e-4, rtol=0)
+        assert abs(float(g.item()) - ref.min()) <= 1.5e-4
+    with pytest.raises(T.TrimError):
+        T.trim_estimate_gamma_normal(gi, torch.from_numpy(rows).cuda(), torch.from_numpy(normals).cuda(), 1.5)
+
+
 # ---- trim_ivf_probe ----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("name", ["c2s", "c4s", "c5s"])
