@@ -251,13 +251,17 @@ def bench_range(args, w, bw, probes_for, setup_s, ceil):
     lut_buf = torch.empty((nq, w.M, 256), dtype=torch.float32, device="cuda") if use_lut else None
     last = {}
 
+    def order_for(pr):
+        return trim.trim_query_order(pr, w.nlist) if pr is not None and not args.no_order else None
+
     def step(ev):
         if ev: ev[0].record()
         pr = probes_for(queries)
+        order = order_for(pr)
         lut = trim.trim_build_lut(queries, ix.codebooks, out=lut_buf) if use_lut else None
         if ev: ev[1].record()
         last["r"] = trim.trim_search_range(ix, queries, radius, gamma, probes=pr, capacity=cap,
-                                           want_stats=False, workspace=ws, lut=lut)
+                                           want_stats=False, workspace=ws, lut=lut, query_order=order)
         if ev: ev[2].record()
 
     t = timed_steps(args, step)
@@ -310,7 +314,7 @@ def bench_range(args, w, bw, probes_for, setup_s, ceil):
                    "truth": f"all vectors within the radius by the CPU oracle's exact distance over all n, "
                             f"first {nt} queries",
                    "pruning_ratio": chosen["pruning_ratio"], "results": chosen["results"],
-                   "timed": "probe selection + tables + fused scan/refine/filter + offsets + CSR fill "
+                   "timed": "probe selection + query ordering + tables + fused scan/refine/filter + offsets + CSR fill "
                             "(one host read of the result count per step), inputs in HBM",
                    "setup_s": round(setup_s, 1)},
         "roofline": roof, "cpu_baseline": cpu, "ceilings": ceil, "sweep": rows,

@@ -311,11 +311,13 @@ int trim_search_knn(const trim_index_view *index, const float *queries, int64_t 
  * is below `capacity` are written (the caller checks *required after synchronising and
  * calls again with a larger buffer).
  * workspace: device, at least trim_range_workspace_bytes(...) bytes, 256-byte aligned;
- * contents on entry are ignored.  survivor_mask as in trim_search_knn.
+ * contents on entry are ignored.  survivor_mask and query_order as in trim_search_knn (a query
+ * that query_order does not name gets no results).
  */
 int trim_search_range(const trim_index_view *index, const float *queries, int64_t nq,
                       const float *lut, const trim_candidates *cand, float radius, float gamma,
-                      int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                      const int32_t *query_order, int64_t *out_offsets, int32_t *out_ids,
+                      float *out_d2, int64_t capacity,
                       int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                       int64_t mask_words, void *workspace, size_t workspace_bytes,
                       void *stream);
@@ -337,7 +339,8 @@ int trim_search_range(const trim_index_view *index, const float *queries, int64_
 #define TRIM_STATIC_SCRATCH_BYTES (32u * 1024u * 1024u)
 int trim_search_range_static(const trim_index_view *index, const float *queries, int64_t nq,
                              const float *lut, const trim_candidates *cand, float radius, float gamma,
-                             int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                             const int32_t *query_order, int64_t *out_offsets, int32_t *out_ids,
+                             float *out_d2, int64_t capacity,
                              int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                              int64_t mask_words, void *stream);
 /* TRIM_STATIC_SCRATCH_BYTES of the loaded library. */

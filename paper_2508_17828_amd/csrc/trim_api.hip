@@ -345,7 +345,8 @@ int scratch_for_current_device(void **out) {
 // device's copy of the static scratch area.
 int range_search(const trim_index_view *index, const float *queries, int64_t nq,
                  const float *lut, const trim_candidates *cand, float radius, float gamma,
-                 int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                 const int32_t *query_order, int64_t *out_offsets, int32_t *out_ids,
+                 float *out_d2, int64_t capacity,
                  int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                  int64_t mask_words, void *workspace, size_t workspace_bytes, void *stream) {
     int rc = check_index(index);
@@ -393,6 +394,9 @@ int range_search(const trim_index_view *index, const float *queries, int64_t nq,
     a.chunk = L.chunk; a.nsplit = L.nsplit;
     a.result_mask = rmask; a.rmask_words = L.rmask_words; a.chunk_counts = counts;
     a.result_d2 = rd2;
+    a.order = query_order;
+    // a query that the order does not name is not searched: its counts must read zero
+    if (query_order && (rc = fill_u32(reinterpret_cast<uint32_t *>(counts), (size_t)nq * L.nsplit, 0u, st))) return rc;
     if (a.max_cand > max_cand) a.max_cand = (int32_t)max_cand;
 
     RangeFillArgs f{};
@@ -800,17 +804,19 @@ size_t trim_range_workspace_bytes(int64_t nq, int64_t max_candidates) {
 
 int trim_search_range(const trim_index_view *index, const float *queries, int64_t nq,
                       const float *lut, const trim_candidates *cand, float radius, float gamma,
-                      int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                      const int32_t *query_order, int64_t *out_offsets, int32_t *out_ids,
+                      float *out_d2, int64_t capacity,
                       int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                       int64_t mask_words, void *workspace, size_t workspace_bytes, void *stream) {
-    return range_search(index, queries, nq, lut, cand, radius, gamma, out_offsets, out_ids, out_d2,
+    return range_search(index, queries, nq, lut, cand, radius, gamma, query_order, out_offsets, out_ids, out_d2,
                         capacity, required, stats, survivor_mask, mask_words, workspace,
                         workspace_bytes, stream);
 }
 
 int trim_search_range_static(const trim_index_view *index, const float *queries, int64_t nq,
                              const float *lut, const trim_candidates *cand, float radius, float gamma,
-                             int64_t *out_offsets, int32_t *out_ids, float *out_d2, int64_t capacity,
+                             const int32_t *query_order, int64_t *out_offsets, int32_t *out_ids,
+                             float *out_d2, int64_t capacity,
                              int64_t *required, const trim_stats *stats, uint32_t *survivor_mask,
                              int64_t mask_words, void *stream) {
     // refuse what does not fit before anything else: no device call has been made yet
@@ -822,7 +828,7 @@ int trim_search_range_static(const trim_index_view *index, const float *queries,
     void *ws = nullptr;
     const int rc = scratch_for_current_device(&ws);
     if (rc) return rc;
-    return range_search(index, queries, nq, lut, cand, radius, gamma, out_offsets, out_ids, out_d2,
+    return range_search(index, queries, nq, lut, cand, radius, gamma, query_order, out_offsets, out_ids, out_d2,
                         capacity, required, stats, survivor_mask, mask_words, ws, kScratchBytes, stream);
 }
 

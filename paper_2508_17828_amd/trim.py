@@ -116,10 +116,10 @@ def lib() -> C.CDLL:
         L.trim_ceiling_lds_gather.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p]
         L.trim_query_order.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.trim_search_range.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
-                                        C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
-        L.trim_search_range_static.argtypes = L.trim_search_range.argtypes[:15] + [C.c_void_p]
+        L.trim_search_range_static.argtypes = L.trim_search_range.argtypes[:16] + [C.c_void_p]
         L.trim_static_scratch_bytes.restype = C.c_size_t
         L.trim_ivf_probe.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                      C.c_int32, C.c_void_p, C.c_void_p]
@@ -397,7 +397,7 @@ def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma:
                       probes: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
                       capacity: int = 0, want_stats: bool = True, want_mask: bool = False,
                       workspace: Optional[torch.Tensor] = None, static_scratch: bool = False,
-                      want_work: bool = False):
+                      want_work: bool = False, query_order: Optional[torch.Tensor] = None):
     """CSR results in scan order: dict(offsets [nq+1] int64, ids, d2, n_scanned, n_exact, mask).
 
     Synchronises once to read the result count; raises TrimCapacityError if a caller-given
@@ -434,7 +434,8 @@ def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma:
             _check(lib().trim_search_range_static(
                 C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
                 _ptr(lut, torch.float32, "lut"), C.byref(cand) if cand is not None else None,
-                radius, gamma, _ptr(offsets, torch.int64, "offsets"), _ptr(oi, torch.int32, "out_ids"),
+                radius, gamma, _ptr(query_order, torch.int32, "query_order"),
+                _ptr(offsets, torch.int64, "offsets"), _ptr(oi, torch.int32, "out_ids"),
                 _ptr(od, torch.float32, "out_d2"), cap, _ptr(required, torch.int64, "required"),
                 C.byref(stats) if stats is not None else None, _ptr(mask, torch.int32, "mask"), mw,
                 _stream()), "trim_search_range_static")
@@ -442,7 +443,8 @@ def trim_search_range(index: Index, queries: torch.Tensor, radius: float, gamma:
         _check(lib().trim_search_range(
             C.byref(view), _ptr(queries, torch.float32, "queries"), nq,
             _ptr(lut, torch.float32, "lut"), C.byref(cand) if cand is not None else None,
-            radius, gamma, _ptr(offsets, torch.int64, "offsets"), _ptr(oi, torch.int32, "out_ids"),
+            radius, gamma, _ptr(query_order, torch.int32, "query_order"),
+            _ptr(offsets, torch.int64, "offsets"), _ptr(oi, torch.int32, "out_ids"),
             _ptr(od, torch.float32, "out_d2"), cap, _ptr(required, torch.int64, "required"),
             C.byref(stats) if stats is not None else None, _ptr(mask, torch.int32, "mask"), mw,
             C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()), "trim_search_range")

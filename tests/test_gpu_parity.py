@@ -338,6 +338,16 @@ def test_query_order_changes_nothing_but_scheduling(T, oracle):
     keep = np.setdiff1d(np.arange(q.shape[0]), skipped)
     np.testing.assert_array_equal(got[keep], r["ids"][keep])
     assert np.all(got[skipped] == -7)
+    # range searches take the order too; a query it does not name gets no results
+    radius = helpers.radius_at_percentile(b, 1.0)
+    ra = T.trim_search_range(gi, q, radius, 0.3, probes=probes)
+    rb = T.trim_search_range(gi, q, radius, 0.3, probes=probes, query_order=order)
+    for key in ("offsets", "ids", "d2", "n_exact"):
+        np.testing.assert_array_equal(ra[key].cpu().numpy(), rb[key].cpu().numpy())
+    rc = T.trim_search_range(gi, q, radius, 0.3, probes=probes, query_order=bad, want_stats=False)
+    ca, cc = np.diff(ra["offsets"].cpu().numpy()), np.diff(rc["offsets"].cpu().numpy())
+    np.testing.assert_array_equal(cc[keep], ca[keep])
+    assert np.all(cc[skipped] == 0) and ca.sum() > 0
 
 
 def test_scan_head_is_a_copy_and_changes_no_result(T, oracle):
