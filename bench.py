@@ -51,6 +51,10 @@ def parse():
     ap.add_argument("--no-list-bounds", action="store_true",
                     help="time the search without the per-list summaries only (no list-level pruning)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the machine-ceiling measurements")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run only a plain elementwise pass that reads 1 GiB and writes 1 GiB, three "
+                         "times (the known-size kernel that rocprofv3's FETCH_SIZE / WRITE_SIZE are "
+                         "scaled by), and exit")
     ap.add_argument("--code-bits", type=int, default=8, choices=(8, 4),
                     help="4: index the workload with the 4-bit codes of the FastScan variant "
                          "(d/2 subspaces of 16 centroids) instead of its M subspaces of 256")
@@ -336,6 +340,14 @@ def main():
         sys.exit(2)
     trim.lib()
     torch.cuda.set_device(0)
+    if args.calibrate:
+        x = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(3):
+            torch.add(x, 1.0, out=y)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate": "3 elementwise passes, each reading 1 GiB and writing 1 GiB"}))
+        return
     w = synth.WORKLOADS[args.workload]
     batch = args.batch or w.batch
     t0 = time.time()
