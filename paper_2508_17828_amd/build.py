@@ -65,7 +65,8 @@ def check_resources(res) -> None:
 
 
 # The search kernel's instances: one object per (mode, result entries per lane, bits per code).
-INSTANCES = [(0, e, b) for b in (8, 4) for e in (1, 2, 4, 16)] + [(1, 1, 8), (1, 1, 4)]
+INSTANCES = ([(0, e, b, 0) for b in (8, 4) for e in (1, 2, 4, 16)] + [(1, 1, 8, 0), (1, 1, 4, 0)] +
+             [(0, 1, 8, 1), (0, 1, 4, 1)])   # last: the lean (80-register) small-k kNN instances
 
 
 def _compile(cmd, verbose):
@@ -89,10 +90,10 @@ def build(verbose: bool = False, extra=()) -> str:
     os.makedirs(objdir, exist_ok=True)
     cflags = [f for f in FLAGS if f != "-shared"] + list(extra) + ["-c"]
     jobs = [([hipcc] + cflags + ["-o", os.path.join(objdir, "trim_api.o"), os.path.join(CSRC, "trim_api.hip")])]
-    for mode, e, bits in INSTANCES:
-        obj = os.path.join(objdir, f"search_m{mode}_e{e}_c{bits}.o")
+    for mode, e, bits, lean in INSTANCES:
+        obj = os.path.join(objdir, f"search_m{mode}_e{e}_c{bits}_l{lean}.o")
         jobs.append([hipcc] + cflags + [f"-DTRIM_INST_MODE={mode}", f"-DTRIM_INST_E={e}",
-                                        f"-DTRIM_INST_BITS={bits}", "-o", obj,
+                                        f"-DTRIM_INST_BITS={bits}", f"-DTRIM_INST_LEAN={lean}", "-o", obj,
                                         os.path.join(CSRC, "trim_search_inst.hip")])
     workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 4))))
     res = {}

@@ -86,6 +86,7 @@ struct Ctl {
     int32_t nresult;     // range: results in this chunk
     int32_t nexact;
     int32_t nposs;       // cruise: number of possibles found in the stretch
+    int32_t npassed;     // cruise: candidates of the stretch that passed the first subspaces
     uint32_t work[8];    // WorkCounter totals of this workgroup (only kept when asked for)
 };
 
@@ -352,20 +353,24 @@ __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *
 }
 
 // E = result_slots(k) is a template parameter of the kernel, so that the common small-k case
-// does not carry the registers of the wide result sets.  That instance is held to 80
-// registers (6 waves per SIMD), so that three 512-thread workgroups share a CU.
-constexpr int kSmallKWavesPerSimd = 6;
+// does not carry the registers of the wide result sets.
+// LEAN (kNN, E = 1 only): the instance held to 80 registers (6 waves per SIMD), so that three
+// 512-thread workgroups share a CU when the table is short enough for that; it goes without
+// the bulk rounds over long codes, the tiled code copy and the deeper refine pipelines, which
+// the other instances (128 registers, at most 4 waves per SIMD) use.
+constexpr int kLeanWavesPerSimd = 6;
 // ACCT: the instance that keeps the work counters (SearchArgs::work); the plain one carries none
 // of that code.
 // FS: 4-bit codes, two per code byte, with rows of 16 table entries (see kByteRow); SearchArgs::M
 // counts code bytes in either case.
-template <int MODE, int VEC, int E, bool ACCT, bool FS>
+template <int MODE, int VEC, int E, bool ACCT, bool FS, bool LEAN>
 __global__ __launch_bounds__(1024)
-__attribute__((amdgpu_waves_per_eu(MODE == kKnn && E == 1 ? kSmallKWavesPerSimd : 4)))
+__attribute__((amdgpu_waves_per_eu(LEAN ? kLeanWavesPerSimd : 4)))
 void search_kernel(const SearchArgs a) {
+    static_assert(!LEAN || (MODE == kKnn && E == 1), "the lean instance is the small-k kNN one");
     // The tiled copy of the codes is read by the instances with 16-byte code loads, except the
-    // 80-register small-k kNN instance, whose codes are short (it reads the row-major array).
-    constexpr bool kTiledOk = VEC == 4 && !(MODE == kKnn && E == 1);
+    // lean one, whose codes are short (it reads the row-major array).
+    constexpr bool kTiledOk = VEC == 4 && !LEAN;
     extern __shared__ __align__(16) unsigned char smem[];
     float *tab = reinterpret_cast<float *>(smem);
     float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
@@ -622,7 +627,7 @@ void search_kernel(const SearchArgs a) {
         // Few long rows (the survivors of a short span): two rows per half wave with all their
         // loads in flight, instead of four rows step by step.  (Instances with the larger
         // register budget only.)
-        if ((MODE != kKnn || E > 1) && a.d >= 512 && ns <= 8 * nhalf) {
+        if (!LEAN && a.d >= 512 && ns <= 8 * nhalf) {
             for (int i = half; i < ns; i += 2 * nhalf) {
                 const int i1 = i + nhalf;
                 const bool ok1 = i1 < ns;               // uniform within the half wave
@@ -652,7 +657,7 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) rid4[u] = (MODE == kKnn && a.ids) ? a.ids[pos[u]] : pos[u];
             float d2[4];
-            exact_d2_half_x4<(MODE != kKnn || E > 1)>(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
+            exact_d2_half_x4<!LEAN>(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
                              a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d, q_lds,
                              a.d, lane32, d2);
             if (lane32 == 0) {
@@ -812,11 +817,12 @@ void search_kernel(const SearchArgs a) {
             const int S = c0 + cruise < c_end ? cruise : c_end - c0;
             const int nb = (S + a.bucket - 1) / a.bucket;   // buckets (= batches unless they are very small)
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
-            if (tid == 0) ctl->nposs = 0;
+            if (tid == 0) { ctl->nposs = 0; ctl->npassed = 0; }
             __syncthreads();
             {
                 uint32_t *ring = reinterpret_cast<uint32_t *>(wq) + (size_t)wave * kRing;  // (segment << 16) | number
                 int head = 0, count = 0;  // same in every lane of the wave
+                int passed = 0;           // candidates this wave put on its ring in this stretch
                 // A drain takes up to 64 queued candidates, one per lane.  It is split in two so
                 // that its loads are in flight while the next block is bounded: drain_issue pops
                 // the entries and starts the loads of the landmark distance and the first code
@@ -1023,14 +1029,20 @@ void search_kernel(const SearchArgs a) {
                             ring[at & (kRing - 1)] = (uint32_t)sg[u] | (uint32_t)cl;
                         }
                         count += __popcll(m);
+                        passed += __popcll(m);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                 }
                 if (d_n > 0) drain_finish();
                 while (count > 0) { drain_issue(); drain_finish(); }
+                if (lane == 0 && passed > 0) atomicAdd(&ctl->npassed, passed);
             }
             __syncthreads();
+            // A first pass that abandons less than half of the candidates only adds work (its
+            // lookups are redone when the survivor's whole code is summed): such a query goes on
+            // span by span, where a round takes a long piece of every code at once.
+            if (2 * ctl->npassed > S) cruise = 0;
             const int np = ctl->nposs;
             if (np <= a.poss_cap) {
                 // Stage B of a stretch.  The possibles are put in batch order (counting sort on
@@ -1171,7 +1183,7 @@ void search_kernel(const SearchArgs a) {
                 // Long codes: the first 8 subspaces are a small share of the sum and abandon
                 // nobody, so the first round of phase 0 is a bulk round over the whole slice.
                 const bool slice_round = ph == 0 && h0 == 0;
-                constexpr int kPieces = (MODE == kKnn && E == 1) ? 0 : 6;
+                constexpr int kPieces = LEAN ? 0 : 6;
                 const bool bulk_first = kPieces > 0 && VEC == 4 && a.M >= 64;
                 if (slice_round && !bulk_first) {
                     // ---- round 0 ----
@@ -1213,7 +1225,7 @@ void search_kernel(const SearchArgs a) {
                     // up to the next 16-byte boundary, then up to kPieces 16-byte pieces) and issues
                     // all its loads together with the landmark distance: one memory latency per
                     // queue entry instead of one per piece.  Otherwise: 32 subspaces, piece by piece.
-                    // (not in the 80-register kNN instance, which meets later rounds only on fallback)
+                    // (not in the lean instance, which meets later rounds only on fallback)
                     const bool lead8 = kPieces > 0 && VEC == 4 && (h0 & 15) == 8 && h0 + 8 <= a.Mp;
                     const int ja = h0 + (lead8 ? 8 : 0);
                     int n16 = kPieces > 0 && VEC == 4 && (ja & 15) == 0 ? (a.Mp - ja) / 16 : 0;

@@ -1,6 +1,7 @@
 // One group of instances of the fused scan kernel and its launcher.  Compiled once per
 // (TRIM_INST_MODE: 0 kNN / 1 range, TRIM_INST_E: result entries per lane of the merging wave,
-// TRIM_INST_BITS: 8- or 4-bit codes), each time into an object of its own.
+// TRIM_INST_BITS: 8- or 4-bit codes, TRIM_INST_LEAN: the 80-register small-k kNN instance), each
+// time into an object of its own.
 #include <atomic>
 
 #include "trim_launch.h"
@@ -8,10 +9,15 @@
 #if !defined(TRIM_INST_MODE) || !defined(TRIM_INST_E) || !defined(TRIM_INST_BITS)
 #error "define TRIM_INST_MODE, TRIM_INST_E and TRIM_INST_BITS"
 #endif
+#ifndef TRIM_INST_LEAN
+#define TRIM_INST_LEAN 0   // 1: the 80-register instance of small-k kNN (see search_kernel)
+#endif
 
 #define TRIM_CAT_(a, b, c, d, e, f) a##b##c##d##e##f
 #define TRIM_CAT(a, b, c, d, e, f) TRIM_CAT_(a, b, c, d, e, f)
-#if TRIM_INST_MODE == 0
+#if TRIM_INST_MODE == 0 && TRIM_INST_LEAN
+#define TRIM_INST_NAME TRIM_CAT(launch_search_, knnlean, _e, TRIM_INST_E, _c, TRIM_INST_BITS)
+#elif TRIM_INST_MODE == 0
 #define TRIM_INST_NAME TRIM_CAT(launch_search_, knn, _e, TRIM_INST_E, _c, TRIM_INST_BITS)
 #else
 #define TRIM_INST_NAME TRIM_CAT(launch_search_, range, _e, TRIM_INST_E, _c, TRIM_INST_BITS)
@@ -24,17 +30,18 @@ namespace {
 constexpr int kMode = TRIM_INST_MODE;
 constexpr int kE = TRIM_INST_E;
 constexpr bool kFs = TRIM_INST_BITS == 4;
+constexpr bool kLean = TRIM_INST_LEAN != 0;
 
 template <bool ACCT>
 int launch_instance(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
     void (*fn)(const SearchArgs) = nullptr;
     switch (pl.vec) {
-        case 4: fn = search_kernel<kMode, 4, kE, ACCT, kFs>; break;
-        case 2: fn = search_kernel<kMode, 2, kE, ACCT, kFs>; break;
+        case 4: fn = search_kernel<kMode, 4, kE, ACCT, kFs, kLean>; break;
+        case 2: fn = search_kernel<kMode, 2, kE, ACCT, kFs, kLean>; break;
         default:
             // 4-bit codes come in rows of a multiple of 8 bytes: no 4-byte code loads there
             if constexpr (kFs) return TRIM_UNSUPPORTED_SHAPE;
-            else fn = search_kernel<kMode, 1, kE, ACCT, kFs>;
+            else fn = search_kernel<kMode, 1, kE, ACCT, kFs, kLean>;
             break;
     }
     // The kernel addresses its distance table with immediate offsets from LDS address 0, so it
