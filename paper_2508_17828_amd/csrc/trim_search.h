@@ -87,6 +87,8 @@ struct Ctl {
     int32_t nexact;
     int32_t nposs;       // cruise: number of possibles found in the stretch
     int32_t npassed;     // cruise: candidates of the stretch that passed the first subspaces
+    int32_t hold;        // candidates still to be taken span by span before the next stretch is tried
+    int32_t nfail;       // stretches that failed in a row (the next one is a short trial while > 0)
     uint32_t work[8];    // WorkCounter totals of this workgroup (only kept when asked for)
 };
 
@@ -450,6 +452,13 @@ void search_kernel(const SearchArgs a) {
         ctl->tau = MODE == kRange ? a.radius2 : __builtin_inff();
         ctl->nresult = 0;
         ctl->nexact = 0;
+        ctl->hold = 0;
+        // The first stretch of a query is a trial (a short one) where a long one is likely to
+        // fail: with long codes (8 of 64 or more subspaces may abandon too few candidates for
+        // stretches to pay at all), or when much of the first probed list is still to come after
+        // the first batch (the rest of the query's nearest list passes every filter and would
+        // fill the list of possibles).
+        ctl->nfail = (a.M >= 64 || segp[1] - (a.k + a.batch) > a.poss_cap / 2) ? 1 : 0;
         for (int i = 0; i < kWorkCounters; ++i) ctl->work[i] = 0;
     }
     if (a.P == 1) fill_table<FS>(tab, a, q_lds, q, 0, a.M);
@@ -812,9 +821,17 @@ void search_kernel(const SearchArgs a) {
         // (The first span after the seed is always taken span by span: it is what makes tau tight.)
         int replay_np = -1;  // >= 0: the candidates [c0, c0 + advance) end in a replay of that many possibles
         int advance = 0;
-        if (cruise > 0 && small_span >= a.span && c0 > c_begin + kseed &&
+        if (cruise > 0 && ctl->hold <= 0 && small_span >= a.span && c0 > c_begin + kseed &&
             tau0 < __builtin_inff() && c_end - c0 > a.span) {
-            const int S = c0 + cruise < c_end ? cruise : c_end - c0;
+            // (the first stretch of a query, and the first after a failed one, is a short trial:
+            // it shows whether the first pass abandons enough for stretches to pay, see below)
+            int want = cruise;
+            const int nfail = ctl->nfail;
+            if (nfail > 0) {
+                const int probe = 4096 / a.batch * a.batch;
+                if (probe >= a.batch && probe < want) want = probe;
+            }
+            const int S = c0 + want < c_end ? want : c_end - c0;
             const int nb = (S + a.bucket - 1) / a.bucket;   // buckets (= batches unless they are very small)
             for (int b = tid; b < nb; b += T) cnt0[b] = 0;
             if (tid == 0) { ctl->nposs = 0; ctl->npassed = 0; }
@@ -822,7 +839,8 @@ void search_kernel(const SearchArgs a) {
             {
                 uint32_t *ring = reinterpret_cast<uint32_t *>(wq) + (size_t)wave * kRing;  // (segment << 16) | number
                 int head = 0, count = 0;  // same in every lane of the wave
-                int passed = 0;           // candidates this wave put on its ring in this stretch
+
+                const bool long_codes = a.M >= 64;
                 // A drain takes up to 64 queued candidates, one per lane.  It is split in two so
                 // that its loads are in flight while the next block is bounded: drain_issue pops
                 // the entries and starts the loads of the landmark distance and the first code
@@ -835,6 +853,8 @@ void search_kernel(const SearchArgs a) {
                 uint32_t d_w0[DV], d_w1[DV];
                 auto drain_issue = [&]() {
                     d_n = count < kWave ? count : kWave;
+                    // (long codes: every candidate that passed is drained once; counted for the test below)
+                    if (long_codes && lane == 0) atomicAdd(&ctl->npassed, d_n);
                     if (lane < d_n) {
                         const uint32_t e = ring[(head + lane) & (kRing - 1)];
                         d_cl = (int)(e & 0xffffu);
@@ -893,11 +913,15 @@ void search_kernel(const SearchArgs a) {
                             if (g <= tau0) {
                                 const int at = atomicAdd(&ctl->nposs, 1);
                                 if (at < a.poss_cap) { poss_cl[at] = d_cl; poss_g[at] = g; }
+
                                 atomicAdd(&cnt0[d_cl / a.bucket], 1);
                             }
                         }
                     }
                     d_n = 0;
+                    // the list of possibles has run full (a loose threshold, or near lists): the
+                    // stretch will be redone span by span anyway, so this wave stops bounding
+
                 };
                 const int nblk = (S + U * kWave - 1) / (U * kWave);
                 // the wave's own cursor into the segment table, in scalar registers
@@ -1029,20 +1053,20 @@ void search_kernel(const SearchArgs a) {
                             ring[at & (kRing - 1)] = (uint32_t)sg[u] | (uint32_t)cl;
                         }
                         count += __popcll(m);
-                        passed += __popcll(m);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                 }
                 if (d_n > 0) drain_finish();
                 while (count > 0) { drain_issue(); drain_finish(); }
-                if (lane == 0 && passed > 0) atomicAdd(&ctl->npassed, passed);
             }
             __syncthreads();
             // A first pass that abandons less than half of the candidates only adds work (its
-            // lookups are redone when the survivor's whole code is summed): such a query goes on
-            // span by span, where a round takes a long piece of every code at once.
-            if (2 * ctl->npassed > S) cruise = 0;
+            // lookups are redone when the survivor's whole code is summed, piece after piece): the
+            // query then goes on span by span, where a round takes a long piece of every code at
+            // once, for a while (twice as long after every failure in a row), and tries again
+            // with a short stretch: near lists pass the first subspaces, far ones do not.
+            bool failed = 2 * ctl->npassed > S;
             const int np = ctl->nposs;
             if (np <= a.poss_cap) {
                 // Stage B of a stretch.  The possibles are put in batch order (counting sort on
@@ -1079,14 +1103,18 @@ void search_kernel(const SearchArgs a) {
                     }
                 }
             } else {
-                // overflow: redo from c0 span by span, and shorter stretches from now on (or
-                // none): np counts every possible of the stretch, so the length that would
-                // have half filled the list is known
-                const long long want = (long long)S * a.poss_cap / (2LL * np);
-                const int shorter = (int)(want < cruise / 2 ? want : cruise / 2) / a.batch * a.batch;
-                cruise = shorter >= 2 * a.span ? shorter : 0;
+                // overflow: redo from c0 span by span, then try again with a short stretch (waves
+                // stop as soon as they see the list full, so np is no measure of the length that
+                // would have fitted: the stretch just failed)
+                failed = true;
                 cur.init(segp, segd);
                 __syncthreads();
+            }
+            if (tid == 0) {   // (read again only after the barrier at the top of the loop)
+                // (long codes: a first pass that fails once rarely pays later; short codes: the
+                // near lists are soon over)
+                ctl->hold = failed ? (a.M >= 64 ? 8192 : 2048) << (nfail < 7 ? nfail : 7) : 0;
+                ctl->nfail = failed ? nfail + 1 : 0;
             }
         }
         if (replay_np < 0) {
@@ -1368,6 +1396,7 @@ void search_kernel(const SearchArgs a) {
             if (ns > 0) refine_and_select(ns);
         }
         if (replay_np < 0) advance = span;
+        if (tid == 0) ctl->hold -= advance;   // (several barriers after everybody read it)
         }  // span path
         if (replay_np > 0) {
             __syncthreads();   // the possibles are in place
