@@ -77,7 +77,8 @@ bool fit_plan(int d, int M, int row_bytes, int nsegs, int cap, int batch, int k,
     if (cruise / batch > 1024) bucket = batch * (((cruise + 1023) / 1024 + batch - 1) / batch);
     const int nbucket = cruise > 0 ? (cruise + bucket - 1) / bucket : 0;
     const int ncnt = nbucket > nbatch ? nbucket : nbatch;
-    const size_t tab = (size_t)Mp * row_bytes;
+    // (4-bit codes: 8 KB in front of the table for the pair table of the first filter pass)
+    const size_t tab = (size_t)Mp * row_bytes + (row_bytes == (int)kByteRow<true> ? 8 * kC * 4 : 0);
     const bool can_cruise = cruise > 0 && P == 1;  // table phases need block-wide barriers
     if (need_poss && !can_cruise) return false;
     const int nwaves = tier.threads / 64;

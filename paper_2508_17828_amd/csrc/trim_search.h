@@ -15,6 +15,16 @@ enum Mode { kKnn = 0, kRange = 1 };
 // the kernel's static LDS size (it must be 0) before the first launch of an instance, and the
 // build refuses a library in which it is not.
 constexpr uint32_t kTabLds = 0;
+// With 4-bit codes the first 8 KB of LDS hold a second, derived table for the first filter pass
+// of the barrier-free stretches: P[i][c] = T[2i][c & 15] + T[2i+1][c >> 4] for the first 8 code
+// bytes i and all 256 values c of a byte, so that the pass costs one lookup and one shift per
+// code byte, as with 8-bit codes (a row of 16 entries never makes lanes collide, but costs two
+// lookups and 2.5 times the address arithmetic per byte, which is what limits this kernel).
+// The pass only decides who is looked at again: its sums may round differently from the
+// table sum proper (a pair is added first), which the abandon margin covers like the other
+// roundings of a partial sum (see abandon_threshold), and every candidate that passes has its
+// sum redone from the 16-entry rows in subspace order.  The table proper follows at kTabAt.
+template <bool FS> constexpr uint32_t kTabAt = FS ? 8 * kC * 4 : kTabLds;
 constexpr int kXcds = 8;  // accelerator dies of an MI355X, each with its own L2
 
 struct SearchArgs {
@@ -374,7 +384,8 @@ void search_kernel(const SearchArgs a) {
     // lean one, whose codes are short (it reads the row-major array).
     constexpr bool kTiledOk = VEC == 4 && !LEAN;
     extern __shared__ __align__(16) unsigned char smem[];
-    float *tab = reinterpret_cast<float *>(smem);
+    float *tab = reinterpret_cast<float *>(smem + kTabAt<FS>);
+    float *pair_tab = reinterpret_cast<float *>(smem);   // 4-bit codes only: see kTabAt
     float *q_lds = reinterpret_cast<float *>(smem + a.off_q);
     int *segp = reinterpret_cast<int *>(smem + a.off_segp);   // [nseg+1] prefix of lengths
     int *segd = reinterpret_cast<int *>(smem + a.off_segd);   // [nseg] start - prefix
@@ -463,6 +474,12 @@ void search_kernel(const SearchArgs a) {
     }
     if (a.P == 1) fill_table<FS>(tab, a, q_lds, q, 0, a.M);
     __syncthreads();
+    if constexpr (FS) {   // the pair table of the first 8 code bytes (read after later barriers)
+        for (int e = tid; e < 8 * kC; e += T) {
+            const float *row = tab + (size_t)(e >> 8) * kByteEntries<true>;
+            pair_tab[e] = row[e & 15] + row[kC4 + ((e >> 4) & 15)];
+        }
+    }
     // restv[i] = sum over the subspaces j >= 4i of the smallest entry of table row j: what the
     // subspaces still to come add to a running sum at the very least (see abandon_threshold).
     // Here: the sums of four rows' minima, one wave per group; turned into suffix sums below.
@@ -874,10 +891,10 @@ void search_kernel(const SearchArgs a) {
                         // every test of a running sum is against the threshold less what the
                         // subspaces still to come add at the least (restv; a half-way stop inside
                         // a 16-subspace piece comes back as +inf)
-                        float sum = gather_add<DV, true, FS>(0.0f, kTabLds, d_w0, thr - restv[DV == 4 ? 2 : 0]);
+                        float sum = gather_add<DV, true, FS>(0.0f, kTabAt<FS>, d_w0, thr - restv[DV == 4 ? 2 : 0]);
                         int j = 4 * DV;
                         if (two_chunks && !(sum > thr - restv[j >> 2])) {
-                            sum = gather_add<DV, true, FS>(sum, kTabLds + 4 * DV * kByteRow<FS>, d_w1,
+                            sum = gather_add<DV, true, FS>(sum, kTabAt<FS> + 4 * DV * kByteRow<FS>, d_w1,
                                                        thr - restv[DV == 4 ? 6 : 0]);
                             j = 8 * DV;
                         }
@@ -885,17 +902,17 @@ void search_kernel(const SearchArgs a) {
                             if (VEC == 4 && (j & 15) == 0 && j + 16 <= a.M) {
                                 uint32_t w[4];
                                 load_codes<4>(w, cr.at(j));
-                                sum = gather_add<4, true, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr - restv[(j >> 2) + 2]);
+                                sum = gather_add<4, true, FS>(sum, kTabAt<FS> + j * kByteRow<FS>, w, thr - restv[(j >> 2) + 2]);
                                 j += 16;
                             } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= a.M) {
                                 uint32_t w[2];
                                 load_codes<2>(w, cr.at(j));
-                                sum = gather_add<2, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
+                                sum = gather_add<2, false, FS>(sum, kTabAt<FS> + j * kByteRow<FS>, w, thr);
                                 j += 8;
                             } else {
                                 uint32_t w[1];
                                 load_codes<1>(w, cr.at(j));
-                                sum = gather_add<1, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
+                                sum = gather_add<1, false, FS>(sum, kTabAt<FS> + j * kByteRow<FS>, w, thr);
                                 j += 4;
                             }
                         }
@@ -1016,7 +1033,7 @@ void search_kernel(const SearchArgs a) {
                         const uint32_t nv = cb + U * kWave <= S ? U * kWave : S - cb;  // candidates of the block
                         tally(kWorkFirstPass, nv);
                         tally(kWorkCodeBytes, nv * (full ? (uint32_t)sizeof(HeadRecord) : H0 + 4u));
-                        tally(kWorkLookups, nv * H0 * kByteLookups<FS>);
+                        tally(kWorkLookups, nv * H0);   // (4-bit codes: one lookup per byte in the pair table)
                     }
                     if (d_n > 0) drain_finish();
                     while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
@@ -1025,11 +1042,11 @@ void search_kernel(const SearchArgs a) {
                     if constexpr (H0 == 8 && U % 2 == 0) {
 #pragma unroll
                         for (int u = 0; u < U; u += 2)
-                            gather8_pair<FS>(kTabLds, w[u], w[u + 1], sums[u], sums[u + 1]);
+                            gather8_pair<false>(kTabLds, w[u], w[u + 1], sums[u], sums[u + 1]);   // (4-bit codes: the pair table)
                     } else {
 #pragma unroll
                         for (int u = 0; u < U; ++u)
-                            sums[u] = gather_add<H0 / 4, false, FS>(0.0f, kTabLds, w[u], __builtin_inff());
+                            sums[u] = gather_add<H0 / 4, false, FS>(0.0f, kTabAt<FS>, w[u], __builtin_inff());
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
@@ -1180,7 +1197,7 @@ void search_kernel(const SearchArgs a) {
 #pragma unroll
                     for (int c = 0; c < kDirectChunks; ++c)
                         if (c * 4 * VEC < a.M)
-                            sum = gather_add<VEC, false, FS>(sum, kTabLds + c * 4 * VEC * kByteRow<FS>, w[u][c],
+                            sum = gather_add<VEC, false, FS>(sum, kTabAt<FS> + c * 4 * VEC * kByteRow<FS>, w[u][c],
                                                   __builtin_inff());
                     if (cl < whi) {
                         const float g = plb_from_s(sum, b[u], a.two_gamma);
@@ -1224,7 +1241,7 @@ void search_kernel(const SearchArgs a) {
                         issue_loads(c0, base, whi, w, bq, sg_unused);
 #pragma unroll
                         for (int u = 0; u < U; ++u) {
-                            const float sum = gather_add<H0 / 4, false, FS>(0.0f, kTabLds, w[u], __builtin_inff());
+                            const float sum = gather_add<H0 / 4, false, FS>(0.0f, kTabAt<FS>, w[u], __builtin_inff());
                             const int cl = base + u * kWave + lane;
                             const float thr = abandon_threshold(bq[u], sqrt_tau0);
                             const bool valid = cl < whi;
@@ -1288,11 +1305,11 @@ void search_kernel(const SearchArgs a) {
                             // (a sum stopped inside a 16-byte piece comes back as +inf: still
                             // above every threshold, and the accounting can tell)
                             if (bulk) {
-                                if (lead8) sum = gather_add<2, false, FS>(sum, kTabLds + h0 * kByteRow<FS>, w8, thr);
+                                if (lead8) sum = gather_add<2, false, FS>(sum, kTabAt<FS> + h0 * kByteRow<FS>, w8, thr);
 #pragma unroll
                                 for (int c = 0; c < kPieces; ++c)
                                     if (c < n16 && !(sum > thr)) {
-                                        sum = gather_add<4, true, FS>(sum, kTabLds + (ja + 16 * c) * kByteRow<FS>,
+                                        sum = gather_add<4, true, FS>(sum, kTabAt<FS> + (ja + 16 * c) * kByteRow<FS>,
                                                                   w16[c], thr);
                                         ++used16;
                                     }
@@ -1302,17 +1319,17 @@ void search_kernel(const SearchArgs a) {
                                 if (VEC == 4 && (j & 15) == 0 && j + 16 <= h1) {
                                     uint32_t w[4];
                                     load_codes<4>(w, cr.at(jp + j));
-                                    sum = gather_add<4, true, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
+                                    sum = gather_add<4, true, FS>(sum, kTabAt<FS> + j * kByteRow<FS>, w, thr);
                                     j += 16;
                                 } else if (VEC >= 2 && (j & 7) == 0 && j + 8 <= h1) {
                                     uint32_t w[2];
                                     load_codes<2>(w, cr.at(jp + j));
-                                    sum = gather_add<2, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
+                                    sum = gather_add<2, false, FS>(sum, kTabAt<FS> + j * kByteRow<FS>, w, thr);
                                     j += 8;
                                 } else {
                                     uint32_t w[1];
                                     load_codes<1>(w, cr.at(jp + j));
-                                    sum = gather_add<1, false, FS>(sum, kTabLds + j * kByteRow<FS>, w, thr);
+                                    sum = gather_add<1, false, FS>(sum, kTabAt<FS> + j * kByteRow<FS>, w, thr);
                                     j += 4;
                                 }
                                 if (sum > thr) break;

@@ -135,7 +135,7 @@ def test_range(T, oracle, name, percent, gamma):
     assert ref["offsets"][-1] > 0
 
 
-def test_work_counters_count_two_lookups_per_code_byte(T, oracle):
+def test_work_counters(T, oracle):
     b = case("c2s")
     gi, q, probes = to_dev(T, b)
     got = T.trim_search_knn(gi, q, 10, 0.4, 1024, probes=probes, want_work=True)
@@ -145,7 +145,8 @@ def test_work_counters_count_two_lookups_per_code_byte(T, oracle):
     ns = got["n_scanned"].cpu().numpy()
     nbytes = b.index.codes.shape[1]
     assert np.all(w[:, 0] + w[:, 1] + np.minimum(10, ns) >= ns)
-    assert np.all(w[:, 3] >= 16 * w[:, 0]) and np.all(w[:, 3] <= 2 * (nbytes + 8) * w[:, 0])
+    # (first pass: 8 lookups in the pair table, or 16 in the rows of 16; a full sum: 2 per code byte)
+    assert np.all(w[:, 3] >= 8 * w[:, 0]) and np.all(w[:, 3] <= 2 * (nbytes + 8) * w[:, 0])
     assert np.all(w[:, 4] >= got["n_exact"].cpu().numpy())
 
 

@@ -146,3 +146,31 @@ def test_range_full_batch_sampled_against_oracle(c2, oracle):
             np.testing.assert_array_equal(gi[off[q]:off[q + 1]], ref["ids"][ref["offsets"][j]:ref["offsets"][j + 1]])
             np.testing.assert_array_equal(gd[off[q]:off[q + 1]], ref["d2"][ref["offsets"][j]:ref["offsets"][j + 1]])
             assert ne[q] == ref["n_exact"][j]
+
+
+def test_four_bit_codes_every_query_against_oracle(oracle):
+    """C2 indexed with the 4-bit codes of the FastScan variant (64 subspaces of 16 centroids), all
+    10,000 queries in the launch configuration bench.py --code-bits 4 times: ids, distances and
+    both counters of every query equal oracle/trim_oracle_fs's; the library's encoding of all
+    1,000,000 rows equals the oracle's."""
+    import torch
+    from oracle import trim_oracle_fs as fs
+    from paper_2508_17828_amd import index_setup, trim
+    w = synth.WORKLOADS["C2"]
+    bw = index_setup.build_workload(w, code_bits=4)
+    ix = bw.index
+    h = lambda t: t.cpu().numpy()
+    host = fs.Index(h(ix.base), h(ix.codes), h(ix.dlx), h(ix.codebooks), ids=h(ix.ids),
+                    list_offsets=h(ix.list_offsets), centroids=h(bw.centroids))
+    codes, dlx = fs.encode(host.base, host.codebooks)
+    np.testing.assert_array_equal(codes, host.codes)
+    np.testing.assert_array_equal(dlx.view(np.uint32), host.dlx.view(np.uint32))
+    probes = trim.trim_ivf_probe(bw.queries, bw.centroids, w.nprobe)
+    order = trim.trim_query_order(probes, w.nlist)
+    for gamma, batch in ((0.4, 1024), (0.0, 1024), (0.4, 16)):
+        full = trim.trim_search_knn(ix, bw.queries, w.k, gamma, batch, probes=probes, query_order=order)
+        ref = fs.search_knn(host, h(bw.queries), w.k, gamma, batch, h(probes))
+        np.testing.assert_array_equal(full["ids"].cpu().numpy(), ref["ids"])
+        np.testing.assert_array_equal(full["d2"].cpu().numpy().view(np.uint32), ref["d2"].view(np.uint32))
+        np.testing.assert_array_equal(full["n_exact"].cpu().numpy(), ref["n_exact"])
+        np.testing.assert_array_equal(full["n_scanned"].cpu().numpy(), ref["n_scanned"])
