@@ -55,6 +55,13 @@ def parse():
                     help="run only a plain elementwise pass that reads 1 GiB and writes 1 GiB, three "
                          "times (the known-size kernel that rocprofv3's FETCH_SIZE / WRITE_SIZE are "
                          "scaled by), and exit")
+    ap.add_argument("--no-compare", action="store_true",
+                    help="skip the second timed leg (the same steps without list-level pruning)")
+    ap.add_argument("--ceilings-only", action="store_true",
+                    help="measure the two machine ceilings (streaming read, LDS table lookups) and exit")
+    ap.add_argument("--tables-only", action="store_true",
+                    help="time trim_build_lut on the workload's queries (vector-ALU form and matrix-core "
+                         "form, 20 launches each) and exit")
     ap.add_argument("--code-bits", type=int, default=8, choices=(8, 4),
                     help="4: index the workload with the 4-bit codes of the FastScan variant "
                          "(d/2 subspaces of 16 centroids) instead of its M subspaces of 256")
@@ -348,7 +355,20 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate": "3 elementwise passes, each reading 1 GiB and writing 1 GiB"}))
         return
+    if args.ceilings_only:
+        print(json.dumps(machine_ceilings(trim)))
+        return
     w = synth.WORKLOADS[args.workload]
+    if args.tables_only:
+        # random codebooks of the workload's shape do: the table kernels' work does not depend on values
+        q = torch.from_numpy(synth.query_vectors(w)).cuda()
+        cb = torch.randn((w.M, 256, w.d // w.M), dtype=torch.float32, device="cuda")
+        out = torch.empty((w.nq, w.M, 256), dtype=torch.float32, device="cuda")
+        res = {"workload": w.name, "table_bytes": out.numel() * 4}
+        for name, mfma in (("vector_alu_ms", False), ("matrix_cores_ms", True)):
+            res[name] = round(_event_ms(lambda: trim.trim_build_lut(q, cb, mfma=mfma, out=out), 20), 4)
+        print(json.dumps(res))
+        return
     batch = args.batch or w.batch
     t0 = time.time()
     bw = index_setup.build_workload(w, code_bits=args.code_bits)
@@ -427,7 +447,7 @@ def main():
     t = timed_steps(args, make_step(main_ix))
     got = out[0].cpu().numpy()
     other = None
-    if ix.list_bounds is not None and not args.no_list_bounds:
+    if ix.list_bounds is not None and not args.no_list_bounds and not args.no_compare:
         # the same steps without the per-list summaries (no list-level pruning)
         t2 = timed_steps(args, make_step(ix_plain))
         other = dict(value=round(nq / (t2["ms_per_step"] * 1e-3), 1), ms_per_step=round(t2["ms_per_step"], 4),

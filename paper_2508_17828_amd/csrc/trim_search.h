@@ -817,7 +817,10 @@ void search_kernel(const SearchArgs a) {
             }
         }
     };
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    // number of set bits of a ballot below the calling lane
+    auto below = [](unsigned long long m) {
+        return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    };
     int cruise = MODE == kKnn ? a.cruise : 0;  // candidates per cruise stretch (0 = never)
     // next span length while the spans of a small-batch search still grow (a multiple of batch)
     int small_span = (MODE == kKnn && a.batch < kSmallBatch) ? (64 + a.batch - 1) / a.batch * a.batch : a.span;
@@ -1254,7 +1257,7 @@ void search_kernel(const SearchArgs a) {
                             }
                             if (valid) plbs[cl] = keep;
                             const unsigned long long m = __ballot(alive);
-                            if (alive) qout[qnext + __popcll(m & lt_mask)] = (uint16_t)cl;
+                            if (alive) qout[qnext + below(m)] = (uint16_t)cl;
                             qnext += __popcll(m);
                         }
                     }
@@ -1356,7 +1359,7 @@ void search_kernel(const SearchArgs a) {
                             }
                         }
                         const unsigned long long m = __ballot(alive);
-                        if (alive) qout[qnext + __popcll(m & lt_mask)] = (uint16_t)cl;
+                        if (alive) qout[qnext + below(m)] = (uint16_t)cl;
                         qnext += __popcll(m);
                     }
                 }
