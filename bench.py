@@ -55,6 +55,10 @@ def parse():
                     help="run only a plain elementwise pass that reads 1 GiB and writes 1 GiB, three "
                          "times (the known-size kernel that rocprofv3's FETCH_SIZE / WRITE_SIZE are "
                          "scaled by), and exit")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="do not measure HBM traffic (four short child runs of this script under "
+                         "rocprofv3 --pmc before the GPU is touched here)")
+    ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--no-compare", action="store_true",
                     help="skip the second timed leg (the same steps without list-level pruning)")
     ap.add_argument("--ceilings-only", action="store_true",
@@ -100,6 +104,75 @@ def machine_ceilings(trim):
         for blocks in (768, 1024))
     return dict(stream_read_GBps=round(read, 1), lds_random_lookup_Glookups=round(look, 1),
                 lds_rows_of_16_lookup_Glookups=round(look16, 1))
+
+
+def _counter_rows(csv_path, needle):
+    """(dispatch id, value) of every dispatch of a kernel whose name contains `needle`, in order."""
+    import csv
+    rows = {}
+    with open(csv_path, newline="") as f:
+        for r in csv.DictReader(f):
+            if needle in r["Kernel_Name"]:
+                rows[int(r["Dispatch_Id"])] = rows.get(int(r["Dispatch_Id"]), 0.0) + float(r["Counter_Value"])
+    return [rows[k] for k in sorted(rows)]
+
+
+def measure_traffic(args):
+    """HBM traffic of the dominant kernel in the timed configuration: FETCH_SIZE and WRITE_SIZE (KiB
+    per dispatch) of its last three launches in a child run of this script under rocprofv3 --pmc,
+    one counter per run, each scaled by what the same counter reads for a plain elementwise pass
+    that reads 1 GiB and writes 1 GiB (two more child runs).  Must be called before this process
+    touches the GPU.  Returns None if rocprofv3 is not there or a run fails."""
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+    prof = shutil.which("rocprofv3") or "/opt/rocm/bin/rocprofv3"
+    if not os.path.exists(prof) or any(k.startswith("ROCPROF") for k in os.environ):
+        return None
+    me = os.path.abspath(__file__)
+    child = ["--workload", args.workload, "--code-bits", str(args.code_bits), "--truth-queries",
+             str(args.truth_queries), "--traffic-child"]
+    for flag, on in (("--no-order", args.no_order), ("--no-list-bounds", args.no_list_bounds),
+                     ("--no-sweep", args.no_sweep)):
+        if on:
+            child.append(flag)
+    if args.gamma is not None:
+        child += ["--gamma", str(args.gamma)]
+    if args.batch:
+        child += ["--batch", str(args.batch)]
+    env = dict(os.environ, TMPDIR="/tmp")
+    got = {}
+    try:
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            for what, argv, needle in (("kernel", child, "search_kernel"), ("copy", ["--calibrate"], "elementwise")):
+                out = tempfile.mkdtemp(prefix="trim_pmc_", dir="/tmp")
+                cmd = ["timeout", "-s", "KILL", "600", prof, "--pmc", counter, "-d", out, "-o", "p",
+                       "--output-format", "csv", "--", "python3", me] + argv
+                r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+                files = glob.glob(os.path.join(out, "**", "p_counter_collection.csv"), recursive=True)
+                if r.returncode != 0 or not files:
+                    shutil.rmtree(out, ignore_errors=True)
+                    return None
+                vals = _counter_rows(files[0], needle)
+                shutil.rmtree(out, ignore_errors=True)
+                if len(vals) < 3:
+                    return None
+                # the kernel: its last three launches are the timed configuration; the copy: its
+                # three largest dispatches are the three passes (the fill before them reads nothing)
+                got[(counter, what)] = (sum(vals[-3:]) / 3 if what == "kernel" else sum(sorted(vals)[-3:]) / 3)
+    except (OSError, KeyError, ValueError):
+        return None
+    gib_kib = float(1 << 20)
+    sf = gib_kib / got[("FETCH_SIZE", "copy")] if got[("FETCH_SIZE", "copy")] > 0 else 0.0
+    sw = gib_kib / got[("WRITE_SIZE", "copy")] if got[("WRITE_SIZE", "copy")] > 0 else 0.0
+    fetch_b = got[("FETCH_SIZE", "kernel")] * 1024 * sf
+    write_b = got[("WRITE_SIZE", "kernel")] * 1024 * sw
+    return dict(bytes_per_launch=int(fetch_b + write_b), fetch_bytes=int(fetch_b), write_bytes=int(write_b),
+                FETCH_SIZE_KiB=round(got[("FETCH_SIZE", "kernel")], 1), WRITE_SIZE_KiB=round(got[("WRITE_SIZE", "kernel")], 1),
+                scale_fetch=round(sf, 4), scale_write=round(sw, 4),
+                method="rocprofv3 --pmc, one counter per child run of this script (last 3 launches of the "
+                       "search kernel), scaled by the same counter on a 1 GiB read + 1 GiB write pass")
 
 
 def host_index(orc, ix, centroids):
@@ -151,7 +224,7 @@ def touched_bytes(w, nq, k_or_results, wt, use_lut, ncent=256):
                 total=wt["code_bytes"] + wt["rows"] * (4 * w.d + 4) + nq * 4 * w.d + table_src + k_or_results * 8)
 
 
-def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel, fs=False):
+def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel, fs=False, traffic=None):
     """The dominant kernel against the resource that binds it.  Long codes streamed once per
     query are bound by HBM; short codes shared by many queries through the caches are bound by
     the rate of table lookups out of LDS."""
@@ -181,13 +254,25 @@ def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel, fs=Fal
     # the peak, the bytes cannot have come from HBM (queries share the codes through the caches,
     # lists are passed over): HBM bounds nothing there, and the kernel is priced against the
     # table-lookup rate of LDS instead, with the byte rates listed beside it.
+    lookup_ceiling = ceil.get("lds_rows_of_16_lookup_Glookups" if fs else "lds_random_lookup_Glookups")
+    f_lds = looks / (lookup_ceiling or LDS_PEAK_GLOOKUPS)
+    trf = traffic["bytes_per_launch"] / sec / 1e9 if traffic else None
+    hbm["measured_traffic_GBps"] = round(trf, 1) if trf else None
+    hbm["measured_traffic_frac_of_peak"] = round(trf / HBM_PEAK_GBS, 4) if trf else None
     if alg <= HBM_PEAK_GBS:
         head = dict(bound="hbm", achieved=round(alg, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(alg / HBM_PEAK_GBS, 4))
+                    frac=round(alg / HBM_PEAK_GBS, 4), achieved_is="algorithmic bytes / kernel time")
+    elif trf and trf / HBM_PEAK_GBS >= f_lds:
+        # the model's bytes exceed the peak (the first pass reads 12 bytes instead of M + 4, lists
+        # are passed over, queries share codes), yet what does reach HBM is the larger share
+        head = dict(bound="hbm", achieved=round(trf, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(trf / HBM_PEAK_GBS, 4),
+                    achieved_is="HBM traffic measured in this run (rocprofv3 counters) / kernel time; the "
+                                "algorithmic bytes would exceed the peak")
     else:
         head = dict(bound="lds", achieved=round(looks, 1), peak=LDS_PEAK_GLOOKUPS, unit="Glookup/s",
                     frac=round(looks / LDS_PEAK_GLOOKUPS, 4))
-    head.update(traffic=None, kernel=kernel, kernel_ms=round(scan_ms, 4), hbm=hbm, lds=lds, work=wt,
+    head.update(traffic=traffic["bytes_per_launch"] if traffic else None, traffic_detail=traffic, kernel=kernel, kernel_ms=round(scan_ms, 4), hbm=hbm, lds=lds, work=wt,
                 candidates_per_s=dict(
                     counted=round((wt["first_pass"] + wt["skipped"]) / sec, 1),
                     read=round(wt["first_pass"] / sec, 1),
@@ -215,7 +300,7 @@ def timed_steps(args, step_fn):
                 scan_mean=sum(scans) / len(scans), scan_median=statistics.median(scans))
 
 
-def bench_range(args, w, bw, probes_for, setup_s, ceil):
+def bench_range(args, w, bw, probes_for, setup_s, ceil, traffic=None):
     """Range-search workloads (Section 2.1, range search): a step = probe selection + tables +
     the fused scan / refine / radius filter + offsets + the CSR fill, for the whole query set."""
     import numpy as np
@@ -240,8 +325,12 @@ def bench_range(args, w, bw, probes_for, setup_s, ceil):
              for q in range(nt)]
     rows = []
     gammas = [args.gamma] if args.gamma is not None else sorted(set(w.gammas))
+    def order_for(pr):
+        return trim.trim_query_order(pr, w.nlist) if pr is not None and not args.no_order else None
+
     for g in gammas:
-        r = trim.trim_search_range(ix, queries, radius, g, probes=probes_for(queries))
+        pr = probes_for(queries)
+        r = trim.trim_search_range(ix, queries, radius, g, probes=pr, query_order=order_for(pr))
         go, gi = r["offsets"].cpu().numpy(), r["ids"].cpu().numpy()
         # average precision of Section 2.1: |R'| / |R| over the queries with R nonempty (R' is a subset of R)
         vals = [len(np.intersect1d(truth[q], gi[go[q]:go[q + 1]])) / len(truth[q])
@@ -262,9 +351,6 @@ def bench_range(args, w, bw, probes_for, setup_s, ceil):
     lut_buf = torch.empty((nq, w.M, 256), dtype=torch.float32, device="cuda") if use_lut else None
     last = {}
 
-    def order_for(pr):
-        return trim.trim_query_order(pr, w.nlist) if pr is not None and not args.no_order else None
-
     def step(ev):
         if ev: ev[0].record()
         pr = probes_for(queries)
@@ -275,18 +361,25 @@ def bench_range(args, w, bw, probes_for, setup_s, ceil):
                                            want_stats=False, workspace=ws, lut=lut, query_order=order)
         if ev: ev[2].record()
 
+    if args.traffic_child:      # (run under rocprofv3 by measure_traffic: the timed launch, a few times)
+        for _ in range(4):
+            step(None)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_child": True, "gamma": gamma}))
+        return None
     t = timed_steps(args, step)
     got = last["r"]
     # what the launch touched (one untimed launch with the work counters)
     lut = trim.trim_build_lut(queries, ix.codebooks, out=lut_buf) if use_lut else None
-    acc = trim.trim_search_range(ix, queries, radius, gamma, probes=probes_for(queries), capacity=cap,
-                                 workspace=ws, lut=lut, want_work=True)
+    pr = probes_for(queries)
+    acc = trim.trim_search_range(ix, queries, radius, gamma, probes=pr, capacity=cap, workspace=ws, lut=lut,
+                                 want_work=True, query_order=order_for(pr))
     wt = work_totals(trim, acc["work"])
     touched = touched_bytes(w, nq, chosen["results"], wt, use_lut)
     alg_bytes = (chosen["n_scanned"] * (w.M + 4) + chosen["n_exact"] * (4 * w.d + 4) + nq * 4 * w.d +
                  chosen["results"] * 8 + (nq + 1) * 8)
     roof = roofline_object(w, nq, t["scan_mean"], alg_bytes, wt, touched, ceil,
-                           "search_kernel<range> + range_offsets_kernel + range_fill_kernel")
+                           "search_kernel<range> + range_offsets_kernel + range_fill_kernel", traffic=traffic)
 
     # ---- CPU baseline: the oracle on a bounded sample, results compared with the GPU's ----
     cpu = None
@@ -338,6 +431,10 @@ def main():
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
               "(the path has no collective: queries would simply be dealt out to the GPUs)", file=sys.stderr)
         sys.exit(2)
+    # HBM traffic first: its child processes must run before this one touches the GPU
+    traffic = None
+    if not (args.no_traffic or args.traffic_child or args.calibrate or args.ceilings_only or args.tables_only):
+        traffic = measure_traffic(args)
     import numpy as np
     import torch
     from paper_2508_17828_amd import index_setup, synth, trim
@@ -378,7 +475,7 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t0
     nq, k = w.nq, w.k
-    ceil = {} if args.no_ceilings else machine_ceilings(trim)
+    ceil = {} if args.no_ceilings or args.traffic_child else machine_ceilings(trim)
 
     def probes_for(q):
         return trim.trim_ivf_probe(q, bw.centroids, w.nprobe) if w.nlist else None
@@ -387,7 +484,9 @@ def main():
         if fs:
             print("bench.py: --code-bits 4 is timed on the kNN workloads", file=sys.stderr)
             sys.exit(2)
-        print(json.dumps(bench_range(args, w, bw, probes_for, setup_s, ceil)))
+        line = bench_range(args, w, bw, probes_for, setup_s, ceil, traffic)
+        if line is not None:
+            print(json.dumps(line))
         return
 
     from oracle import trim_oracle, trim_oracle_fs
@@ -420,7 +519,8 @@ def main():
     main_ix = ix_plain if args.no_list_bounds else ix
     for g in gammas:
         r = run_once(main_ix, g)
-        ms = _event_ms(lambda: run_once(main_ix, g, want_stats=False), 3) if args.gamma is None else None
+        ms = (_event_ms(lambda: run_once(main_ix, g, want_stats=False), 3)
+              if args.gamma is None and not args.traffic_child else None)
         scanned, exact = int(r["n_scanned"].sum().item()), int(r["n_exact"].sum().item())
         sweep.append(dict(gamma=g, recall=round(index_setup.recall_at_k(r["ids"][:nt], truth), 4),
                           pruning_ratio=round(1.0 - exact / max(1, scanned), 5),
@@ -444,6 +544,13 @@ def main():
             if ev: ev[2].record()
         return step
 
+    if args.traffic_child:      # (run under rocprofv3 by measure_traffic: the timed launch, a few times)
+        step = make_step(main_ix)
+        for _ in range(4):
+            step(None)
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_child": True, "gamma": gamma}))
+        return
     t = timed_steps(args, make_step(main_ix))
     got = out[0].cpu().numpy()
     other = None
@@ -465,7 +572,7 @@ def main():
     alg_bytes = (chosen["n_scanned"] * (code_bytes + 4) + chosen["n_exact"] * (4 * w.d + 4) +
                  nq * (4 * w.d + 8 * k))
     roof = roofline_object(w, nq, t["scan_mean"], alg_bytes, wt, touched, ceil,
-                           "search_kernel<knn, 4-bit codes>" if fs else "search_kernel<knn>", fs)
+                           "search_kernel<knn, 4-bit codes>" if fs else "search_kernel<knn>", fs, traffic)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload ----
     cpu = None

@@ -841,6 +841,14 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
     const int lane32 = tid & 31;
     const int ng = d >> 2;
     const int nh = T >> 5;
+    // Short vectors (at most 128 values: one 16-byte group per lane of the half wave): the lane's
+    // share of every query stays in registers, and the distance loop reads no LDS at all.
+    const bool in_regs = ng <= 32;
+    float4 qreg[QT];
+#pragma unroll
+    for (int qi = 0; qi < QT; ++qi)
+        qreg[qi] = (in_regs && lane32 < ng) ? *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * lane32)
+                                            : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     for (int l0 = tid >> 5; l0 < nlist; l0 += 2 * nh) {   // two centroid rows in flight
         const int l1 = l0 + nh;
         const bool two = l1 < nlist;                       // same for the whole half wave
@@ -849,6 +857,25 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         float acc[QT], bcc[QT];
 #pragma unroll
         for (int qi = 0; qi < QT; ++qi) { acc[qi] = 0.0f; bcc[qi] = 0.0f; }
+        if (in_regs) {
+            if (lane32 < ng) {
+                const float4 xa = ra[lane32];
+                const float4 xb = rb[lane32];
+#pragma unroll
+                for (int qi = 0; qi < QT; ++qi) {
+                    const float4 qv = qreg[qi];
+                    float e;
+                    e = qv.x - xa.x; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                    e = qv.y - xa.y; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                    e = qv.z - xa.z; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                    e = qv.w - xa.w; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
+                    e = qv.x - xb.x; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                    e = qv.y - xb.y; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                    e = qv.z - xb.z; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                    e = qv.w - xb.w; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
+                }
+            }
+        } else
         for (int g = lane32; g < ng; g += 32) {
             const float4 xa = ra[g];
             const float4 xb = rb[g];
