@@ -163,3 +163,40 @@ def test_argument_errors(T):
         T.trim_fs_encode(gi.base, gi.codebooks[:, :15].contiguous())
     with pytest.raises(T.TrimError):          # the estimator of gamma reads 8-bit codes only
         T.trim_estimate_gamma(gi, torch.zeros(4, dtype=torch.int32, device="cuda"), q, 0.9)
+
+
+def draw(seed):
+    """Seeded random configurations of an index with 4-bit codes (d a multiple of 32, so that a code
+    is a whole number of 8-byte pieces)."""
+    r = np.random.default_rng([4242, seed])
+    d = int(r.choice([32, 64, 96, 128, 256, 384]))
+    law = str(r.choice(["clip255", "aniso01", "unit"]))
+    base = {"clip255": "C2", "aniso01": "C3", "unit": "C4"}[law]
+    n = int(r.integers(2_000, 60_000))
+    use_ivf = bool(r.integers(0, 2))
+    nlist = int(r.choice([8, 24, 64])) if use_ivf else 0
+    nprobe = int(r.integers(1, nlist + 1)) if use_ivf else 0
+    k = int(r.choice([1, 10, 64, 65, 100, 300]))
+    batch = int(r.choice([1, 16, 100, 256, 1024, 4096]))
+    gamma = float(r.choice([0.0, 0.3, 0.6, 0.9]))
+    w = synth.scaled(synth.WORKLOADS[base], n, 6, d=d, M=d // 4, nlist=nlist, nprobe=nprobe, k=k,
+                     ncomp=int(r.integers(4, 40)), seed=7000 + seed, kmeans_iters=3)
+    return w, k, batch, gamma
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configuration(T, oracle, seed):
+    w, k, batch, gamma = draw(seed)
+    b = helpers.build_fs(w, pq_train_max=4096, ivf_train_per_list=32)
+    print(f"seed {seed}: n={w.n} d={w.d} k={k} batch={batch} gamma={gamma} nlist={w.nlist} nprobe={w.nprobe} "
+          f"law={w.law}", flush=True)
+    check_knn(T, b, k, gamma, batch, tiled=seed % 2 == 0, bounds=seed % 3 != 0)
+    gi, q, probes = to_dev(T, b)
+    radius = helpers.radius_at_percentile(b, 3.0, min(6, w.nq), 500)
+    got = T.trim_search_range(gi, q, radius, gamma, probes=probes, want_mask=True)
+    ref = fs.search_range(b.index, b.queries, radius, gamma, b.probes, want_mask=True)
+    np.testing.assert_array_equal(got["offsets"].cpu().numpy(), ref["offsets"])
+    np.testing.assert_array_equal(got["ids"].cpu().numpy(), ref["ids"])
+    np.testing.assert_array_equal(u32(got["d2"]), ref["d2"].view(np.uint32))
+    mw = ref["mask"].shape[1]
+    np.testing.assert_array_equal(u32(got["mask"])[:, :mw], ref["mask"])
