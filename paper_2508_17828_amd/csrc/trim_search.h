@@ -566,13 +566,17 @@ void search_kernel(const SearchArgs a) {
                         const float *row = tab + (size_t)(on ? j : 0) * kByteEntries<FS>;
                         const uint32_t w4[4] = {cw[t][g].x, cw[t][g].y, cw[t][g].z, cw[t][g].w};
                         float m = __builtin_inff();
+                        // (words past the recorded count repeat the first code: skipped)
+                        const int nrec = cnt[t][g] == kSetAny ? 0 : cnt[t][g];
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
+                            if (16 * (lane & 3) + 4 * v < nrec) {
 #pragma unroll
-                            for (int b = 0; b < 4; ++b) {
-                                const uint32_t c = (w4[v] >> (8 * b)) & 255u;
-                                // what a vector with this code byte adds (4-bit codes: both halves)
-                                m = __builtin_fminf(m, FS ? row[c & 15u] + row[kC4 + (c >> 4)] : row[c]);
+                                for (int b = 0; b < 4; ++b) {
+                                    const uint32_t c = (w4[v] >> (8 * b)) & 255u;
+                                    // what a vector with this code byte adds (4-bit codes: both halves)
+                                    m = __builtin_fminf(m, FS ? row[c & 15u] + row[kC4 + (c >> 4)] : row[c]);
+                                }
                             }
                         m = __builtin_fminf(m, __shfl_xor(m, 1));
                         m = __builtin_fminf(m, __shfl_xor(m, 2));
