@@ -152,16 +152,45 @@ __device__ __forceinline__ float exact_d2_half(const float *__restrict__ row,
     return half_reduce(acc);
 }
 
+// The lane sums of four rows at once.  Every lane of the half wave brings four values (one per
+// row); the value returned in lane l is the half-wave total of row 2*(l >> 4) + ((l >> 1) & 1),
+// bit for bit what half_reduce gives for that row: the same pairs are added at every step
+// (binary32 addition commutes, so which lane of a pair does the adding does not matter).  At
+// the step of 16 and at the step of 2 every lane hands one of its two rows to its partner and
+// keeps the other, so 16 exchanges become 7.
+__device__ __forceinline__ float half_reduce_x4(const float (&v)[4], int lane32) {
+    const bool hi = (lane32 & 16) != 0;
+    // lanes 0..15 keep rows 0 and 1, lanes 16..31 rows 2 and 3
+    const float s0 = hi ? v[0] : v[2], s1 = hi ? v[1] : v[3];
+    float k0 = hi ? v[2] : v[0], k1 = hi ? v[3] : v[1];
+    k0 = k0 + __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(s0), 0x401F));
+    k1 = k1 + __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(s1), 0x401F));
+    k0 = k0 + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(k0), 0x128, 0xf, 0xf, false));
+    k1 = k1 + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(k1), 0x128, 0xf, 0xf, false));
+    k0 = k0 + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(k0), 0x124, 0xf, 0xf, false));
+    k1 = k1 + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(k1), 0x124, 0xf, 0xf, false));
+    // lanes with bit 1 clear keep the first of their two rows, the others the second
+    const bool odd = (lane32 & 2) != 0;
+    const float send = odd ? k0 : k1;
+    float k = odd ? k1 : k0;
+    k = k + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0x4E, 0xf, 0xf, false));  // lane ^ 2
+    k = k + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(k), 0xB1, 0xf, 0xf, false));     // lane ^ 1
+    return k;
+}
+// The row whose total half_reduce_x4 leaves in a lane, and the lanes that store the four totals.
+__device__ __forceinline__ int half_reduce_x4_row(int lane32) { return ((lane32 >> 4) << 1) | ((lane32 >> 1) & 1); }
+__device__ __forceinline__ bool half_reduce_x4_writer(int lane32) { return (lane32 & 13) == 0; }
+
 // Four rows at once (same arithmetic per row as exact_d2_half; the four loads of each step
 // are in flight together).  PIPE: the next step's four loads are issued before the current
-// step is reduced (twice the registers; for long rows).
+// step is reduced (twice the registers; for long rows).  Returns the distance of row
+// half_reduce_x4_row(lane32) (see half_reduce_x4).
 template <bool PIPE>
-__device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
-                                                 const float *__restrict__ r1,
-                                                 const float *__restrict__ r2,
-                                                 const float *__restrict__ r3,
-                                                 const float *__restrict__ q, int d, int lane32,
-                                                 float (&out)[4]) {
+__device__ __forceinline__ float exact_d2_half_x4(const float *__restrict__ r0,
+                                                  const float *__restrict__ r1,
+                                                  const float *__restrict__ r2,
+                                                  const float *__restrict__ r3,
+                                                  const float *__restrict__ q, int d, int lane32) {
     const float4 *rows[4] = {reinterpret_cast<const float4 *>(r0), reinterpret_cast<const float4 *>(r1),
                              reinterpret_cast<const float4 *>(r2), reinterpret_cast<const float4 *>(r3)};
     const float4 *q4 = reinterpret_cast<const float4 *>(q);
@@ -195,8 +224,7 @@ __device__ __forceinline__ void exact_d2_half_x4(const float *__restrict__ r0,
             e = qv.w - xv[u].w; acc[u] = __builtin_fmaf(e, e, acc[u]);
         }
     }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) out[u] = half_reduce(acc[u]);
+    return half_reduce_x4(acc, lane32);
 }
 
 // Two long rows at once with ALL their loads in flight together (up to 8 steps of 128 values

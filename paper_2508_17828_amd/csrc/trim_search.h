@@ -652,7 +652,7 @@ void search_kernel(const SearchArgs a) {
 
     // Exact distances of `ns` listed candidates: one half wave per raw row, four rows in flight
     // per half wave.  pos_of(i) gives the storage position of entry i; put(i, d2, id or
-    // position) stores the result (called by one lane of the half wave).
+    // position) stores the result (called by the lane that holds the row's distance).
     auto refine_rows = [&](int ns, auto pos_of, auto put) {
         // Few long rows (the survivors of a short span): two rows per half wave with all their
         // loads in flight, instead of four rows step by step.  (Instances with the larger
@@ -686,15 +686,16 @@ void search_kernel(const SearchArgs a) {
             int32_t rid4[4];  // ids are fetched together with the rows, not after them
 #pragma unroll
             for (int u = 0; u < 4; ++u) rid4[u] = (MODE == kKnn && a.ids) ? a.ids[pos[u]] : pos[u];
-            float d2[4];
-            exact_d2_half_x4<!LEAN>(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
-                             a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d, q_lds,
-                             a.d, lane32, d2);
-            if (lane32 == 0) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (ok[u]) put(idx[u], d2[u], rid4[u]);
-            }
+            const float d2 = exact_d2_half_x4<!LEAN>(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
+                                                     a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d,
+                                                     q_lds, a.d, lane32);
+            // four lanes of the half wave hold one row's distance each and store it
+            const int mine = half_reduce_x4_row(lane32);
+            const bool hi2 = (mine & 2) != 0, lo1 = (mine & 1) != 0;
+            const bool my_ok = hi2 ? (lo1 ? ok[3] : ok[2]) : (lo1 ? ok[1] : ok[0]);
+            const int my_idx = hi2 ? (lo1 ? idx[3] : idx[2]) : (lo1 ? idx[1] : idx[0]);
+            const int32_t my_id = hi2 ? (lo1 ? rid4[3] : rid4[2]) : (lo1 ? rid4[1] : rid4[0]);
+            if (half_reduce_x4_writer(lane32) && my_ok) put(my_idx, d2, my_id);
         }
     };
 
