@@ -847,10 +847,10 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
     if (d % 4) return TRIM_UNSUPPORTED_SHAPE;
     int npow2 = 1;
     while (npow2 < nlist) npow2 <<= 1;
-    // queries per workgroup: 4, fewer if their key arrays do not fit a quarter of the LDS
-    // (so that several workgroups share a CU)
+    // queries per workgroup: 4, fewer if their key arrays do not fit half of the LDS
+    // (so that two workgroups share a CU)
     int qt = 4;
-    while (qt > 1 && (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4) > kLdsBytes / 4) qt >>= 1;
+    while (qt > 1 && (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4) > kLdsBytes / 2) qt >>= 1;
     const size_t lds = (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4);
     if (lds > kLdsBytes) return TRIM_UNSUPPORTED_SHAPE;
     if (nq == 0) return TRIM_OK;

@@ -815,9 +815,50 @@ __global__ __launch_bounds__(256) void range_fill_kernel(const RangeFillArgs a) 
     }
 }
 
+// Half-wave totals of N (32, 16 or 8) lane sums per lane at once: v[i] is the calling lane's share
+// of sum i; lane l of the half wave returns the total of sum l >> (5 - log2 N).  The additions are
+// those of half_reduce, pair by pair (lane ^ 16, ^ 8, ^ 4, ^ 2, ^ 1; binary32 addition commutes,
+// so it does not matter which lane of a pair adds): while a lane still holds several sums, it
+// hands half of them to its partner at each step and keeps the other half, so N sums take
+// N - 1 exchanges (plus one per remaining step) instead of 5 N.
+template <int BIT>
+__device__ __forceinline__ float lane_xor(float x) {
+    const int v = __float_as_int(x);
+    if constexpr (BIT == 16) return __int_as_float(__builtin_amdgcn_ds_swizzle(v, 0x401F));
+    else if constexpr (BIT == 8) return __int_as_float(__builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false));  // row rotation by 8
+    else if constexpr (BIT == 4) return __int_as_float(__builtin_amdgcn_ds_swizzle(v, 0x101F));
+    else if constexpr (BIT == 2) return __int_as_float(__builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false));
+    else return __int_as_float(__builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false));
+}
+template <int N, int BIT, int CAP>
+__device__ __forceinline__ void reduce_step(float (&v)[CAP], int lane32) {
+    if constexpr (N > 1) {
+        const bool up = (lane32 & BIT) != 0;   // these lanes keep the upper half of the sums
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i) {
+            const float keep = up ? v[i + N / 2] : v[i];
+            const float send = up ? v[i] : v[i + N / 2];
+            v[i] = keep + lane_xor<BIT>(send);
+        }
+    } else {
+        v[0] = v[0] + lane_xor<BIT>(v[0]);
+    }
+}
+template <int N>
+__device__ __forceinline__ float reduce_pairs(float (&v)[N], int lane32) {
+    static_assert(N == 32 || N == 16 || N == 8, "sums per lane");
+    reduce_step<N, 16>(v, lane32);
+    reduce_step<(N / 2 > 1 ? N / 2 : 1), 8>(v, lane32);
+    reduce_step<(N / 4 > 1 ? N / 4 : 1), 4>(v, lane32);
+    reduce_step<(N / 8 > 1 ? N / 8 : 1), 2>(v, lane32);
+    reduce_step<(N / 16 > 1 ? N / 16 : 1), 1>(v, lane32);
+    return v[0];
+}
+
 // ---- coarse probe selection (Section 6.1: IVFPQ with C' lists, nprobe probed) ----
 // One workgroup handles QT queries: every centroid row is read once and measured against
-// all QT queries (exact distances by half waves, rounding order as in exact_d2_half), then
+// all QT queries (exact distances by half waves, rounding order as in exact_d2_half; the lane
+// sums of eight rows x QT queries are reduced together), then
 // the nprobe smallest of each query's (distance bits, list id) keys are selected in LDS
 // (bitonic runs and pairwise merges) and their ids are written in ascending key order.
 template <int QT>
@@ -844,66 +885,51 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
     // Short vectors (at most 128 values: one 16-byte group per lane of the half wave): the lane's
     // share of every query stays in registers, and the distance loop reads no LDS at all.
     const bool in_regs = ng <= 32;
-    float4 qreg[QT];
+    float qrx[QT], qry[QT], qrz[QT], qrw[QT];
 #pragma unroll
-    for (int qi = 0; qi < QT; ++qi)
-        qreg[qi] = (in_regs && lane32 < ng) ? *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * lane32)
-                                            : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (int l0 = tid >> 5; l0 < nlist; l0 += 2 * nh) {   // two centroid rows in flight
-        const int l1 = l0 + nh;
-        const bool two = l1 < nlist;                       // same for the whole half wave
-        const float4 *ra = reinterpret_cast<const float4 *>(centroids + (size_t)l0 * d);
-        const float4 *rb = reinterpret_cast<const float4 *>(centroids + (size_t)(two ? l1 : l0) * d);
-        float acc[QT], bcc[QT];
+    for (int qi = 0; qi < QT; ++qi) {
+        float4 t = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (in_regs && lane32 < ng) t = *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * lane32);
+        qrx[qi] = t.x; qry[qi] = t.y; qrz[qi] = t.z; qrw[qi] = t.w;
+    }
+    // A half wave takes kRows consecutive centroid rows per pass (their loads in flight together)
+    // against the QT queries: kRows x QT lane sums per lane, reduced together (reduce_pairs), after
+    // which lane l of the half wave holds the distance of pair l >> kShift = row * QT + query and
+    // the pairs' keys are stored side by side.
+    constexpr int kRows = 8, NP = kRows * QT;
+    constexpr int kShift = NP == 32 ? 0 : NP == 16 ? 1 : 2;
+    for (int l0 = (tid >> 5) * kRows; l0 < nlist; l0 += nh * kRows) {
+        // (rows past the end: the last row again, never stored)
+        const float4 *row0 = reinterpret_cast<const float4 *>(centroids + (size_t)l0 * d);
+        const int last = nlist - 1 - l0;     // >= 0
+        float acc[NP];
 #pragma unroll
-        for (int qi = 0; qi < QT; ++qi) { acc[qi] = 0.0f; bcc[qi] = 0.0f; }
-        if (in_regs) {
-            if (lane32 < ng) {
-                const float4 xa = ra[lane32];
-                const float4 xb = rb[lane32];
-#pragma unroll
-                for (int qi = 0; qi < QT; ++qi) {
-                    const float4 qv = qreg[qi];
-                    float e;
-                    e = qv.x - xa.x; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                    e = qv.y - xa.y; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                    e = qv.z - xa.z; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                    e = qv.w - xa.w; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                    e = qv.x - xb.x; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                    e = qv.y - xb.y; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                    e = qv.z - xb.z; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                    e = qv.w - xb.w; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                }
-            }
-        } else
+        for (int i = 0; i < NP; ++i) acc[i] = 0.0f;
         for (int g = lane32; g < ng; g += 32) {
-            const float4 xa = ra[g];
-            const float4 xb = rb[g];
+            float4 x[kRows];
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) x[r] = row0[(r < last ? r : last) * ng + g];
 #pragma unroll
             for (int qi = 0; qi < QT; ++qi) {
-                const float4 qv = *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * g);
-                float e;
-                e = qv.x - xa.x; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                e = qv.y - xa.y; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                e = qv.z - xa.z; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                e = qv.w - xa.w; acc[qi] = __builtin_fmaf(e, e, acc[qi]);
-                e = qv.x - xb.x; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                e = qv.y - xb.y; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                e = qv.z - xb.z; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-                e = qv.w - xb.w; bcc[qi] = __builtin_fmaf(e, e, bcc[qi]);
-            }
-        }
+                float4 qv = make_float4(qrx[qi], qry[qi], qrz[qi], qrw[qi]);
+                if (!in_regs) qv = *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * g);
 #pragma unroll
-        for (int qi = 0; qi < QT; ++qi) {
-            const float da = half_reduce(acc[qi]);
-            const float db = half_reduce(bcc[qi]);
-            // a distance is >= 0 (or NaN): its bit pattern orders like its value
-            if (lane32 == 0) {
-                keys[(size_t)qi * npow2 + l0] = ((unsigned long long)__float_as_uint(da) << 32) | (uint32_t)l0;
-                if (two)
-                    keys[(size_t)qi * npow2 + l1] = ((unsigned long long)__float_as_uint(db) << 32) | (uint32_t)l1;
+                for (int r = 0; r < kRows; ++r) {
+                    float e, a0 = acc[r * QT + qi];
+                    e = qv.x - x[r].x; a0 = __builtin_fmaf(e, e, a0);
+                    e = qv.y - x[r].y; a0 = __builtin_fmaf(e, e, a0);
+                    e = qv.z - x[r].z; a0 = __builtin_fmaf(e, e, a0);
+                    e = qv.w - x[r].w; a0 = __builtin_fmaf(e, e, a0);
+                    acc[r * QT + qi] = a0;
+                }
             }
         }
+        const float dist = reduce_pairs<NP>(acc, lane32);
+        const int pair = lane32 >> kShift;
+        const int l = l0 + pair / QT, qi = pair % QT;
+        // a distance is >= 0 (or NaN): its bit pattern orders like its value
+        if ((lane32 & ((1 << kShift) - 1)) == 0 && l < nlist)
+            keys[(size_t)qi * npow2 + l] = ((unsigned long long)__float_as_uint(dist) << 32) | (uint32_t)l;
     }
     __syncthreads();
     // Short probe lists (nprobe <= 64, at least 256 lists): one wave per query.  The keys are seen
