@@ -199,6 +199,23 @@ def test_ivf_probe(T, oracle, name):
         np.testing.assert_array_equal(got, oracle.ivf_probe(b.queries, b.centroids, nprobe))
 
 
+@pytest.mark.parametrize("nlist,d,nq", [(1000, 128, 9), (4093, 20, 7), (4096, 384, 6), (9000, 8, 5),
+                                        (37, 516, 5), (8, 4, 3), (1, 12, 2)])
+def test_ivf_probe_shapes(T, oracle, nlist, d, nq):
+    """Every instance of the probe kernel (4, 2 and 1 queries per workgroup, chosen by the list
+    count), list counts that are not a multiple of the 8 rows a half wave takes per pass, vectors
+    shorter and longer than the 128 values a half wave holds in registers."""
+    import torch
+    rng = np.random.default_rng([77, nlist, d])
+    cen = rng.normal(size=(nlist, d)).astype(np.float32)
+    cen[nlist // 2] = cen[0]                              # equal distances: the smaller list id first
+    q = rng.normal(size=(nq, d)).astype(np.float32)
+    q[0] = cen[nlist - 1]                                 # a query on a centroid (the last row)
+    for nprobe in sorted({1, min(32, nlist), min(64, nlist), min(100, nlist)}):
+        got = T.trim_ivf_probe(torch.from_numpy(q).cuda(), torch.from_numpy(cen).cuda(), nprobe)
+        np.testing.assert_array_equal(got.cpu().numpy(), oracle.ivf_probe(q, cen, nprobe))
+
+
 # ---- trim_search_knn ---------------------------------------------------------------------------
 
 def test_ivf_probe_keys_crowded_in_few_columns(T, oracle):
