@@ -56,11 +56,15 @@ constexpr int kPossMin = 512;    // smallest possibles list worth cruising with
 constexpr int kPossMax = 2048;
 
 // Block size and LDS bytes per workgroup for 4, 3, 2 and 1 workgroups per CU (LDS is handed
-// out in 1280-byte granules).  Three 512-thread workgroups are 6 waves per SIMD: only the
-// kernel instances built for that register budget (result_slots == 1) can use that tier.
-struct Tier { int threads; size_t lds; bool needs_6_waves; };
-constexpr Tier kTiers[] = {{256, 40960, false}, {512, 53760, true}, {512, 81920, false},
-                           {1024, kLdsBytes, false}};
+// out in 1280-byte granules).  Three 512-thread workgroups, or two of 768 threads, are 6 waves
+// per SIMD: only the kernel instances built for that register budget (result_slots == 1) can use
+// those tiers.  The second is for tables too long for three workgroups (M = 40..60): with 24
+// instead of 16 waves per CU more rows and code blocks are in flight (5M x 384, M = 48: the
+// scan went 5.06 -> 4.70 ms); it is kept to codes under 64 bytes, which the 80-register
+// instance is the better one for anyway.
+struct Tier { int threads; size_t lds; bool needs_6_waves; bool short_codes_only; };
+constexpr Tier kTiers[] = {{256, 40960, false, false}, {512, 53760, true, false}, {768, 81920, true, true},
+                           {512, 81920, false, false}, {1024, kLdsBytes, false, false}};
 
 // One attempt: table phases P, a footprint tier, a span; need_poss: only layouts with a possibles
 // list (a cruise) count.
@@ -164,6 +168,7 @@ bool make_plan(int d, int M, bool fs, int nseg, int cap, int batch, int k, bool 
         for (int t = 0; t < nt; ++t) {
             const Tier &tier = kTiers[t];
             if (tier.needs_6_waves && (range || result_slots(k) != 1)) continue;
+            if (tier.short_codes_only && M >= 64) continue;
             // a short table would fit four small workgroups per CU (16 waves); the instance built
             // for six waves per SIMD does better as three 512-thread ones (24 waves)
             if (t == 0 && !range && result_slots(k) == 1 && fs) continue;

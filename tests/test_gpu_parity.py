@@ -49,6 +49,7 @@ CASES = {
     "c3s": ("C3", 12_000, 24, -1, -1),           # d=960, M=120 (8-byte code loads), k=100
     "c4s": ("C4", 16_000, 32, 32, 6),            # d=1536, M=192: table in two LDS phases
     "c5s": ("C5", 80_000, 64, 128, 16),          # M=32 with many short lists
+    "t384s": ("T384", 60_000, 48, 64, 16),       # d=384, M=48: two 768-thread workgroups per CU
 }
 
 
@@ -263,7 +264,8 @@ def test_knn_c1(T, oracle, gamma, batch):
 @pytest.mark.parametrize("name,k,batch", [("c2s", 10, 1024), ("c2s", 1, 64), ("c2s", 70, 333),
                                           ("c5s", 10, 1024), ("c3s", 100, 4096),
                                           ("c3s", 100, 512), ("c4s", 10, 2048),
-                                          ("c3s", 100, 16), ("c2s", 70, 1), ("c2s", 300, 5)])
+                                          ("c3s", 100, 16), ("c2s", 70, 1), ("c2s", 300, 5),
+                                          ("t384s", 10, 1024), ("t384s", 64, 96), ("t384s", 3, 1)])
 @pytest.mark.parametrize("gamma", [0.0, 0.5, 0.8])
 def test_knn_shapes(T, oracle, name, k, batch, gamma):
     got, ref = check_knn(T, oracle, case(name), k, gamma, batch)
