@@ -66,7 +66,7 @@ def check_resources(res) -> None:
 
 # The search kernel's instances: one object per (mode, result entries per lane, bits per code).
 INSTANCES = ([(0, e, b, 0) for b in (8, 4) for e in (1, 2, 4, 16)] + [(1, 1, 8, 0), (1, 1, 4, 0)] +
-             [(0, 1, 8, 1), (0, 1, 4, 1)])   # last: the lean (80-register) small-k kNN instances
+             [(0, 1, 8, 1), (0, 1, 4, 1), (0, 1, 8, 2), (0, 1, 4, 2)])   # last: the lean (80-register) small-k kNN instances, for short and for long rows
 
 
 def _compile(cmd, verbose):

@@ -139,7 +139,7 @@ bool fit_plan(int d, int M, int row_bytes, int nsegs, int cap, int batch, int k,
         pl->threads = tier.threads;
         // the 80-register instance: needed for three workgroups per CU, and the better one for short
         // codes in any case (the other's bulk rounds and deeper refine pipelines pay from 64 code bytes on)
-        pl->lean = tier.needs_6_waves || M < 64;
+        pl->lean = !(tier.needs_6_waves || M < 64) ? kFullInstance : d <= 128 ? kLeanShortRows : kLeanLongRows;
         pl->wqcap = wqcap;
         pl->cruise = p > 0 ? cruise : 0;
         pl->poss_cap = p;
@@ -203,6 +203,7 @@ int launch_search(bool range, bool fs, const SearchArgs &a, const Plan &pl, dim3
     // k decides how many result entries a lane of the merging wave holds (result_slots)
     switch (result_slots(a.k)) {
         case 1:
+            if (pl.lean == kLeanLongRows) return fs ? launch_search_knnleanlong_e1_c4(a, pl, grid, st) : launch_search_knnleanlong_e1_c8(a, pl, grid, st);
             if (pl.lean) return fs ? launch_search_knnlean_e1_c4(a, pl, grid, st) : launch_search_knnlean_e1_c8(a, pl, grid, st);
             return fs ? launch_search_knn_e1_c4(a, pl, grid, st) : launch_search_knn_e1_c8(a, pl, grid, st);
         case 2: return fs ? launch_search_knn_e2_c4(a, pl, grid, st) : launch_search_knn_e2_c8(a, pl, grid, st);

@@ -183,9 +183,10 @@ __device__ __forceinline__ bool half_reduce_x4_writer(int lane32) { return (lane
 
 // Four rows at once (same arithmetic per row as exact_d2_half; the four loads of each step
 // are in flight together).  PIPE: the next step's four loads are issued before the current
-// step is reduced (twice the registers; for long rows).  Returns the distance of row
+// step is reduced (twice the registers; for long rows).  ONE_STEP: the caller guarantees rows of
+// at most 128 values.  Returns the distance of row
 // half_reduce_x4_row(lane32) (see half_reduce_x4).
-template <bool PIPE>
+template <bool PIPE, bool ONE_STEP = false>
 __device__ __forceinline__ float exact_d2_half_x4(const float *__restrict__ r0,
                                                   const float *__restrict__ r1,
                                                   const float *__restrict__ r2,
@@ -201,6 +202,7 @@ __device__ __forceinline__ float exact_d2_half_x4(const float *__restrict__ r0,
 #pragma unroll
         for (int u = 0; u < 4; ++u) nxt[u] = rows[u][lane32];
     }
+    // (ONE_STEP: rows of at most 128 values, one 16-byte group per lane)
     for (int g = lane32; g < ng; g += 32) {
         float4 xv[4];
         if (PIPE) {
@@ -223,19 +225,20 @@ __device__ __forceinline__ float exact_d2_half_x4(const float *__restrict__ r0,
             e = qv.z - xv[u].z; acc[u] = __builtin_fmaf(e, e, acc[u]);
             e = qv.w - xv[u].w; acc[u] = __builtin_fmaf(e, e, acc[u]);
         }
+        if (ONE_STEP) break;
     }
     return half_reduce_x4(acc, lane32);
 }
 
-// Two long rows at once with ALL their loads in flight together (up to 8 steps of 128 values
+// Two long rows at once with ALL their loads in flight together (up to kDeep steps of 128 values
 // per row and pass; longer rows take several passes).  For the few survivors of a short span,
 // where the latency of a row's dependent steps, not bandwidth, is what the refine step waits
 // for.  Same arithmetic per row as exact_d2_half.
+template <int kDeep = 8>
 __device__ __forceinline__ void exact_d2_half_x2_deep(const float *__restrict__ r0,
                                                       const float *__restrict__ r1,
                                                       const float *__restrict__ q, int d, int lane32,
                                                       float (&out)[2]) {
-    constexpr int kDeep = 8;
     const float4 *rows[2] = {reinterpret_cast<const float4 *>(r0), reinterpret_cast<const float4 *>(r1)};
     const float4 *q4 = reinterpret_cast<const float4 *>(q);
     float acc[2] = {0.0f, 0.0f};

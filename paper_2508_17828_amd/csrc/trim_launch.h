@@ -19,7 +19,7 @@ struct Plan {
     uint32_t off_q, off_segp, off_segd, off_rest, off_seglb, off_spos, off_sd2, off_sidx, off_rd2, off_rid, off_ctl;
     uint32_t off_plb, off_cnt, off_wq;
     int span, wqcap, cruise, poss_cap, scap, rcap, bucket;
-    bool lean;   // small-k kNN: launch the 80-register instance (three workgroups per CU, or short codes)
+    int lean;    // a LeanKind; small-k kNN: launch an 80-register instance (six waves per SIMD, or short codes)
 };
 
 // Records a failed HIP call for trim_last_hip_error and returns TRIM_HIP_ERROR.
@@ -37,6 +37,8 @@ int hip_fail(hipError_t e);
     int name(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st)
 TRIM_DECLARE_LAUNCH(launch_search_knnlean_e1_c8);
 TRIM_DECLARE_LAUNCH(launch_search_knnlean_e1_c4);
+TRIM_DECLARE_LAUNCH(launch_search_knnleanlong_e1_c8);
+TRIM_DECLARE_LAUNCH(launch_search_knnleanlong_e1_c4);
 TRIM_DECLARE_LAUNCH(launch_search_knn_e1_c8);
 TRIM_DECLARE_LAUNCH(launch_search_knn_e2_c8);
 TRIM_DECLARE_LAUNCH(launch_search_knn_e4_c8);

@@ -366,22 +366,27 @@ __device__ __forceinline__ int replay_batches(const int32_t *s_cl, const float *
 
 // E = result_slots(k) is a template parameter of the kernel, so that the common small-k case
 // does not carry the registers of the wide result sets.
-// LEAN (kNN, E = 1 only): the instance held to 80 registers (6 waves per SIMD), so that three
+// LEAN_KIND (kNN, E = 1 only; see LeanKind): the instances held to 80 registers (6 waves per SIMD), so that three
 // 512-thread workgroups share a CU when the table is short enough for that; it goes without
 // the bulk rounds over long codes, the tiled code copy and the deeper refine pipelines, which
 // the other instances (128 registers, at most 4 waves per SIMD) use.
 constexpr int kLeanWavesPerSimd = 6;
+// The lean instance comes in two kinds, one per shape of the refine step, so that neither carries
+// the other's code: rows of at most 128 values (four rows per half wave, one 16-byte group per
+// lane and row) and longer rows (two rows per half wave with three groups of each in flight).
+enum LeanKind { kFullInstance = 0, kLeanShortRows = 1, kLeanLongRows = 2 };
 // ACCT: the instance that keeps the work counters (SearchArgs::work); the plain one carries none
 // of that code.
 // FS: 4-bit codes, two per code byte, with rows of 16 table entries (see kByteRow); SearchArgs::M
 // counts code bytes in either case.
-template <int MODE, int VEC, int E, bool ACCT, bool FS, bool LEAN>
+template <int MODE, int VEC, int E, bool ACCT, bool FS, int LEAN_KIND>
 __global__ __launch_bounds__(1024)
-__attribute__((amdgpu_waves_per_eu(LEAN ? kLeanWavesPerSimd : 4)))
+__attribute__((amdgpu_waves_per_eu(LEAN_KIND != kFullInstance ? kLeanWavesPerSimd : 4)))
 void search_kernel(const SearchArgs a) {
-    static_assert(!LEAN || (MODE == kKnn && E == 1), "the lean instance is the small-k kNN one");
+    constexpr bool LEAN = LEAN_KIND != kFullInstance;
+    static_assert(!LEAN || (MODE == kKnn && E == 1), "the lean instances are the small-k kNN ones");
     // The tiled copy of the codes is read by the instances with 16-byte code loads, except the
-    // lean one, whose codes are short (it reads the row-major array).
+    // lean ones, whose codes are short (they read the row-major array).
     constexpr bool kTiledOk = VEC == 4 && !LEAN;
     extern __shared__ __align__(16) unsigned char smem[];
     float *tab = reinterpret_cast<float *>(smem + kTabAt<FS>);
@@ -654,10 +659,10 @@ void search_kernel(const SearchArgs a) {
     // per half wave.  pos_of(i) gives the storage position of entry i; put(i, d2, id or
     // position) stores the result (called by the lane that holds the row's distance).
     auto refine_rows = [&](int ns, auto pos_of, auto put) {
-        // Few long rows (the survivors of a short span): two rows per half wave with all their
-        // loads in flight, instead of four rows step by step.  (Instances with the larger
-        // register budget only.)
-        if (!LEAN && a.d >= 512 && ns <= 8 * nhalf) {
+        // Two rows per half wave with several 16-byte groups of each in flight, instead of four
+        // rows step by step: the lean instance for long rows always (three groups: its register
+        // budget), the full instance for the few long rows that survive a short span (eight).
+        if (LEAN_KIND == kLeanLongRows || (!LEAN && a.d >= 512 && ns <= 8 * nhalf)) {
             for (int i = half; i < ns; i += 2 * nhalf) {
                 const int i1 = i + nhalf;
                 const bool ok1 = i1 < ns;               // uniform within the half wave
@@ -665,8 +670,8 @@ void search_kernel(const SearchArgs a) {
                 const int32_t id0 = (MODE == kKnn && a.ids) ? a.ids[p0] : p0;
                 const int32_t id1 = (MODE == kKnn && a.ids) ? a.ids[p1] : p1;
                 float d2[2];
-                exact_d2_half_x2_deep(a.base + (size_t)p0 * a.d, a.base + (size_t)p1 * a.d, q_lds, a.d,
-                                      lane32, d2);
+                exact_d2_half_x2_deep<LEAN ? 3 : 8>(a.base + (size_t)p0 * a.d, a.base + (size_t)p1 * a.d, q_lds,
+                                                    a.d, lane32, d2);
                 if (lane32 == 0) {
                     put(i, d2[0], id0);
                     if (ok1) put(i1, d2[1], id1);
@@ -674,6 +679,7 @@ void search_kernel(const SearchArgs a) {
             }
             return;
         }
+        if constexpr (LEAN_KIND != kLeanLongRows)   // (that instance goes without this loop)
         for (int i = half; i < ns; i += 4 * nhalf) {
             int idx[4], pos[4];
             bool ok[4];
@@ -686,9 +692,9 @@ void search_kernel(const SearchArgs a) {
             int32_t rid4[4];  // ids are fetched together with the rows, not after them
 #pragma unroll
             for (int u = 0; u < 4; ++u) rid4[u] = (MODE == kKnn && a.ids) ? a.ids[pos[u]] : pos[u];
-            const float d2 = exact_d2_half_x4<!LEAN>(a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d,
-                                                     a.base + (size_t)pos[2] * a.d, a.base + (size_t)pos[3] * a.d,
-                                                     q_lds, a.d, lane32);
+            const float d2 = exact_d2_half_x4<!LEAN, LEAN_KIND == kLeanShortRows>(
+                a.base + (size_t)pos[0] * a.d, a.base + (size_t)pos[1] * a.d, a.base + (size_t)pos[2] * a.d,
+                a.base + (size_t)pos[3] * a.d, q_lds, a.d, lane32);
             // four lanes of the half wave hold one row's distance each and store it
             const int mine = half_reduce_x4_row(lane32);
             const bool hi2 = (mine & 2) != 0, lo1 = (mine & 1) != 0;

@@ -1,6 +1,6 @@
 // One group of instances of the fused scan kernel and its launcher.  Compiled once per
 // (TRIM_INST_MODE: 0 kNN / 1 range, TRIM_INST_E: result entries per lane of the merging wave,
-// TRIM_INST_BITS: 8- or 4-bit codes, TRIM_INST_LEAN: the 80-register small-k kNN instance), each
+// TRIM_INST_BITS: 8- or 4-bit codes, TRIM_INST_LEAN: an 80-register small-k kNN instance), each
 // time into an object of its own.
 #include <atomic>
 
@@ -10,12 +10,14 @@
 #error "define TRIM_INST_MODE, TRIM_INST_E and TRIM_INST_BITS"
 #endif
 #ifndef TRIM_INST_LEAN
-#define TRIM_INST_LEAN 0   // 1: the 80-register instance of small-k kNN (see search_kernel)
+#define TRIM_INST_LEAN 0   // 1, 2: the 80-register instances of small-k kNN (see LeanKind)
 #endif
 
 #define TRIM_CAT_(a, b, c, d, e, f) a##b##c##d##e##f
 #define TRIM_CAT(a, b, c, d, e, f) TRIM_CAT_(a, b, c, d, e, f)
-#if TRIM_INST_MODE == 0 && TRIM_INST_LEAN
+#if TRIM_INST_MODE == 0 && TRIM_INST_LEAN == 2
+#define TRIM_INST_NAME TRIM_CAT(launch_search_, knnleanlong, _e, TRIM_INST_E, _c, TRIM_INST_BITS)
+#elif TRIM_INST_MODE == 0 && TRIM_INST_LEAN
 #define TRIM_INST_NAME TRIM_CAT(launch_search_, knnlean, _e, TRIM_INST_E, _c, TRIM_INST_BITS)
 #elif TRIM_INST_MODE == 0
 #define TRIM_INST_NAME TRIM_CAT(launch_search_, knn, _e, TRIM_INST_E, _c, TRIM_INST_BITS)
@@ -30,7 +32,7 @@ namespace {
 constexpr int kMode = TRIM_INST_MODE;
 constexpr int kE = TRIM_INST_E;
 constexpr bool kFs = TRIM_INST_BITS == 4;
-constexpr bool kLean = TRIM_INST_LEAN != 0;
+constexpr int kLean = TRIM_INST_LEAN;   // a LeanKind
 
 template <bool ACCT>
 int launch_instance(const SearchArgs &a, const Plan &pl, dim3 grid, hipStream_t st) {
