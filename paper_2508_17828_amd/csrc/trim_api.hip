@@ -139,7 +139,8 @@ bool fit_plan(int d, int M, int row_bytes, int nsegs, int cap, int batch, int k,
         pl->threads = tier.threads;
         // the 80-register instance: needed for three workgroups per CU, and the better one for short
         // codes in any case (the other's bulk rounds and deeper refine pipelines pay from 64 code bytes on)
-        pl->lean = !(tier.needs_6_waves || M < 64) ? kFullInstance : d <= 128 ? kLeanShortRows : kLeanLongRows;
+        pl->lean = !(P == 1 && M <= 256 && (tier.needs_6_waves || M < 64)) ? kFullInstance
+                   : d <= 128 ? kLeanShortRows : kLeanLongRows;
         pl->wqcap = wqcap;
         pl->cruise = p > 0 ? cruise : 0;
         pl->poss_cap = p;

@@ -415,6 +415,11 @@ void search_kernel(const SearchArgs a) {
     // optional accounting of the work done (same for every thread); totals gather in LDS
     constexpr bool acct = ACCT;
     auto tally = [&](int which, uint32_t v) { atomicAdd(&ctl->work[which], v); };
+    // The lean instances only run with the whole table in LDS and the tighter thresholds on (the
+    // host sees to it), so the table phases and the switch are compiled out of them.
+    const int nphase = LEAN ? 1 : a.P;
+    const int Mp = LEAN ? a.M : a.Mp;
+    const bool use_rest = LEAN ? true : a.use_rest != 0;
     // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of the
     // (optionally sorted) query order so that concurrent workgroups of an XCD scan the same
     // lists and share its L2.
@@ -477,7 +482,7 @@ void search_kernel(const SearchArgs a) {
         ctl->nfail = (a.M >= 64 || segp[1] - (a.k + a.batch) > a.poss_cap / 2) ? 1 : 0;
         for (int i = 0; i < kWorkCounters; ++i) ctl->work[i] = 0;
     }
-    if (a.P == 1) fill_table<FS>(tab, a, q_lds, q, 0, a.M);
+    if (nphase == 1) fill_table<FS>(tab, a, q_lds, q, 0, a.M);
     __syncthreads();
     if constexpr (FS) {   // the pair table of the first 8 code bytes (read after later barriers)
         for (int e = tid; e < 8 * kC; e += T) {
@@ -488,7 +493,7 @@ void search_kernel(const SearchArgs a) {
     // restv[i] = sum over the subspaces j >= 4i of the smallest entry of table row j: what the
     // subspaces still to come add to a running sum at the very least (see abandon_threshold).
     // Here: the sums of four rows' minima, one wave per group; turned into suffix sums below.
-    if (MODE == kKnn && a.use_rest) {
+    if (MODE == kKnn && use_rest) {
         for (int i = tid >> 6; i < a.M / 4; i += T >> 6) {
             float gsum = 0.0f;
 #pragma unroll
@@ -516,9 +521,9 @@ void search_kernel(const SearchArgs a) {
     __syncthreads();
     if (tid == 0) {
         float acc = 0.0f;
-        restv[a.Mp / 4] = 0.0f;
-        for (int i = a.Mp / 4 - 1; i >= 0; --i) {
-            acc = (MODE == kKnn && a.use_rest) ? acc + restv[i] : 0.0f;
+        restv[Mp / 4] = 0.0f;
+        for (int i = Mp / 4 - 1; i >= 0; --i) {
+            acc = (MODE == kKnn && use_rest) ? acc + restv[i] : 0.0f;
             restv[i] = acc;
         }
     }   // (read after the next barrier: the seed's, or the one at the top of the main loop)
@@ -530,7 +535,7 @@ void search_kernel(const SearchArgs a) {
     // landmark distance), so while lb exceeds that, nothing in the list can survive.
     // Two segments per wave and round; a lane takes 16 recorded codes of one subspace (4 lanes
     // per subspace, 32 subspaces of either list per step, all loads of a step issued together).
-    if (MODE == kKnn && a.use_rest && a.nseg > 0 && a.list_bounds != nullptr) {
+    if (MODE == kKnn && use_rest && a.nseg > 0 && a.list_bounds != nullptr) {
         constexpr int kH0 = VEC >= 2 ? 8 : 4;
         const size_t rec_bytes = list_record_bytes(a.M);
         if (acct && tid == 0) tally(kWorkCodeBytes, (uint32_t)(nseg * rec_bytes));
@@ -964,7 +969,7 @@ void search_kernel(const SearchArgs a) {
                     float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, restv[H0 / 4])));
                 // list-level pruning: a list is passed over while its slack > st (both compared as
                 // integers: st > 0, and a negative slack is a negative integer)
-                const bool have_lb = a.use_rest && a.nseg > 0 && a.list_bounds != nullptr;
+                const bool have_lb = use_rest && a.nseg > 0 && a.list_bounds != nullptr;
                 const int st_bits = __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sqrt_tau0));
                 for (int blk = wave; blk < nblk; blk += nwaves) {
                     // this block's loads fly while the previous drain is finished; the next
@@ -1180,7 +1185,7 @@ void search_kernel(const SearchArgs a) {
         // nobody, so the rounds would only add dependent memory latencies: its candidates are
         // bounded in one go instead, two per lane, with all their loads issued together.
         constexpr int kDirectChunks = 2;  // code chunks of 4*VEC bytes a lane keeps per candidate
-        const bool direct = MODE == kKnn && VEC == 4 && a.P == 1 && a.M <= 4 * VEC * kDirectChunks &&
+        const bool direct = MODE == kKnn && VEC == 4 && nphase == 1 && a.M <= 4 * VEC * kDirectChunks &&
                             a.M % (4 * VEC) == 0 && c0 == c_begin + kseed;
         if (direct) {
             constexpr int UD = 2;
@@ -1229,14 +1234,14 @@ void search_kernel(const SearchArgs a) {
             }
         }
         int rnd = 0;  // rounds taken so far (the second one reads the rest of a code for the first time)
-        for (int ph = 0; ph < (direct ? 0 : a.P); ++ph) {
-            if (a.P > 1) {
+        for (int ph = 0; ph < (direct ? 0 : nphase); ++ph) {
+            if (nphase > 1) {
                 __syncthreads();
-                fill_table<FS>(tab, a, q_lds, q, ph * a.Mp, a.Mp);
+                fill_table<FS>(tab, a, q_lds, q, ph * Mp, Mp);
                 __syncthreads();
             }
-            const bool last_ph = ph == a.P - 1;
-            for (int h0 = 0; h0 < a.Mp;) {
+            const bool last_ph = ph == nphase - 1;
+            for (int h0 = 0; h0 < Mp;) {
                 int h1;
                 int qnext = 0;
                 // Long codes: the first 8 subspaces are a small share of the sum and abandon
@@ -1246,8 +1251,8 @@ void search_kernel(const SearchArgs a) {
                 const bool bulk_first = kPieces > 0 && VEC == 4 && a.M >= 64;
                 if (slice_round && !bulk_first) {
                     // ---- round 0 ----
-                    h1 = H0 < a.Mp ? H0 : a.Mp;
-                    const bool fin = last_ph && h1 == a.Mp;
+                    h1 = H0 < Mp ? H0 : Mp;
+                    const bool fin = last_ph && h1 == Mp;
                     for (int base = wlo; base < whi; base += U * kWave) {
                         float bq[U];
                         uint32_t w[U][H0 / 4];
@@ -1285,13 +1290,13 @@ void search_kernel(const SearchArgs a) {
                     // all its loads together with the landmark distance: one memory latency per
                     // queue entry instead of one per piece.  Otherwise: 32 subspaces, piece by piece.
                     // (not in the lean instance, which meets later rounds only on fallback)
-                    const bool lead8 = kPieces > 0 && VEC == 4 && (h0 & 15) == 8 && h0 + 8 <= a.Mp;
+                    const bool lead8 = kPieces > 0 && VEC == 4 && (h0 & 15) == 8 && h0 + 8 <= Mp;
                     const int ja = h0 + (lead8 ? 8 : 0);
-                    int n16 = kPieces > 0 && VEC == 4 && (ja & 15) == 0 ? (a.Mp - ja) / 16 : 0;
+                    int n16 = kPieces > 0 && VEC == 4 && (ja & 15) == 0 ? (Mp - ja) / 16 : 0;
                     if (n16 > kPieces) n16 = kPieces;
                     const bool bulk = lead8 || n16 > 0;
-                    h1 = bulk ? ja + 16 * n16 : (h0 + 32 < a.Mp ? h0 + 32 : a.Mp);
-                    const bool fin = last_ph && h1 == a.Mp;
+                    h1 = bulk ? ja + 16 * n16 : (h0 + 32 < Mp ? h0 + 32 : Mp);
+                    const bool fin = last_ph && h1 == Mp;
                     // entries: the wave's queue, or (first round of phase 0) its whole slice
                     const int nent = slice_round ? (whi > wlo ? whi - wlo : 0) : qn;
                     for (int i0 = 0; i0 < nent; i0 += kWave) {
@@ -1302,7 +1307,7 @@ void search_kernel(const SearchArgs a) {
                             cl = slice_round ? wlo + i : qin[i];
                             const int pos = slice_round ? cur.pos(c0 + cl, segp, segd) : locate(c0 + cl);
                             const CodeRow cr = code_row<kTiledOk>(a, pos);
-                            const int jp = ph * a.Mp;  // first subspace of this phase
+                            const int jp = ph * Mp;  // first subspace of this phase
                             uint32_t w8[2] = {0, 0};
                             uint32_t w16[kPieces > 0 ? kPieces : 1][4];
                             if (bulk) {
