@@ -1054,9 +1054,16 @@ void search_kernel(const SearchArgs a) {
                         tally(kWorkCodeBytes, nv * (full ? (uint32_t)sizeof(HeadRecord) : H0 + 4u));
                         tally(kWorkLookups, nv * H0);   // (4-bit codes: one lookup per byte in the pair table)
                     }
-                    if (d_n > 0) drain_finish();
-                    while (count >= 2 * kWave) { drain_issue(); drain_finish(); }  // keep room
-                    if (count >= kWave) drain_issue();
+                    // finish the drain in flight; drain whole waves while two or more wait (keep
+                    // room), and leave the last one in flight behind the gathers below.  (One call
+                    // site each for issue and finish: the kernel's speed follows its code size.)
+#pragma clang loop unroll(disable)
+                    for (;;) {
+                        if (d_n > 0) drain_finish();
+                        if (count < kWave) break;
+                        drain_issue();
+                        if (count < kWave) break;
+                    }
                     float sums[U];
                     if constexpr (H0 == 8 && U % 2 == 0) {
 #pragma unroll
@@ -1071,9 +1078,12 @@ void search_kernel(const SearchArgs a) {
                     for (int u = 0; u < U; ++u) {
                         if (u == U / 2 && count >= 2 * kWave) {
                             // a ring holds 4 x 64 entries: make room half way through the block
-                            if (d_n > 0) drain_finish();
-                            drain_issue();
-                            drain_finish();
+                            // (finish what is in flight, drain one wave and finish it)
+#pragma clang loop unroll(disable)
+                            for (int r = 0; r < 2; ++r) {
+                                if (d_n > 0) drain_finish();
+                                if (r == 0) drain_issue();
+                            }
                         }
                         const float sum = sums[u];
                         const int cl = cb + u * kWave + lane;
@@ -1093,8 +1103,12 @@ void search_kernel(const SearchArgs a) {
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                     __builtin_amdgcn_wave_barrier();
                 }
-                if (d_n > 0) drain_finish();
-                while (count > 0) { drain_issue(); drain_finish(); }
+#pragma clang loop unroll(disable)
+                for (;;) {
+                    if (d_n > 0) drain_finish();
+                    if (count <= 0) break;
+                    drain_issue();
+                }
             }
             __syncthreads();
             // A first pass that abandons less than half of the candidates only adds work (its
