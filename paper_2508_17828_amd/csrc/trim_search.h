@@ -1,4 +1,4 @@
-// The fused filter-then-refine scan (Section 4.2) as one persistent workgroup per query
+// The fused filter-then-refine scan (Section 4.2) as one workgroup per query, resident for the whole scan of it
 // (kNN) or per (query, candidate chunk) (range).  Everything a query needs between
 // batches (distance table, query, result set R, threshold tau, survivor list) stays in
 // LDS; the only HBM traffic is the streamed codes + landmark distances, the raw rows of
