@@ -854,9 +854,9 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
     if (d % 4) return TRIM_UNSUPPORTED_SHAPE;
     int npow2 = 1;
     while (npow2 < nlist) npow2 <<= 1;
-    // queries per workgroup: 4, fewer if their key arrays do not fit half of the LDS
-    // (so that two workgroups share a CU)
-    int qt = 4;
+    // queries per workgroup: 8 (one per wave for the selection), fewer if their key arrays do not
+    // fit half of the LDS (so that two workgroups share a CU)
+    int qt = 8;
     while (qt > 1 && (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4) > kLdsBytes / 2) qt >>= 1;
     const size_t lds = (size_t)qt * ((size_t)npow2 * 8 + (size_t)d * 4);
     if (lds > kLdsBytes) return TRIM_UNSUPPORTED_SHAPE;
@@ -865,7 +865,7 @@ int trim_ivf_probe(const float *queries, int64_t nq, int32_t d, const float *cen
     if (nq > 0x7fffffff) return TRIM_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     void (*fn)(const float *, int64_t, int, const float *, int, int, int, int32_t *) =
-        qt == 4 ? ivf_probe_kernel<4> : qt == 2 ? ivf_probe_kernel<2> : ivf_probe_kernel<1>;
+        qt == 8 ? ivf_probe_kernel<8> : qt == 4 ? ivf_probe_kernel<4> : qt == 2 ? ivf_probe_kernel<2> : ivf_probe_kernel<1>;
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     // a launch holds fewer than 2^32 threads: walk the queries in slabs

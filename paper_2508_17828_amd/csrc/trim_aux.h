@@ -892,11 +892,11 @@ __global__ __launch_bounds__(512) void ivf_probe_kernel(const float *__restrict_
         if (in_regs && lane32 < ng) t = *reinterpret_cast<const float4 *>(q_lds + qi * d + 4 * lane32);
         qrx[qi] = t.x; qry[qi] = t.y; qrz[qi] = t.z; qrw[qi] = t.w;
     }
-    // A half wave takes kRows consecutive centroid rows per pass (their loads in flight together)
+    // A half wave takes kRows (8; 4 with 8 queries) consecutive centroid rows per pass (their loads in flight together)
     // against the QT queries: kRows x QT lane sums per lane, reduced together (reduce_pairs), after
     // which lane l of the half wave holds the distance of pair l >> kShift = row * QT + query and
     // the pairs' keys are stored side by side.
-    constexpr int kRows = 8, NP = kRows * QT;
+    constexpr int kRows = QT == 8 ? 4 : 8, NP = kRows * QT;
     constexpr int kShift = NP == 32 ? 0 : NP == 16 ? 1 : 2;
     for (int l0 = (tid >> 5) * kRows; l0 < nlist; l0 += nh * kRows) {
         // (rows past the end: the last row again, never stored)
