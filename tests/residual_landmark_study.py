@@ -10,10 +10,10 @@ exact distances per query, and the share of candidates whose partial landmark di
 first 8 subspaces alone already exceeds (Gamma(l,x) + sqrt(tau))^2 at the final threshold (what
 an early-abandoning scan can stop after 8 code bytes).
 
-Test infrastructure like the rest of this directory: it calls the oracle's index routines and
-the seeded input generators only, never the HIP path.
+A study, not a test (pytest does not collect it): it calls the oracle's index routines and the
+seeded input generators only, never the HIP path.
 
-    python oracle/residual_landmark_study.py [workload=C2] [n=100000] [queries=100]
+    python tests/residual_landmark_study.py [workload=C2] [n=100000] [queries=100]
 """
 import os
 import sys
