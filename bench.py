@@ -117,6 +117,42 @@ def _counter_rows(csv_path, needle):
     return [rows[k] for k in sorted(rows)]
 
 
+def _counter_table(csv_path, needle):
+    """{counter: [value per dispatch, in dispatch order]} for the kernels whose name contains `needle`."""
+    import csv
+    tab = {}
+    with open(csv_path, newline="") as f:
+        for r in csv.DictReader(f):
+            if needle in r["Kernel_Name"]:
+                d = tab.setdefault(r["Counter_Name"], {})
+                d[int(r["Dispatch_Id"])] = d.get(int(r["Dispatch_Id"]), 0.0) + float(r["Counter_Value"])
+    return {c: [d[k] for k in sorted(d)] for c, d in tab.items()}
+
+
+UNIT_COUNTERS = ("SQ_INSTS_VALU", "SQ_INSTS_LDS", "SQ_ACTIVE_INST_VALU", "SQ_LDS_IDX_ACTIVE", "GRBM_GUI_ACTIVE")
+
+
+def units_busy(table):
+    """How busy the vector ALUs and the LDS were during the search kernel's last three launches,
+    from one rocprofv3 --pmc run (UNIT_COUNTERS): a wave instruction occupies its SIMD's vector
+    ALU for 4 clocks (64 lanes on 16); SQ_LDS_IDX_ACTIVE counts a CU's LDS-busy clocks;
+    GRBM_GUI_ACTIVE is summed over the 8 XCDs.  256 CUs, 1024 SIMDs."""
+    try:
+        m = {c: sum(table[c][-3:]) / 3 for c in UNIT_COUNTERS}
+    except (KeyError, IndexError):
+        return None
+    cycles = m["GRBM_GUI_ACTIVE"] / 8.0
+    if cycles <= 0:
+        return None
+    return dict(valu=round(m["SQ_ACTIVE_INST_VALU"] * 4.0 / (1024.0 * cycles), 4),
+                lds=round(m["SQ_LDS_IDX_ACTIVE"] / (256.0 * cycles), 4),
+                valu_wave_instructions=int(m["SQ_INSTS_VALU"]), lds_wave_instructions=int(m["SQ_INSTS_LDS"]),
+                gpu_cycles=int(cycles),
+                method="rocprofv3 --pmc " + " ".join(UNIT_COUNTERS) + ", one more child run of this script (last 3 "
+                       "launches of the search kernel): valu = SQ_ACTIVE_INST_VALU x 4 / (1024 SIMDs x cycles), "
+                       "lds = SQ_LDS_IDX_ACTIVE / (256 CUs x cycles), cycles = GRBM_GUI_ACTIVE / 8 XCDs")
+
+
 def measure_traffic(args):
     """HBM traffic of the dominant kernel in the timed configuration: FETCH_SIZE and WRITE_SIZE (KiB
     per dispatch) of its last three launches in a child run of this script under rocprofv3 --pmc,
@@ -163,6 +199,18 @@ def measure_traffic(args):
                 got[(counter, what)] = (sum(vals[-3:]) / 3 if what == "kernel" else sum(sorted(vals)[-3:]) / 3)
     except (OSError, KeyError, ValueError):
         return None
+    units = None
+    try:        # how busy the units were: a run of its own, and no reason to lose the traffic if it fails
+        out = tempfile.mkdtemp(prefix="trim_pmc_", dir="/tmp")
+        cmd = ["timeout", "-s", "KILL", "600", prof, "--pmc", *UNIT_COUNTERS, "-d", out, "-o", "p",
+               "--output-format", "csv", "--", "python3", me] + child
+        r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+        files = glob.glob(os.path.join(out, "**", "p_counter_collection.csv"), recursive=True)
+        if r.returncode == 0 and files:
+            units = units_busy(_counter_table(files[0], "search_kernel"))
+        shutil.rmtree(out, ignore_errors=True)
+    except (OSError, KeyError, ValueError):
+        units = None
     gib_kib = float(1 << 20)
     sf = gib_kib / got[("FETCH_SIZE", "copy")] if got[("FETCH_SIZE", "copy")] > 0 else 0.0
     sw = gib_kib / got[("WRITE_SIZE", "copy")] if got[("WRITE_SIZE", "copy")] > 0 else 0.0
@@ -170,7 +218,7 @@ def measure_traffic(args):
     write_b = got[("WRITE_SIZE", "kernel")] * 1024 * sw
     return dict(bytes_per_launch=int(fetch_b + write_b), fetch_bytes=int(fetch_b), write_bytes=int(write_b),
                 FETCH_SIZE_KiB=round(got[("FETCH_SIZE", "kernel")], 1), WRITE_SIZE_KiB=round(got[("WRITE_SIZE", "kernel")], 1),
-                scale_fetch=round(sf, 4), scale_write=round(sw, 4),
+                scale_fetch=round(sf, 4), scale_write=round(sw, 4), units_busy=units,
                 method="rocprofv3 --pmc, one counter per child run of this script (last 3 launches of the "
                        "search kernel), scaled by the same counter on a 1 GiB read + 1 GiB write pass")
 
@@ -272,7 +320,9 @@ def roofline_object(w, nq, scan_ms, alg_bytes, wt, touched, ceil, kernel, fs=Fal
     else:
         head = dict(bound="lds", achieved=round(looks, 1), peak=LDS_PEAK_GLOOKUPS, unit="Glookup/s",
                     frac=round(looks / LDS_PEAK_GLOOKUPS, 4))
-    head.update(traffic=traffic["bytes_per_launch"] if traffic else None, traffic_detail=traffic, kernel=kernel, kernel_ms=round(scan_ms, 4), hbm=hbm, lds=lds, work=wt,
+    head.update(traffic=traffic["bytes_per_launch"] if traffic else None, traffic_detail=traffic,
+                units_busy=traffic.get("units_busy") if traffic else None,
+                kernel=kernel, kernel_ms=round(scan_ms, 4), hbm=hbm, lds=lds, work=wt,
                 candidates_per_s=dict(
                     counted=round((wt["first_pass"] + wt["skipped"]) / sec, 1),
                     read=round(wt["first_pass"] / sec, 1),
