@@ -77,13 +77,35 @@ def draw_ivf_long(seed):
     return w, k, batch, 0, gamma
 
 
-@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(22)] + [2000 + s for s in range(10)])
+def draw_mid_tables(seed):
+    """Tables of 40 to 56 KB (two 768-thread workgroups per CU) with short and long rows (both
+    kinds of the 80-register instance), long candidate sequences, small result sets."""
+    r = np.random.default_rng([4242, seed])
+    M = int(r.choice([40, 48, 56]))
+    dsub = int(r.choice([2, 4, 8, 16]))
+    if M * dsub % 4:
+        dsub = 4
+    n = int(r.integers(60_000, 160_000))
+    use_ivf = bool(r.integers(0, 2))
+    nlist = int(r.choice([24, 64, 150])) if use_ivf else 0
+    nprobe = int(r.integers(2, min(nlist, 40) + 1)) if use_ivf else 0
+    k = int(r.choice([1, 10, 33, 64]))
+    batch = int(r.choice([1, 16, 100, 512, 1024, 2048]))
+    gamma = float(r.choice([0.0, 0.3, 0.6]))
+    law = str(r.choice(["clip255", "aniso01", "unit"]))
+    w = synth.scaled(synth.WORKLOADS[LAWS[law]], n, 5, d=M * dsub, M=M, nlist=nlist, nprobe=nprobe, k=k,
+                     ncomp=int(r.choice([8, 32, 128])), seed=7000 + seed, kmeans_iters=2)
+    return w, k, batch, 0, gamma
+
+
+@pytest.mark.parametrize("seed", list(range(48)) + [1000 + s for s in range(22)] + [2000 + s for s in range(10)] +
+                         [3000 + s for s in range(10)])
 def test_random_configuration(oracle, seed):
     import torch
     from paper_2508_17828_amd import trim as T
     T.lib()
     w, k, batch, _, gamma = (draw(seed) if seed < 1000 else draw_long(seed - 1000) if seed < 2000
-                                 else draw_ivf_long(seed - 2000))
+                                 else draw_ivf_long(seed - 2000) if seed < 3000 else draw_mid_tables(seed - 3000))
     b = helpers.build(w, pq_train_max=4096, ivf_train_per_list=32)
     ix = b.index
     t = lambda a: None if a is None else torch.from_numpy(a).cuda()
